@@ -1,0 +1,78 @@
+"""Oracle: byte images of the stored KV ("we precompute and store all requests'
+KV in advance", Sec. 5.1 "Datasets").  Test infrastructure only.
+
+The storage tier holds one image per logical page of ``page_tokens`` tokens.
+An image is, for every layer, the layer's K block followed by its V block:
+
+    image[layer][0][kv_head][token_in_page][hd]      K, rotated, as cached
+    image[layer][1][kv_head][hd][token_in_page]      V, stored transposed
+
+in the cache's element type.  Token slots past the end of the prompt are zero.
+This is an interface format, restated here from its description; the oracle
+does no arithmetic on the values beyond the storage rounding already applied
+by ``transformer.round_storage``.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from .transformer import KVCache
+
+
+def _encode(x: np.ndarray, dtype: str) -> np.ndarray:
+    """fp64 values (already representable in ``dtype``) -> raw storage words."""
+    x32 = np.ascontiguousarray(x, dtype=np.float32)
+    if dtype == "f32":
+        return x32.view(np.uint32)
+    if dtype == "bf16":
+        return (x32.view(np.uint32) >> np.uint32(16)).astype(np.uint16)
+    raise ValueError(dtype)
+
+
+def decode_words(words: np.ndarray, dtype: str) -> np.ndarray:
+    """Raw storage words -> float64 values (a reinterpretation, no rounding)."""
+    if dtype == "f32":
+        return words.view(np.float32).astype(np.float64)
+    if dtype == "bf16":
+        return (words.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    raise ValueError(dtype)
+
+
+def page_image_words(n_layers: int, n_kv: int, hd: int, page_tokens: int) -> int:
+    return n_layers * 2 * n_kv * page_tokens * hd
+
+
+def pack_store(cache: KVCache, page_tokens: int, dtype: str) -> np.ndarray:
+    """[n_logical_pages, L, 2, n_kv * page_tokens * hd] storage words."""
+    L, T, n_kv, hd = cache.k.shape
+    n_pages = (T + page_tokens - 1) // page_tokens
+    wdt = np.uint32 if dtype == "f32" else np.uint16
+    out = np.zeros((n_pages, L, 2, n_kv * page_tokens * hd), dtype=wdt)
+    for p in range(n_pages):
+        t0, t1 = p * page_tokens, min((p + 1) * page_tokens, T)
+        n = t1 - t0
+        for l in range(L):
+            kblk = np.zeros((n_kv, page_tokens, hd), dtype=np.float64)
+            vblk = np.zeros((n_kv, hd, page_tokens), dtype=np.float64)
+            kblk[:, :n, :] = np.transpose(cache.k[l, t0:t1], (1, 0, 2))   # [kv, tok, hd]
+            vblk[:, :, :n] = np.transpose(cache.v[l, t0:t1], (1, 2, 0))   # [kv, hd, tok]
+            out[p, l, 0] = _encode(kblk, dtype).reshape(-1)
+            out[p, l, 1] = _encode(vblk, dtype).reshape(-1)
+    return out
+
+
+def unpack_store(images: np.ndarray, n_tokens: int, n_kv: int, hd: int,
+                 page_tokens: int, dtype: str) -> KVCache:
+    """Inverse of ``pack_store``."""
+    n_pages, L = images.shape[0], images.shape[1]
+    cache = KVCache(L, n_tokens, n_kv, hd)
+    for p in range(n_pages):
+        t0, t1 = p * page_tokens, min((p + 1) * page_tokens, n_tokens)
+        n = t1 - t0
+        for l in range(L):
+            kblk = decode_words(images[p, l, 0], dtype).reshape(n_kv, page_tokens, hd)
+            vblk = decode_words(images[p, l, 1], dtype).reshape(n_kv, hd, page_tokens)
+            cache.k[l, t0:t1] = np.transpose(kblk[:, :n, :], (1, 0, 2))
+            cache.v[l, t0:t1] = np.transpose(vblk[:, :, :n], (2, 0, 1))
+    cache.filled = n_tokens
+    return cache

@@ -1,0 +1,181 @@
+"""Pins for oracle/meet_point.py: hand-worked splits, the closed form for affine compute
+cost, the paper's Table 3 cells, Alg. 1's known failure mode, protocol invariants."""
+import math
+import random
+
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from oracle import meet_point as mp
+
+
+def test_hand_worked_splits():
+    # c = (3,3,3), l = (2,2,2): TTFT(0..3) = 6, max(3,4)=4, max(6,2)=6, 9
+    assert [mp.ttft_of_split([3, 3, 3], [2, 2, 2], m) for m in range(4)] == [6, 4, 6, 9]
+    assert mp.brute_force_meet_point([3, 3, 3], [2, 2, 2]) == (1, 4)
+    assert mp.brute_force_meet_point([2, 2], [2, 2]) == (1, 2)
+    assert mp.brute_force_meet_point([4], [4]) == (0, 4)                # tie -> smallest m
+    assert mp.brute_force_meet_point([1, 1], [5, 5]) == (2, 2)          # compute-only wins
+    assert mp.brute_force_meet_point([1, 1], [5, 5], o_c=10) == (0, 10) # a busy compute side
+    assert mp.brute_force_meet_point([5, 5], [1, 1], o_l=3) == (0, 5)
+    assert mp.brute_force_meet_point([], []) == (0, 0)
+    # the order of the load costs matters: the loader takes the *last* chunks
+    assert mp.ttft_of_split([1, 1, 1], [10, 1, 1], 1) == 2
+    assert mp.ttft_of_split([1, 1, 1], [1, 1, 10], 1) == 11
+
+
+def test_never_worse_than_either_baseline_and_brackets_crossing():
+    for seed in range(200):
+        n = 1 + seed % 12
+        c, l = si.make_costs(n, seed)
+        c, l = [int(x) for x in c], [int(x) for x in l]
+        m, t = mp.brute_force_meet_point(c, l)
+        assert t <= min(sum(c), sum(l))                    # the two extremes (Sec. 5.1 baselines)
+        assert t == mp.ttft_of_split(c, l, m)
+        # A(m) rises, B(m) falls: the optimum sits at the crossing
+        A = [sum(c[:k]) for k in range(n + 1)]
+        B = [sum(l[k:]) for k in range(n + 1)]
+        cross = next(k for k in range(n + 1) if A[k] >= B[k])
+        assert m in (cross - 1, cross)
+        assert t >= max(sum(c) * sum(l) // (sum(c) + sum(l)) // max(1, n), 0)
+
+
+def test_closed_form_affine_compute_flat_load():
+    """c_i = alpha + beta*i, l = lam.  Setting alpha*m + beta*m(m-1)/2 = lam*(N-m) gives
+    m^ = [-(a+lam-b/2) + sqrt((a+lam-b/2)^2 + 2*b*lam*N)] / b; the integer optimum is one of
+    its neighbours (Sec. 4 Part 2: compute cost rises with position, I/O cost is flat)."""
+    rng = random.Random(4)
+    for _ in range(300):
+        N = rng.randint(2, 80)
+        alpha, beta, lam = rng.randint(1, 5000), rng.randint(1, 400), rng.randint(1, 8000)
+        c = [alpha + beta * i for i in range(N)]
+        l = [lam] * N
+        m, t = mp.brute_force_meet_point(c, l)
+        p = alpha + lam - beta / 2
+        mhat = (-p + math.sqrt(p * p + 2 * beta * lam * N)) / beta
+        assert math.floor(mhat) <= m <= math.ceil(mhat) or abs(m - mhat) < 1e-9
+        # convex compute cost: TTFT/T_c + TTFT/T_l <= 1 + one chunk of discretisation
+        s = t / sum(c) + t / sum(l)
+        assert s <= 1 + max(max(c) / sum(c), lam / sum(l)) + 1e-12
+    # flat compute cost: m^ = lam N / (alpha + lam)
+    m, _ = mp.brute_force_meet_point([30] * 40, [10] * 40)
+    assert m == 10
+
+
+def test_paper_table3_cells_follow_the_split_model(golden):
+    """A cell a\\b fixes T_c/T_l = b/a.  With that ratio and 32 chunks (16K / 512) the best
+    split of the TTFT model reproduces the paper's two speedups within 8 %."""
+    rows = golden("table3_speedups.txt")
+    assert len(rows) == 55
+    for hw, util, gbps, a, b in rows:
+        a, b = float(a), float(b)
+        c = [int(round(b / a * 10000))] * 32
+        l = [10000] * 32
+        _, t = mp.brute_force_meet_point(c, l)
+        assert abs(sum(l) / t / a - 1) < 0.08, (hw, util, gbps)
+        assert abs(sum(c) / t / b - 1) < 0.08, (hw, util, gbps)
+
+
+def test_literal_race_matches_alg1_behaviour():
+    # balanced: 4 chunks, both sides one unit per chunk -> each takes two, done at t = 2
+    assert mp.literal_race([1] * 4, [1] * 4) == (2, 2, 2)
+    # the failure mode behind the paper's sub-1.0 cells (Sec. 5.3/5.4): a fast compute side
+    # still waits for the slow fetch in flight, and duplicates the last chunk
+    t, nc, nl = mp.literal_race([1] * 4, [100] * 4)
+    assert (t, nc, nl) == (100, 4, 1)
+    assert t > min(4, 400)
+    assert mp.brute_force_meet_point([1] * 4, [100] * 4) == (4, 4)
+    # the planner's split is never slower than the printed race
+    for seed in range(200):
+        n = 1 + seed % 10
+        c, l = si.make_costs(n, seed + 1000)
+        t_lit, nc, nl = mp.literal_race(c, l)
+        assert nc + nl >= n
+        assert mp.brute_force_meet_point(list(c), list(l))[1] <= t_lit
+
+
+def _exact_setup(c, l):
+    """Estimates equal the actual durations: 1 flop costs 1 ns, 1 byte costs 1 ns."""
+    est = mp.Estimator(1, 1, 1, 1)
+    return dict(n_chunks=len(c), chunk_flops=list(c), chunk_bytes=list(l),
+                actual_compute_ns=list(c), actual_load_ns=list(l), est=est)
+
+
+def test_claim_protocol_with_exact_estimates_reaches_the_optimum():
+    for seed in range(300):
+        n = 1 + seed % 14
+        c, l = si.make_costs(n, seed + 5000)
+        c, l = [int(x) for x in c], [int(x) for x in l]
+        t, src, log = mp.simulate_claims(**_exact_setup(c, l))
+        m = src.count(mp.COMPUTE)
+        assert src == [mp.COMPUTE] * m + [mp.LOAD] * (n - m)          # prefix / suffix, no gaps
+        assert t == mp.brute_force_meet_point(c, l)[1]
+        for d in log:
+            assert d.f <= d.m_star <= d.b + 1
+
+
+def test_claim_protocol_modes_and_failure():
+    c, l = [5, 6, 7, 8, 9, 10], [7] * 6
+    t, src, _ = mp.simulate_claims(**_exact_setup(c, l), mode=mp.MODE_COMPUTE_ONLY)
+    assert (t, src) == (45, [mp.COMPUTE] * 6)
+    t, src, _ = mp.simulate_claims(**_exact_setup(c, l), mode=mp.MODE_LOAD_ONLY)
+    assert (t, src) == (42, [mp.LOAD] * 6)
+    for m in range(7):
+        t, src, _ = mp.simulate_claims(**_exact_setup(c, l), mode=mp.MODE_FORCED, forced_m=m)
+        assert src.count(mp.COMPUTE) == m and t == mp.ttft_of_split(c, l, m)
+    t_b, src_b, _ = mp.simulate_claims(**_exact_setup(c, l))
+    assert t_b == mp.brute_force_meet_point(c, l)[1] == 21 and src_b.count(mp.COMPUTE) == 3
+    t_g, src_g, _ = mp.simulate_claims(**_exact_setup(c, l), mode=mp.MODE_GREEDY)
+    assert t_g >= t_b and sorted(set(src_g)) == [0, 1]
+    # the load of chunk 4 fails: it returns to the range, the loader retires, compute finishes
+    t_f, src_f, _ = mp.simulate_claims(**_exact_setup(c, l), fail_load_chunk=4)
+    assert src_f == [mp.COMPUTE] * 5 + [mp.LOAD]
+    assert t_f == sum(c[:5])
+
+
+def test_claim_protocol_adapts_to_a_bandwidth_step():
+    """Sec. 4 Part 3 / Sec. 5.6: when the I/O rate drops mid-run the merge point moves
+    towards the load side's end (more chunks computed)."""
+    n = 32
+    flops = [100 + 4 * i for i in range(n)]
+    byts = [100] * n
+    fast = [100] * n                                  # 1 ns per byte
+    slow = list(fast)
+    for j in range(n - 9, -1, -1):                    # after the loader's 8th chunk: 12x slower
+        slow[j] = 1200
+    est = lambda: mp.Estimator(1, 1, 1, 1)
+    t0, s0, _ = mp.simulate_claims(n, flops, byts, flops, fast, est())
+    t1, s1, log = mp.simulate_claims(n, flops, byts, flops, slow, est())
+    assert s1.count(mp.COMPUTE) > s0.count(mp.COMPUTE)
+    assert t1 > t0
+    stars = [d.m_star for d in log if d.who == mp.COMPUTE]
+    assert stars[-1] > stars[0]                       # the planned meet point moved right
+    # and no schedule fixed in advance at the old plan would have been better than the old optimum
+    assert t1 <= mp.ttft_of_split(flops, slow, s0.count(mp.COMPUTE)) 
+
+
+def test_estimator_integer_rules():
+    e = mp.Estimator(prior_compute_ns=1000, prior_compute_flops=10**6, prior_load_ns=10**9,
+                     prior_load_bytes=4 * 10**9)
+    assert e.est_compute(3 * 10**6 + 999) == 3000            # floor
+    assert e.est_load(2**20) == 2**20 * 10**9 // (4 * 10**9)
+    for k in range(6):
+        e.add_compute(100 + k, 1000)
+    assert e.compute_state() == (102 + 103 + 104 + 105, 4000)  # last four
+    e.add_load(50, 10); e.add_load(70, 10)
+    assert e.load_state() == (70, 10)
+    # 128-bit range: 3.4e14 flops * 1e10 ns does not overflow in the oracle
+    e2 = mp.Estimator(10**10, 3 * 10**14, 1, 1)
+    assert e2.est_compute(34 * 10**13) == 34 * 10**13 * 10**10 // (3 * 10**14)
+
+
+def test_range_flops_matches_chunk_formula():
+    from oracle import transformer as otf
+    s = si.LLAMA3_8B
+    for i in (0, 3, 31):
+        assert mp.range_flops(s.n_layers, s.d_model, s.n_q, s.n_kv, s.head_dim, s.ffn,
+                              i * 1024, (i + 1) * 1024) == otf.chunk_flops(s, i, 1024)
+    # additivity over a ragged split is exact
+    a = mp.range_flops(2, 8, 2, 1, 4, 12, 0, 7) + mp.range_flops(2, 8, 2, 1, 4, 12, 7, 10)
+    assert a == mp.range_flops(2, 8, 2, 1, 4, 12, 0, 10)
