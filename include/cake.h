@@ -1,0 +1,294 @@
+/*
+ * cake.h -- C ABI of the bidirectional KV-cache producer for one long prompt.
+ *
+ * Method: "Compute Or Load KV Cache? Why not Both?" (the Cake paper).  The KV
+ * cache of a prompt whose KV is already held by a slow storage tier is
+ * produced from both ends at once (Sec. 4 Part 2; App. A; Alg. 1): the GPU
+ * prefills chunks front-to-back, each chunk attending to all earlier KV
+ * (Sec. 3 "Chunk Prefill"), while stored chunks are fetched back-to-front at
+ * the tier's bandwidth (Sec. 5.1 "I/O Bandwidth Control"), until the two
+ * sweeps meet.  Where they meet is planned from measured per-chunk costs:
+ * compute cost grows with position, load cost is flat (Sec. 4 Part 2
+ * "Insight").
+ *
+ * Conventions
+ *  - Every call returns 0 (CAKE_OK) or a negative cake_status.  Nothing is
+ *    thrown across this boundary.  cake_last_error() gives the text of the
+ *    last failure on a context (owned by the context, valid until the next
+ *    failing call on it).
+ *  - "host" / "device" / "pinned host" is stated for every pointer.  The
+ *    caller owns weights, token ids, the KV pool, the block tables, the store
+ *    and both streams; the library borrows them (cake_create: until
+ *    cake_destroy; other calls: until the call returns, or for async calls
+ *    until the stream work they queued has finished).  The library owns only
+ *    what sits inside cake_ctx (activation workspace, events, a device copy of
+ *    the token ids).  No call allocates memory the caller must free.
+ *  - Streams are hipStream_t passed as void*.  All device pointers belong to
+ *    the device that was current when cake_create ran.
+ *  - 1 GB/s = 1e9 bytes per second.  Times are integer nanoseconds.
+ *
+ * Matrix layout.  Every projection matrix is stored [out_features][in_features]
+ * row-major (the transpose of the paper's W in Q = X W_Q), in the model's
+ * element type.  Norm gains are float32 [d_model].
+ *
+ * KV layout.  Tokens are grouped into logical pages of page_tokens tokens
+ * (a multiple of 64).  block_table[logical_page] names the physical page.
+ * Device pool, element type = model dtype:
+ *     pool[layer][physical_page][0][kv_head][token_in_page][head_dim]   K (rotated)
+ *     pool[layer][physical_page][1][kv_head][head_dim][token_in_page]   V (transposed)
+ * The storage tier holds one image per logical page,
+ *     image[layer][0|1][...as above...],   at base + logical_page * page_stride_bytes,
+ * so loading a page is n_layers contiguous copies and the bytes land exactly
+ * as stored.
+ */
+#ifndef CAKE_H
+#define CAKE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct cake_ctx cake_ctx;
+
+typedef enum {
+    CAKE_OK = 0,
+    CAKE_E_INVAL = -1,      /* bad argument; nothing was enqueued */
+    CAKE_E_NOMEM = -2,      /* workspace allocation failed (cake_create only) */
+    CAKE_E_HIP = -3,        /* a HIP runtime call failed */
+    CAKE_E_STORE_MISS = -4, /* the store does not hold the requested page */
+    CAKE_E_STATE = -5,      /* call order violated (e.g. earlier KV not resident) */
+    CAKE_E_CAPACITY = -6    /* a caller-provided log array was too small (result still valid) */
+} cake_status;
+
+typedef enum { CAKE_F32 = 0, CAKE_BF16 = 1 } cake_dtype;
+
+typedef enum {
+    CAKE_BIDIR = 0,        /* planned race from both ends (the method) */
+    CAKE_COMPUTE_ONLY = 1, /* baseline: prefill every chunk (Sec. 5.1 "Baselines") */
+    CAKE_LOAD_ONLY = 2,    /* baseline: load every chunk */
+    CAKE_FORCED_SPLIT = 3, /* chunks [0,forced_m) computed, [forced_m,N) loaded */
+    CAKE_GREEDY = 4        /* Alg. 1 without a plan: both sides claim whenever free */
+} cake_mode;
+
+typedef enum { CAKE_SRC_NONE = -1, CAKE_SRC_COMPUTE = 0, CAKE_SRC_LOAD = 1 } cake_source;
+
+typedef enum {
+    CAKE_CHUNK_EMPTY = 0, CAKE_CHUNK_COMPUTING = 1, CAKE_CHUNK_LOADING = 2, CAKE_CHUNK_RESIDENT = 3
+} cake_chunk_status;
+
+/* Llama-style decoder shape (pre-RMSNorm, rotary q/k with adjacent-pair rotation,
+ * grouped-query attention, SwiGLU, no biases).  head_dim must be 64 or 128. */
+typedef struct {
+    int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, ffn_dim, vocab;
+    int32_t dtype;          /* cake_dtype: element type of weights, activations fed to GEMMs, and KV */
+    float rms_eps;
+    float rope_theta;
+} cake_model_desc;
+
+typedef struct {
+    const float* attn_norm; /* device, [d_model] */
+    const void* wqkv;       /* device, [(n_q+2*n_kv)*head_dim][d_model]: W_Q rows, then W_K, then W_V */
+    const void* wo;         /* device, [d_model][n_q*head_dim] */
+    const float* ffn_norm;  /* device, [d_model] */
+    const void* w_gate;     /* device, [ffn_dim][d_model] */
+    const void* w_up;       /* device, [ffn_dim][d_model] */
+    const void* w_down;     /* device, [d_model][ffn_dim] */
+} cake_layer_weights;
+
+typedef struct {
+    const void* embed;                /* device, [vocab][d_model] */
+    const cake_layer_weights* layers; /* host array of n_layers structs (copied by cake_create) */
+} cake_weights;
+
+typedef struct {
+    void* pool;                      /* device, layout above */
+    const int32_t* block_table_host; /* host,   [n_logical_pages] */
+    const int32_t* block_table_dev;  /* device, same contents */
+    int32_t page_tokens;             /* multiple of 64 */
+    int32_t n_physical_pages;        /* pages per layer in the pool */
+    int32_t n_logical_pages;
+} cake_kv;
+
+typedef struct {
+    const void* base;           /* pinned host */
+    uint64_t page_stride_bytes; /* >= n_layers*2*n_kv*page_tokens*head_dim*elem */
+    int32_t page_tokens;        /* must equal cake_kv.page_tokens */
+    int32_t n_pages;            /* logical pages held */
+} cake_kv_store;
+
+/* One record per chunk, indexed by chunk number. */
+typedef struct {
+    int32_t source;     /* cake_source */
+    int32_t tok_begin, tok_count;
+    uint64_t start_ns, end_ns; /* since the call started; end = KV of the chunk resident */
+    uint64_t work;             /* compute: algorithmic FLOPs of the chunk; load: bytes */
+    uint64_t device_ns;        /* compute: HIP-event time of the chunk's kernels; load: 0 */
+} cake_chunk_log;
+
+/* One record per look at the unclaimed range [f,b] by a free worker.  The
+ * estimates the planner used are reproducible from these integers:
+ *   compute estimate of chunk i = floor(flops_i * est_compute_ns / est_compute_flops)
+ *   load estimate of chunk j    = floor(bytes_j * est_load_ns    / est_load_bytes)   */
+typedef struct {
+    int32_t who;     /* cake_source of the worker */
+    int32_t f, b;    /* unclaimed chunks before the decision */
+    int32_t m_star;  /* planned meet point (absolute chunk index) */
+    int32_t claimed; /* chunk claimed, or -1 (wait) */
+    int32_t pad_;
+    uint64_t now_ns;
+    uint64_t o_c, o_l;                            /* predicted remaining ns of the chunk in flight on each side */
+    uint64_t est_compute_ns, est_compute_flops;   /* throughput sample: last <= 4 computed chunks, or the prior */
+    uint64_t est_load_ns, est_load_bytes;         /* last loaded chunk, or the prior */
+} cake_decision_log;
+
+typedef struct {
+    /* in: capacities of the two caller-provided arrays (may be 0 / NULL) */
+    cake_chunk_log* chunks;
+    int32_t chunks_cap;
+    cake_decision_log* decisions;
+    int32_t decisions_cap;
+    /* out */
+    int32_t n_chunks;
+    int32_t n_decisions;       /* number recorded (<= cap) */
+    int32_t meet_point;        /* chunks [0,meet_point) were computed, the rest loaded */
+    int32_t load_failed_chunk; /* -1, or the chunk whose load failed and was recomputed */
+    uint64_t ttft_ns;          /* entry -> every chunk's KV resident */
+    uint64_t compute_busy_ns;  /* sum of computed chunks' wall times */
+    uint64_t compute_device_ns;/* sum of computed chunks' HIP-event times */
+    uint64_t compute_flops;    /* algorithmic FLOPs of the computed chunks */
+    uint64_t load_busy_ns;
+    uint64_t load_bytes;
+} cake_result;
+
+/* Priors used before the first measurement, and pacing granularity. 0 = default. */
+typedef struct {
+    uint64_t prior_compute_ns, prior_compute_flops; /* default 1e9 ns per 5e14 FLOP */
+    uint64_t piece_bytes;                           /* largest single DMA; default 4 MiB */
+    int32_t kernel_path; /* 0: MFMA kernels where the shape allows (bf16); 1: generic kernels only */
+    int32_t pad_;
+} cake_tuning;
+
+/* ---- life cycle ------------------------------------------------------- */
+
+/* Creates a context on the current device: copies the layer table, allocates the
+ * activation workspace for chunks of up to max_chunk tokens and a device buffer for
+ * max_tokens token ids.  compute_stream / copy_stream: hipStream_t, default priority.
+ * Errors: CAKE_E_INVAL (shape not supported), CAKE_E_NOMEM, CAKE_E_HIP. */
+int32_t cake_create(cake_ctx** out, const cake_model_desc* model, const cake_weights* weights,
+                    int32_t max_tokens, int32_t max_chunk, void* compute_stream, void* copy_stream);
+int32_t cake_destroy(cake_ctx* ctx);
+const char* cake_last_error(const cake_ctx* ctx);
+int32_t cake_set_tuning(cake_ctx* ctx, const cake_tuning* t);
+
+/* ---- the four calls of the method ------------------------------------- */
+
+/* Sec. 3 "Chunk Prefill"; App. A step 4.  Enqueues, on the compute stream, the prefill of
+ * tokens [tok_begin, tok_begin+tok_count) through every layer: their K/V are written into
+ * kv's pages and they attend to the pages of [0, tok_begin+tok_count).  Asynchronous.
+ * token_ids: host, the whole prompt (indexed absolutely).  tok_count <= max_chunk.
+ * The KV of [0,tok_begin) must be resident before the stream reaches this work; the
+ * library cannot check data it did not produce, the caller orders it.
+ * Errors: CAKE_E_INVAL (range outside the block table / max_chunk), CAKE_E_HIP. */
+int32_t cake_prefill_chunk(cake_ctx* ctx, const int32_t* token_ids, int32_t tok_begin,
+                           int32_t tok_count, const cake_kv* kv);
+
+/* Sec. 5.1 "I/O Bandwidth Control"; App. A step 5.  Copies the stored images of the logical
+ * pages covering [tok_begin, tok_begin+tok_count) into their physical pages on the copy
+ * stream, in pieces, releasing a piece only once the tier would have delivered it at `gbps`
+ * (cumulative bytes issued <= gbps * elapsed).  Blocks the calling thread while pacing and
+ * returns when the last piece is enqueued; the chunk is resident once the copy stream has
+ * drained (cake_sync_load or an event of the caller's).  tok_begin must be page aligned.
+ * gbps <= 0 means unthrottled.  Errors: CAKE_E_INVAL, CAKE_E_STORE_MISS, CAKE_E_HIP. */
+int32_t cake_load_chunk(cake_ctx* ctx, const cake_kv_store* store, int32_t tok_begin,
+                        int32_t tok_count, const cake_kv* kv, double gbps);
+
+/* Sec. 4 Part 3 ("always ensuring minimal latency").  Pure host function, no context.
+ * Chunks [0,m) computed front-to-back, [m,n) loaded back-to-front:
+ *   TTFT(m) = max(compute_offset_ns + sum_{i<m} compute_ns[i],
+ *                 load_offset_ns    + sum_{j>=m} load_ns[j]),   m in 0..n.
+ * Returns the smallest m minimising TTFT(m) and that TTFT.  O(n).
+ * Errors: CAKE_E_INVAL (n < 0, NULL with n > 0, an offset above 2^62, or a running sum the
+ * scan needs exceeding 2^63). */
+int32_t cake_plan_meet_point(const uint64_t* compute_ns, const uint64_t* load_ns, int32_t n,
+                             uint64_t compute_offset_ns, uint64_t load_offset_ns,
+                             int32_t* m_out, uint64_t* ttft_ns_out);
+
+/* App. A; Alg. 1.  Produces the KV of the whole prompt.  Blocking.  Splits n_tokens into
+ * chunks of `chunk` tokens (a multiple of page_tokens; the last may be short), then runs a
+ * compute worker (caller's thread, compute stream) from chunk 0 upward and a load worker
+ * (own thread, copy stream) from the last chunk downward; each claims its end of the
+ * unclaimed range under a lock after re-planning the meet point from measured costs, so no
+ * chunk is produced twice.  Returns when both have drained; ttft_ns covers entry to that
+ * point.  A failed load returns its chunk to the range, retires the loader and is reported
+ * in load_failed_chunk (the call still succeeds if compute can finish the range).
+ * Errors: CAKE_E_INVAL, CAKE_E_STORE_MISS (load-only mode and the store lacks a page),
+ * CAKE_E_HIP, CAKE_E_CAPACITY (logs truncated; KV and scalars valid). */
+int32_t cake_bidirectional_prefill(cake_ctx* ctx, const int32_t* token_ids, int32_t n_tokens,
+                                   const cake_kv_store* store, int32_t chunk, double gbps,
+                                   int32_t mode, int32_t forced_m, const cake_kv* kv,
+                                   cake_result* res);
+
+/* ---- small helpers ---------------------------------------------------- */
+
+/* Bandwidth of the simulated tier; thread-safe; takes effect at the next paced piece
+ * (Sec. 5.6: the I/O rate fluctuates while a request is in flight).  gbps must be > 0. */
+int32_t cake_set_bandwidth(cake_ctx* ctx, double gbps);
+/* Schedules cake_set_bandwidth(gbps) to happen by itself when the load worker of the next
+ * cake_bidirectional_prefill has completed `after_loaded_chunks` chunks (a count trigger, so
+ * runs are repeatable).  after_loaded_chunks < 0 clears it. */
+int32_t cake_schedule_bandwidth_step(cake_ctx* ctx, int32_t after_loaded_chunks, double gbps);
+/* The paper's is_resident (App. B.2 step 4): cake_chunk_status of a chunk of the running or
+ * last cake_bidirectional_prefill; negative cake_status on a bad index. */
+int32_t cake_chunk_state(const cake_ctx* ctx, int32_t chunk);
+/* Blocks until the compute / copy stream has drained. */
+int32_t cake_sync_compute(cake_ctx* ctx);
+int32_t cake_sync_load(cake_ctx* ctx);
+
+/* Algorithmic FLOPs of prefilling tokens [tok_begin, tok_begin+tok_count): projections
+ * 2*P_lin*n plus causal attention n_layers*4*n_q*head_dim*(tok_begin*n + n(n+1)/2). */
+uint64_t cake_range_flops(const cake_model_desc* model, int32_t tok_begin, int32_t tok_count);
+/* Bytes of one page image (all layers, K and V). */
+uint64_t cake_page_image_bytes(const cake_model_desc* model, int32_t page_tokens);
+
+/* Virtual-time run of the claim protocol (the same decision code the threaded executor
+ * uses), for host-side testing: chunk i costs actual_compute_ns[i] if computed and
+ * actual_load_ns[i] if loaded; estimates follow the rules documented at
+ * cake_decision_log with the given priors.  fail_load_chunk >= 0 makes that load fail.
+ * sources_out[n]: cake_source per chunk.  decisions may be NULL.  No GPU involved. */
+int32_t cake_simulate_race(int32_t n_chunks, const uint64_t* chunk_flops,
+                           const uint64_t* chunk_bytes, const uint64_t* actual_compute_ns,
+                           const uint64_t* actual_load_ns, uint64_t prior_compute_ns,
+                           uint64_t prior_compute_flops, uint64_t prior_load_ns,
+                           uint64_t prior_load_bytes, int32_t mode, int32_t forced_m,
+                           int32_t fail_load_chunk, int32_t* sources_out, uint64_t* ttft_ns_out,
+                           cake_decision_log* decisions, int32_t decisions_cap,
+                           int32_t* n_decisions_out);
+
+/* Single kernels, exposed for parity tests and profiling.  All asynchronous on the compute
+ * stream; all pointers device; element type = the context's dtype unless stated. */
+int32_t cake_op_rmsnorm(cake_ctx* ctx, const float* x, const float* gain, void* out,
+                        int32_t rows, int32_t cols);
+/* out[M][N] (float32) = a[M][K] * w[N][K]^T */
+int32_t cake_op_gemm(cake_ctx* ctx, const void* a, const void* w, float* out,
+                     int32_t M, int32_t N, int32_t K);
+/* x[M][N] (float32) += a[M][K] * w[N][K]^T */
+int32_t cake_op_gemm_residual(cake_ctx* ctx, const void* a, const void* w, float* x,
+                              int32_t M, int32_t N, int32_t K);
+/* out[M][N] = silu(a*wg^T) .* (a*wu^T), element type out */
+int32_t cake_op_gemm_swiglu(cake_ctx* ctx, const void* a, const void* wg, const void* wu,
+                            void* out, int32_t M, int32_t N, int32_t K);
+/* q[n_q][rows][hd] from qkv[rows][(n_q+2n_kv)*hd] (float32) rotated at positions
+ * tok_begin+row; K (rotated) and V written into layer `layer` of kv's pages. */
+int32_t cake_op_rope_kv_write(cake_ctx* ctx, const float* qkv, void* q, int32_t layer,
+                              int32_t tok_begin, int32_t rows, const cake_kv* kv);
+/* out[rows][n_q*hd] = causal attention of q[n_q][rows][hd] (positions tok_begin+row)
+ * against layer `layer` of kv's pages, keys 0 .. tok_begin+rows-1. */
+int32_t cake_op_attention(cake_ctx* ctx, const void* q, void* out, int32_t layer,
+                          int32_t tok_begin, int32_t rows, const cake_kv* kv);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CAKE_H */

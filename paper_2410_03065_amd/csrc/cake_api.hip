@@ -1,0 +1,476 @@
+// C ABI: context, chunk prefill, throttled chunk load, bidirectional prefill.
+// See include/cake.h for the contract of every entry point.
+#include <hip/hip_runtime.h>
+
+#include <atomic>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <memory>
+#include <mutex>
+#include <string>
+#include <thread>
+#include <vector>
+
+#include "executor.hpp"
+#include "kernels.hpp"
+
+using namespace cake;
+
+struct cake_ctx {
+    cake_model_desc m{};
+    std::vector<cake_layer_weights> layers;
+    const void* embed = nullptr;
+    int device = 0;
+    int max_tokens = 0, max_chunk = 0;
+    hipStream_t cs = nullptr, ls = nullptr;
+    // activation workspace (device)
+    float* x = nullptr;       // [max_chunk][d]            residual stream, float32
+    void* h = nullptr;        // [max_chunk][d]            normed activations, model dtype
+    float* qkv = nullptr;     // [max_chunk][(n_q+2n_kv)hd] float32
+    void* q = nullptr;        // [n_q][rows][hd]           rotated queries, model dtype
+    void* ao = nullptr;       // [max_chunk][n_q*hd]       attention output, model dtype
+    void* act = nullptr;      // [max_chunk][ffn]          SwiGLU output, model dtype
+    float* rope_cs = nullptr; // [max_chunk][hd/2][2]
+    int32_t* d_ids = nullptr; // [max_tokens]
+    hipEvent_t ev_a = nullptr, ev_b = nullptr;
+    std::atomic<double> gbps{0.0};
+    int step_after = -1;
+    double step_gbps = 0.0;
+    cake_tuning tun{1000000000ull, 500000000000000ull, 4ull << 20, 0, 0};
+    std::mutex err_mu;
+    std::string err;
+    std::unique_ptr<std::atomic<int32_t>[]> status;
+    int n_status = 0;
+};
+
+static int fail(cake_ctx* ctx, int code, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (ctx) {
+        std::lock_guard<std::mutex> g(ctx->err_mu);
+        ctx->err = buf;
+    }
+    return code;
+}
+
+#define HIP_TRY(ctx, expr)                                                                      \
+    do {                                                                                        \
+        hipError_t e_ = (expr);                                                                 \
+        if (e_ != hipSuccess) return fail(ctx, CAKE_E_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+static size_t esize(const cake_ctx* c) { return c->m.dtype == CAKE_F32 ? 4 : 2; }
+
+static int check_kv(cake_ctx* ctx, const cake_kv* kv, int tok_end) {
+    if (!kv || !kv->pool || !kv->block_table_host || !kv->block_table_dev) return fail(ctx, CAKE_E_INVAL, "kv: null pointer");
+    if (kv->page_tokens <= 0 || kv->page_tokens % 64) return fail(ctx, CAKE_E_INVAL, "kv: page_tokens must be a positive multiple of 64");
+    if (kv->n_physical_pages <= 0 || kv->n_logical_pages <= 0) return fail(ctx, CAKE_E_INVAL, "kv: no pages");
+    int need = (tok_end + kv->page_tokens - 1) / kv->page_tokens;
+    if (need > kv->n_logical_pages) return fail(ctx, CAKE_E_INVAL, "kv: block table has %d pages, %d needed", kv->n_logical_pages, need);
+    for (int p = 0; p < need; ++p) {
+        int pp = kv->block_table_host[p];
+        if (pp < 0 || pp >= kv->n_physical_pages) return fail(ctx, CAKE_E_INVAL, "kv: block_table[%d] = %d outside the pool", p, pp);
+    }
+    return CAKE_OK;
+}
+
+static KvView make_view(const cake_ctx* c, const cake_kv* kv, int layer) {
+    KvView v;
+    v.pool = kv->pool;
+    v.block_table = kv->block_table_dev;
+    v.page_tokens = kv->page_tokens;
+    v.n_physical_pages = kv->n_physical_pages;
+    v.n_kv = c->m.n_kv_heads;
+    v.head_dim = c->m.head_dim;
+    v.layer = layer;
+    return v;
+}
+
+// ------------------------------------------------------------------ kernel dispatch
+static hipError_t gemm(cake_ctx* c, int epi, const void* a, const void* w, const void* w2, void* out, int M, int N, int K) {
+    if (c->m.dtype == CAKE_BF16 && c->tun.kernel_path == 0 && gemm_mfma_supported(epi, M, N, K))
+        return launch_gemm_mfma(epi, a, w, w2, out, M, N, K, c->cs);
+    return launch_gemm_generic(c->m.dtype, epi, a, w, w2, out, M, N, K, c->cs);
+}
+
+static hipError_t attention(cake_ctx* c, const void* q, void* out, int tok_begin, int rows, const KvView& kv) {
+    if (c->m.dtype == CAKE_BF16 && c->tun.kernel_path == 0 && attention_mfma_supported(kv.head_dim, kv.page_tokens))
+        return launch_attention_mfma(q, out, c->m.n_q_heads, tok_begin, rows, kv, c->cs);
+    return launch_attention_generic(c->m.dtype, q, out, c->m.n_q_heads, tok_begin, rows, kv, c->cs);
+}
+
+// Enqueues the prefill of [tok_begin, tok_begin+rows); token ids already in c->d_ids.
+static int enqueue_prefill(cake_ctx* c, int tok_begin, int rows, const cake_kv* kv) {
+    const cake_model_desc& m = c->m;
+    const int d = m.d_model, hq = m.n_q_heads * m.head_dim, nqkv = (m.n_q_heads + 2 * m.n_kv_heads) * m.head_dim;
+    HIP_TRY(c, launch_embed(m.dtype, c->embed, c->d_ids + tok_begin, c->x, rows, d, m.vocab, c->cs));
+    HIP_TRY(c, launch_rope_table(c->rope_cs, tok_begin, rows, m.head_dim, m.rope_theta, c->cs));
+    for (int l = 0; l < m.n_layers; ++l) {
+        const cake_layer_weights& w = c->layers[l];
+        KvView view = make_view(c, kv, l);
+        HIP_TRY(c, launch_rmsnorm(m.dtype, c->x, w.attn_norm, c->h, rows, d, m.rms_eps, c->cs));
+        HIP_TRY(c, gemm(c, EPI_STORE_F32, c->h, w.wqkv, nullptr, c->qkv, rows, nqkv, d));
+        HIP_TRY(c, launch_rope_kv_write(m.dtype, c->qkv, c->rope_cs, c->q, m.n_q_heads, tok_begin, rows, view, c->cs));
+        HIP_TRY(c, attention(c, c->q, c->ao, tok_begin, rows, view));
+        HIP_TRY(c, gemm(c, EPI_RESIDUAL_F32, c->ao, w.wo, nullptr, c->x, rows, d, hq));
+        HIP_TRY(c, launch_rmsnorm(m.dtype, c->x, w.ffn_norm, c->h, rows, d, m.rms_eps, c->cs));
+        HIP_TRY(c, gemm(c, EPI_SWIGLU, c->h, w.w_gate, w.w_up, c->act, rows, m.ffn_dim, d));
+        HIP_TRY(c, gemm(c, EPI_RESIDUAL_F32, c->act, w.w_down, nullptr, c->x, rows, d, m.ffn_dim));
+    }
+    return CAKE_OK;
+}
+
+// ------------------------------------------------------------------ throttled load
+static void wait_until_ns(uint64_t deadline) {
+    for (;;) {
+        uint64_t now = mono_ns();
+        if (now >= deadline) return;
+        uint64_t left = deadline - now;
+        if (left > 200000) std::this_thread::sleep_for(std::chrono::nanoseconds(left - 100000));
+        // short remainders are spun: a sleep overshoots by tens of microseconds
+    }
+}
+
+// fixed_gbps > 0: that rate; == 0: unthrottled; < 0: the context's live rate.
+static int enqueue_load(cake_ctx* c, const cake_kv_store* st, int tok_begin, int tok_count, const cake_kv* kv,
+                        double fixed_gbps) {
+    const cake_model_desc& m = c->m;
+    if (!st || !st->base) return fail(c, CAKE_E_INVAL, "store: null");
+    if (tok_count <= 0) return CAKE_OK;
+    if (st->page_tokens != kv->page_tokens) return fail(c, CAKE_E_INVAL, "store/page size mismatch");
+    const int pt = kv->page_tokens;
+    if (tok_begin % pt) return fail(c, CAKE_E_INVAL, "load range must start on a page boundary");
+    const int p0 = tok_begin / pt, p1 = (tok_begin + tok_count + pt - 1) / pt;
+    const uint64_t layer_bytes = uint64_t(2) * m.n_kv_heads * pt * m.head_dim * esize(c);
+    const uint64_t image_bytes = layer_bytes * m.n_layers;
+    if (st->page_stride_bytes < image_bytes) return fail(c, CAKE_E_INVAL, "store: page stride smaller than a page image");
+    if (p1 > st->n_pages) return fail(c, CAKE_E_STORE_MISS, "store holds %d pages, page %d requested", st->n_pages, p1 - 1);
+    const uint64_t piece_max = c->tun.piece_bytes ? c->tun.piece_bytes : (4ull << 20);
+    const uint64_t start = mono_ns();
+    double release = 0.0;  // ns after start at which the tier has delivered everything issued so far
+    for (int p = p0; p < p1; ++p) {
+        const char* img = (const char*)st->base + uint64_t(p) * st->page_stride_bytes;
+        const int pp = kv->block_table_host[p];
+        for (int l = 0; l < m.n_layers; ++l) {
+            char* dst = (char*)kv->pool + (uint64_t(l) * kv->n_physical_pages + pp) * layer_bytes;
+            const char* src = img + uint64_t(l) * layer_bytes;
+            for (uint64_t off = 0; off < layer_bytes; off += piece_max) {
+                uint64_t n = std::min(piece_max, layer_bytes - off);
+                double rate = fixed_gbps < 0 ? c->gbps.load(std::memory_order_relaxed) : fixed_gbps;
+                if (rate > 0) {
+                    release += double(n) / rate;  // GB/s = bytes per ns
+                    wait_until_ns(start + uint64_t(release));
+                }
+                HIP_TRY(c, hipMemcpyAsync(dst + off, src + off, n, hipMemcpyHostToDevice, c->ls));
+            }
+        }
+    }
+    return CAKE_OK;
+}
+
+// ------------------------------------------------------------------ executor backend
+namespace {
+struct HipBackend : Backend {
+    cake_ctx* c;
+    const cake_kv_store* store;
+    const cake_kv* kv;
+    const int32_t *tb, *tc;
+    int rc_hard = CAKE_OK;
+    HipBackend(cake_ctx* c_, const cake_kv_store* s, const cake_kv* k, const int32_t* b, const int32_t* n)
+        : c(c_), store(s), kv(k), tb(b), tc(n) {}
+    int compute_chunk(int i, uint64_t* device_ns) override {
+        if (hipEventRecord(c->ev_a, c->cs) != hipSuccess) return CAKE_E_HIP;
+        int rc = enqueue_prefill(c, tb[i], tc[i], kv);
+        if (rc != CAKE_OK) return rc;
+        if (hipEventRecord(c->ev_b, c->cs) != hipSuccess) return CAKE_E_HIP;
+        if (hipStreamSynchronize(c->cs) != hipSuccess) return fail(c, CAKE_E_HIP, "compute stream failed in chunk %d", i);
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, c->ev_a, c->ev_b) == hipSuccess) *device_ns = uint64_t(double(ms) * 1e6);
+        return CAKE_OK;
+    }
+    int load_chunk(int i) override {
+        static thread_local bool dev_set = false;
+        if (!dev_set) { (void)hipSetDevice(c->device); dev_set = true; }
+        int rc = enqueue_load(c, store, tb[i], tc[i], kv, -1.0);
+        if (rc != CAKE_OK) return rc;
+        if (hipStreamSynchronize(c->ls) != hipSuccess) return fail(c, CAKE_E_HIP, "copy stream failed in chunk %d", i);
+        return CAKE_OK;
+    }
+    void on_load_completed(int n_loaded) override {
+        if (c->step_after >= 0 && n_loaded == c->step_after) c->gbps.store(c->step_gbps);
+    }
+};
+}  // namespace
+
+extern "C" {
+
+int32_t cake_create(cake_ctx** out, const cake_model_desc* model, const cake_weights* weights, int32_t max_tokens,
+                    int32_t max_chunk, void* compute_stream, void* copy_stream) {
+    if (!out || !model || !weights || !weights->layers || !weights->embed) return CAKE_E_INVAL;
+    const cake_model_desc& m = *model;
+    if (m.n_layers <= 0 || m.d_model <= 0 || m.n_q_heads <= 0 || m.n_kv_heads <= 0 || m.ffn_dim <= 0 || m.vocab <= 0)
+        return CAKE_E_INVAL;
+    if (m.head_dim != 64 && m.head_dim != 128) return CAKE_E_INVAL;
+    if (m.n_q_heads % m.n_kv_heads) return CAKE_E_INVAL;
+    if (m.dtype != CAKE_F32 && m.dtype != CAKE_BF16) return CAKE_E_INVAL;
+    if ((m.d_model & 7) || (m.ffn_dim & 7)) return CAKE_E_INVAL;  // 16-byte vector loads of rows
+    if (max_tokens <= 0 || max_chunk <= 0 || max_chunk > max_tokens) return CAKE_E_INVAL;
+    for (int l = 0; l < m.n_layers; ++l) {
+        const cake_layer_weights& w = weights->layers[l];
+        if (!w.attn_norm || !w.wqkv || !w.wo || !w.ffn_norm || !w.w_gate || !w.w_up || !w.w_down) return CAKE_E_INVAL;
+    }
+    cake_ctx* c = new (std::nothrow) cake_ctx();
+    if (!c) return CAKE_E_NOMEM;
+    c->m = m;
+    c->layers.assign(weights->layers, weights->layers + m.n_layers);
+    c->embed = weights->embed;
+    c->max_tokens = max_tokens;
+    c->max_chunk = max_chunk;
+    c->cs = (hipStream_t)compute_stream;
+    c->ls = (hipStream_t)copy_stream;
+    const size_t e = esize(c), R = size_t(max_chunk);
+    const size_t hq = size_t(m.n_q_heads) * m.head_dim, nqkv = size_t(m.n_q_heads + 2 * m.n_kv_heads) * m.head_dim;
+    bool ok = hipGetDevice(&c->device) == hipSuccess;
+    ok = ok && hipMalloc((void**)&c->x, R * m.d_model * 4) == hipSuccess;
+    ok = ok && hipMalloc(&c->h, R * m.d_model * e) == hipSuccess;
+    ok = ok && hipMalloc((void**)&c->qkv, R * nqkv * 4) == hipSuccess;
+    ok = ok && hipMalloc(&c->q, R * hq * e) == hipSuccess;
+    ok = ok && hipMalloc(&c->ao, R * hq * e) == hipSuccess;
+    ok = ok && hipMalloc(&c->act, R * m.ffn_dim * e) == hipSuccess;
+    ok = ok && hipMalloc((void**)&c->rope_cs, R * m.head_dim * 4) == hipSuccess;
+    ok = ok && hipMalloc((void**)&c->d_ids, size_t(max_tokens) * 4) == hipSuccess;
+    ok = ok && hipEventCreate(&c->ev_a) == hipSuccess && hipEventCreate(&c->ev_b) == hipSuccess;
+    if (!ok) {
+        (void)hipGetLastError();
+        cake_destroy(c);
+        return CAKE_E_NOMEM;
+    }
+    *out = c;
+    return CAKE_OK;
+}
+
+int32_t cake_destroy(cake_ctx* c) {
+    if (!c) return CAKE_OK;
+    if (c->cs || c->ls) (void)hipDeviceSynchronize();
+    (void)hipFree(c->x); (void)hipFree(c->h); (void)hipFree(c->qkv); (void)hipFree(c->q);
+    (void)hipFree(c->ao); (void)hipFree(c->act); (void)hipFree(c->rope_cs); (void)hipFree(c->d_ids);
+    if (c->ev_a) (void)hipEventDestroy(c->ev_a);
+    if (c->ev_b) (void)hipEventDestroy(c->ev_b);
+    delete c;
+    return CAKE_OK;
+}
+
+const char* cake_last_error(const cake_ctx* c) { return c ? c->err.c_str() : "null context"; }
+
+int32_t cake_set_tuning(cake_ctx* c, const cake_tuning* t) {
+    if (!c || !t) return CAKE_E_INVAL;
+    if (t->prior_compute_ns && t->prior_compute_flops) {
+        c->tun.prior_compute_ns = t->prior_compute_ns;
+        c->tun.prior_compute_flops = t->prior_compute_flops;
+    }
+    if (t->piece_bytes) {
+        if (t->piece_bytes < 4096) return fail(c, CAKE_E_INVAL, "piece_bytes below 4096");
+        c->tun.piece_bytes = t->piece_bytes;
+    }
+    if (t->kernel_path < 0 || t->kernel_path > 1) return fail(c, CAKE_E_INVAL, "kernel_path must be 0 or 1");
+    c->tun.kernel_path = t->kernel_path;
+    return CAKE_OK;
+}
+
+int32_t cake_prefill_chunk(cake_ctx* c, const int32_t* token_ids, int32_t tok_begin, int32_t tok_count,
+                           const cake_kv* kv) {
+    if (!c || !token_ids) return CAKE_E_INVAL;
+    if (tok_begin < 0 || tok_count < 0 || tok_count > c->max_chunk || tok_begin + tok_count > c->max_tokens)
+        return fail(c, CAKE_E_INVAL, "token range [%d,+%d) outside max_tokens %d / max_chunk %d", tok_begin, tok_count,
+                    c->max_tokens, c->max_chunk);
+    if (tok_count == 0) return CAKE_OK;
+    int rc = check_kv(c, kv, tok_begin + tok_count);
+    if (rc != CAKE_OK) return rc;
+    for (int i = 0; i < tok_count; ++i) {
+        int id = token_ids[tok_begin + i];
+        if (id < 0 || id >= c->m.vocab) return fail(c, CAKE_E_INVAL, "token id %d at %d outside the vocabulary", id, tok_begin + i);
+    }
+    HIP_TRY(c, hipMemcpyAsync(c->d_ids + tok_begin, token_ids + tok_begin, size_t(tok_count) * 4, hipMemcpyHostToDevice, c->cs));
+    return enqueue_prefill(c, tok_begin, tok_count, kv);
+}
+
+int32_t cake_load_chunk(cake_ctx* c, const cake_kv_store* store, int32_t tok_begin, int32_t tok_count,
+                        const cake_kv* kv, double gbps) {
+    if (!c) return CAKE_E_INVAL;
+    if (tok_begin < 0 || tok_count < 0) return fail(c, CAKE_E_INVAL, "negative token range");
+    int rc = check_kv(c, kv, tok_begin + tok_count);
+    if (rc != CAKE_OK) return rc;
+    return enqueue_load(c, store, tok_begin, tok_count, kv, gbps > 0 ? gbps : 0.0);
+}
+
+int32_t cake_bidirectional_prefill(cake_ctx* c, const int32_t* token_ids, int32_t n_tokens,
+                                   const cake_kv_store* store, int32_t chunk, double gbps, int32_t mode,
+                                   int32_t forced_m, const cake_kv* kv, cake_result* res) {
+    if (!c || !token_ids || !res) return CAKE_E_INVAL;
+    if (n_tokens <= 0 || n_tokens > c->max_tokens) return fail(c, CAKE_E_INVAL, "n_tokens %d outside (0, %d]", n_tokens, c->max_tokens);
+    if (chunk <= 0 || chunk > c->max_chunk) return fail(c, CAKE_E_INVAL, "chunk %d outside (0, %d]", chunk, c->max_chunk);
+    if (mode < CAKE_BIDIR || mode > CAKE_GREEDY) return fail(c, CAKE_E_INVAL, "unknown mode %d", mode);
+    int rc = check_kv(c, kv, n_tokens);
+    if (rc != CAKE_OK) return rc;
+    if (chunk % kv->page_tokens) return fail(c, CAKE_E_INVAL, "chunk must be a multiple of page_tokens");
+    const int n = (n_tokens + chunk - 1) / chunk;
+    if (mode == CAKE_FORCED_SPLIT && (forced_m < 0 || forced_m > n)) return fail(c, CAKE_E_INVAL, "forced_m %d outside [0,%d]", forced_m, n);
+    if (mode != CAKE_COMPUTE_ONLY) {
+        if (!store || !store->base) return fail(c, CAKE_E_INVAL, "store: null");
+        if (store->page_tokens != kv->page_tokens) return fail(c, CAKE_E_INVAL, "store/page size mismatch");
+        if (store->page_stride_bytes < cake::page_image_bytes(c->m, kv->page_tokens))
+            return fail(c, CAKE_E_INVAL, "store: page stride smaller than a page image");
+        if (!(gbps > 0)) return fail(c, CAKE_E_INVAL, "gbps must be positive");
+    }
+    if (mode != CAKE_LOAD_ONLY)
+        for (int i = 0; i < n_tokens; ++i)
+            if (token_ids[i] < 0 || token_ids[i] >= c->m.vocab) return fail(c, CAKE_E_INVAL, "token id at %d outside the vocabulary", i);
+
+    std::vector<int32_t> tb(n), tc(n);
+    std::vector<uint64_t> flops(n), bytes(n);
+    const uint64_t image = cake::page_image_bytes(c->m, kv->page_tokens);
+    for (int i = 0; i < n; ++i) {
+        tb[i] = i * chunk;
+        tc[i] = std::min(chunk, n_tokens - tb[i]);
+        flops[i] = cake::range_flops(c->m, tb[i], tc[i]);
+        bytes[i] = uint64_t((tc[i] + kv->page_tokens - 1) / kv->page_tokens) * image;
+    }
+    c->status.reset(new std::atomic<int32_t>[n]);
+    c->n_status = n;
+    for (int i = 0; i < n; ++i) c->status[i].store(CAKE_CHUNK_EMPTY);
+    c->gbps.store(gbps > 0 ? gbps : 0.0);
+
+    Executor ex;
+    ex.core.est.prior_c_ns = c->tun.prior_compute_ns;
+    ex.core.est.prior_c_flops = c->tun.prior_compute_flops;
+    ex.core.est.prior_l_ns = 1000000000ull;
+    ex.core.est.prior_l_bytes = gbps > 0 ? uint64_t(gbps * 1e9) : 4000000000ull;
+    if (ex.core.est.prior_l_bytes == 0) ex.core.est.prior_l_bytes = 1;
+    ex.core.init(n, flops.data(), bytes.data(), mode, forced_m);
+    ex.core.log = res->decisions;
+    ex.core.log_cap = res->decisions ? res->decisions_cap : 0;
+    ex.status = c->status.get();
+    ex.tok_begin = tb.data();
+    ex.tok_count = tc.data();
+
+    HipBackend be(c, store, kv, tb.data(), tc.data());
+    const uint64_t t_entry = mono_ns();
+    if (mode != CAKE_LOAD_ONLY) {
+        HIP_TRY(c, hipMemcpyAsync(c->d_ids, token_ids, size_t(n_tokens) * 4, hipMemcpyHostToDevice, c->cs));
+    }
+    uint64_t race_ns = 0;
+    rc = ex.run(be, &race_ns);
+    const uint64_t ttft = mono_ns() - t_entry;
+    c->step_after = -1;  // a scheduled bandwidth step applies to one run
+
+    res->n_chunks = n;
+    res->n_decisions = ex.core.log_n;
+    res->load_failed_chunk = ex.load_failed_chunk;
+    res->ttft_ns = ttft;
+    res->meet_point = 0;
+    res->compute_busy_ns = res->compute_device_ns = res->compute_flops = res->load_busy_ns = res->load_bytes = 0;
+    for (int i = 0; i < n; ++i) {
+        const cake_chunk_log& cl = ex.chunk_log[i];
+        if (cl.source == CAKE_SRC_COMPUTE) {
+            ++res->meet_point;
+            res->compute_busy_ns += cl.end_ns - cl.start_ns;
+            res->compute_device_ns += cl.device_ns;
+            res->compute_flops += cl.work;
+        } else if (cl.source == CAKE_SRC_LOAD) {
+            res->load_busy_ns += cl.end_ns - cl.start_ns;
+            res->load_bytes += cl.work;
+        }
+        if (res->chunks && i < res->chunks_cap) res->chunks[i] = cl;
+    }
+    if (rc != CAKE_OK) {
+        if (c->err.empty()) fail(c, rc, "race ended with status %d", rc);
+        return rc;
+    }
+    if ((res->chunks && res->chunks_cap < n) || ex.core.log_overflow) return CAKE_E_CAPACITY;
+    return CAKE_OK;
+}
+
+int32_t cake_set_bandwidth(cake_ctx* c, double gbps) {
+    if (!c || !(gbps > 0)) return CAKE_E_INVAL;
+    c->gbps.store(gbps);
+    return CAKE_OK;
+}
+
+int32_t cake_schedule_bandwidth_step(cake_ctx* c, int32_t after_loaded_chunks, double gbps) {
+    if (!c) return CAKE_E_INVAL;
+    if (after_loaded_chunks < 0) { c->step_after = -1; return CAKE_OK; }
+    if (!(gbps > 0)) return CAKE_E_INVAL;
+    c->step_after = after_loaded_chunks;
+    c->step_gbps = gbps;
+    return CAKE_OK;
+}
+
+int32_t cake_chunk_state(const cake_ctx* c, int32_t chunk) {
+    if (!c || chunk < 0 || chunk >= c->n_status) return CAKE_E_INVAL;
+    return c->status[chunk].load();
+}
+
+int32_t cake_sync_compute(cake_ctx* c) {
+    if (!c) return CAKE_E_INVAL;
+    HIP_TRY(c, hipStreamSynchronize(c->cs));
+    return CAKE_OK;
+}
+
+int32_t cake_sync_load(cake_ctx* c) {
+    if (!c) return CAKE_E_INVAL;
+    HIP_TRY(c, hipStreamSynchronize(c->ls));
+    return CAKE_OK;
+}
+
+// ---- single kernels -------------------------------------------------------------------
+int32_t cake_op_rmsnorm(cake_ctx* c, const float* x, const float* gain, void* out, int32_t rows, int32_t cols) {
+    if (!c || !x || !gain || !out || rows < 0 || cols <= 0) return CAKE_E_INVAL;
+    HIP_TRY(c, launch_rmsnorm(c->m.dtype, x, gain, out, rows, cols, c->m.rms_eps, c->cs));
+    return CAKE_OK;
+}
+
+int32_t cake_op_gemm(cake_ctx* c, const void* a, const void* w, float* out, int32_t M, int32_t N, int32_t K) {
+    if (!c || !a || !w || !out || M < 0 || N <= 0 || K <= 0 || (K & 7)) return CAKE_E_INVAL;
+    HIP_TRY(c, gemm(c, EPI_STORE_F32, a, w, nullptr, out, M, N, K));
+    return CAKE_OK;
+}
+
+int32_t cake_op_gemm_residual(cake_ctx* c, const void* a, const void* w, float* x, int32_t M, int32_t N, int32_t K) {
+    if (!c || !a || !w || !x || M < 0 || N <= 0 || K <= 0 || (K & 7)) return CAKE_E_INVAL;
+    HIP_TRY(c, gemm(c, EPI_RESIDUAL_F32, a, w, nullptr, x, M, N, K));
+    return CAKE_OK;
+}
+
+int32_t cake_op_gemm_swiglu(cake_ctx* c, const void* a, const void* wg, const void* wu, void* out, int32_t M,
+                            int32_t N, int32_t K) {
+    if (!c || !a || !wg || !wu || !out || M < 0 || N <= 0 || K <= 0 || (K & 7)) return CAKE_E_INVAL;
+    HIP_TRY(c, gemm(c, EPI_SWIGLU, a, wg, wu, out, M, N, K));
+    return CAKE_OK;
+}
+
+int32_t cake_op_rope_kv_write(cake_ctx* c, const float* qkv, void* q, int32_t layer, int32_t tok_begin, int32_t rows,
+                              const cake_kv* kv) {
+    if (!c || !qkv || !q || layer < 0 || layer >= c->m.n_layers || tok_begin < 0 || rows < 0 || rows > c->max_chunk)
+        return CAKE_E_INVAL;
+    int rc = check_kv(c, kv, tok_begin + rows);
+    if (rc != CAKE_OK) return rc;
+    HIP_TRY(c, launch_rope_table(c->rope_cs, tok_begin, rows, c->m.head_dim, c->m.rope_theta, c->cs));
+    HIP_TRY(c, launch_rope_kv_write(c->m.dtype, qkv, c->rope_cs, q, c->m.n_q_heads, tok_begin, rows, make_view(c, kv, layer), c->cs));
+    return CAKE_OK;
+}
+
+int32_t cake_op_attention(cake_ctx* c, const void* q, void* out, int32_t layer, int32_t tok_begin, int32_t rows,
+                          const cake_kv* kv) {
+    if (!c || !q || !out || layer < 0 || layer >= c->m.n_layers || tok_begin < 0 || rows < 0) return CAKE_E_INVAL;
+    int rc = check_kv(c, kv, tok_begin + rows);
+    if (rc != CAKE_OK) return rc;
+    HIP_TRY(c, attention(c, q, out, tok_begin, rows, make_view(c, kv, layer)));
+    return CAKE_OK;
+}
+
+}  // extern "C"

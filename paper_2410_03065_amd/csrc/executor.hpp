@@ -1,0 +1,118 @@
+// Threaded executor of the two-ended race (App. A steps 3-6; Alg. 1): the caller's
+// thread is the compute worker, a second thread is the load worker.  Both take their
+// decisions from RaceCore under one mutex; a worker that decides to wait sleeps until
+// the other side claims or completes something.
+#pragma once
+#include <atomic>
+#include <chrono>
+#include <condition_variable>
+#include <mutex>
+#include <thread>
+#include <vector>
+
+#include "race_core.hpp"
+
+namespace cake {
+
+// What a worker does with a claimed chunk.  Both calls block until the chunk's KV is
+// resident (stream drained) and return 0 or a negative cake_status.
+struct Backend {
+    virtual ~Backend() {}
+    virtual int compute_chunk(int chunk, uint64_t* device_ns) = 0;
+    virtual int load_chunk(int chunk) = 0;
+    virtual void on_load_completed(int n_loaded_so_far) { (void)n_loaded_so_far; }
+};
+
+inline uint64_t mono_ns() {
+    return uint64_t(std::chrono::duration_cast<std::chrono::nanoseconds>(
+                        std::chrono::steady_clock::now().time_since_epoch()).count());
+}
+
+struct Executor {
+    RaceCore core;
+    std::mutex mu;
+    std::condition_variable cv;
+    uint64_t gen = 0;  // bumped on every claim / completion
+    uint64_t t0 = 0;
+    int first_error = CAKE_OK;
+    int load_failed_chunk = -1;
+    int n_loaded = 0;
+    std::vector<cake_chunk_log> chunk_log;
+    std::atomic<int32_t>* status = nullptr;  // per chunk cake_chunk_status, owned by the caller
+    const int32_t* tok_begin = nullptr;      // per chunk
+    const int32_t* tok_count = nullptr;
+
+    uint64_t now() const { return mono_ns() - t0; }
+
+    void worker(int who, Backend& be) {
+        std::unique_lock<std::mutex> lk(mu);
+        for (;;) {
+            int c = -1;
+            for (;;) {
+                if (first_error != CAKE_OK || core.w[who].retired) return;
+                // An empty range ends this worker only once the other side's chunk in flight
+                // has landed: a failed load hands its chunk back to the range.
+                if (core.range_empty() && !core.w[1 - who].busy) return;
+                uint64_t seen = gen;
+                c = core.range_empty() ? -1 : core.decide(who, now());
+                if (c >= 0) break;
+                cv.wait(lk, [&] { return gen != seen || first_error != CAKE_OK; });
+            }
+            ++gen;
+            cv.notify_all();
+            uint64_t start = core.w[who].started;
+            if (status) status[c].store(who == W_COMPUTE ? CAKE_CHUNK_COMPUTING : CAKE_CHUNK_LOADING);
+            lk.unlock();
+            uint64_t dev_ns = 0;
+            int rc = (who == W_COMPUTE) ? be.compute_chunk(c, &dev_ns) : be.load_chunk(c);
+            lk.lock();
+            uint64_t end = now();
+            bool failed = rc != CAKE_OK;
+            core.complete(who, end, failed);
+            if (failed) {
+                if (status) status[c].store(CAKE_CHUNK_EMPTY);
+                if (who == W_LOAD && !core.w[W_COMPUTE].retired) load_failed_chunk = c;
+                else if (first_error == CAKE_OK) first_error = rc;
+            } else {
+                cake_chunk_log& cl = chunk_log[c];
+                cl.source = who;
+                cl.tok_begin = tok_begin[c];
+                cl.tok_count = tok_count[c];
+                cl.start_ns = start;
+                cl.end_ns = end;
+                cl.work = (who == W_COMPUTE) ? core.flops[c] : core.bytes[c];
+                cl.device_ns = dev_ns;
+                if (status) status[c].store(CAKE_CHUNK_RESIDENT);
+                if (who == W_LOAD) {
+                    ++n_loaded;
+                    be.on_load_completed(n_loaded);
+                }
+            }
+            ++gen;
+            cv.notify_all();
+            if (failed) return;
+        }
+    }
+
+    // Runs the race to the end.  Returns the first hard error, or CAKE_OK.
+    int run(Backend& be, uint64_t* ttft_ns) {
+        chunk_log.assign(size_t(core.n), cake_chunk_log{CAKE_SRC_NONE, 0, 0, 0, 0, 0, 0});
+        first_error = CAKE_OK;
+        load_failed_chunk = -1;
+        n_loaded = 0;
+        gen = 0;
+        t0 = mono_ns();
+        std::thread loader;
+        bool have_loader = !core.w[W_LOAD].retired && core.n > 0;
+        if (have_loader) loader = std::thread([&] { worker(W_LOAD, be); });
+        if (!core.w[W_COMPUTE].retired) worker(W_COMPUTE, be);
+        if (have_loader) loader.join();
+        *ttft_ns = now();
+        if (first_error != CAKE_OK) return first_error;
+        std::lock_guard<std::mutex> g(mu);
+        if (!core.range_empty()) return load_failed_chunk >= 0 ? CAKE_E_STORE_MISS : CAKE_E_STATE;
+        return CAKE_OK;
+    }
+};
+
+}  // namespace cake

@@ -1,0 +1,48 @@
+// Launchers of the device kernels.  Every launcher enqueues on `st` and returns the
+// hipError_t of the launch.  Shapes are validated by the callers in cake_api.hip.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace cake {
+
+typedef __bf16 bf16_t;
+
+// Where a layer's K and V live: see the pool layout in cake.h.
+struct KvView {
+    void* pool;
+    const int32_t* block_table;  // device
+    int32_t page_tokens;
+    int32_t n_physical_pages;
+    int32_t n_kv;
+    int32_t head_dim;
+    int32_t layer;
+    // elements per (layer, page): 2 * n_kv * page_tokens * head_dim
+    __host__ __device__ size_t page_elems() const { return size_t(2) * n_kv * page_tokens * head_dim; }
+};
+
+enum GemmEpilogue { EPI_STORE_F32 = 0, EPI_RESIDUAL_F32 = 1, EPI_SWIGLU = 2 };
+
+// ---- generic kernels (any supported shape; the only path for float32 models) ----
+hipError_t launch_embed(int dtype, const void* table, const int32_t* ids, float* x, int rows,
+                        int d, int vocab, hipStream_t st);
+hipError_t launch_rmsnorm(int dtype, const float* x, const float* gain, void* out, int rows, int d,
+                          float eps, hipStream_t st);
+hipError_t launch_rope_table(float* cs, int tok_begin, int rows, int head_dim, float theta,
+                             hipStream_t st);
+hipError_t launch_rope_kv_write(int dtype, const float* qkv, const float* cs, void* q, int n_q,
+                                int tok_begin, int rows, const KvView& kv, hipStream_t st);
+hipError_t launch_gemm_generic(int dtype, int epi, const void* a, const void* w, const void* w2,
+                               void* out, int M, int N, int K, hipStream_t st);
+hipError_t launch_attention_generic(int dtype, const void* q, void* out, int n_q, int tok_begin,
+                                    int rows, const KvView& kv, hipStream_t st);
+
+// ---- MFMA kernels (bf16) ----
+bool gemm_mfma_supported(int epi, int M, int N, int K);
+hipError_t launch_gemm_mfma(int epi, const void* a, const void* w, const void* w2, void* out,
+                            int M, int N, int K, hipStream_t st);
+bool attention_mfma_supported(int head_dim, int page_tokens);
+hipError_t launch_attention_mfma(const void* q, void* out, int n_q, int tok_begin, int rows,
+                                 const KvView& kv, hipStream_t st);
+
+}  // namespace cake

@@ -1,0 +1,138 @@
+"""GPU parity of the single kernels against the oracle's pieces, through the C ABI."""
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from oracle import transformer as otf
+from oracle import store as ostore
+
+pytestmark = pytest.mark.gpu
+
+
+def _engine(shape, T, C, pt, **kw):
+    import paper_2410_03065_amd as cake
+    w = si.make_weights(shape.with_(vocab=64, n_layers=1), seed=0)
+    return cake.Engine(shape.with_(vocab=64, n_layers=1), w, max_tokens=T, max_chunk=min(C, T), page_tokens=pt, **kw)
+
+
+def _bf16_vals(rng, shape, scale=1.0):
+    a = (rng.standard_normal(shape) * scale).astype(np.float32)
+    a.view(np.uint32)[...] &= np.uint32(0xFFFF0000)
+    return a
+
+
+def _rel(got, want):
+    return float(np.abs(got - want).max() / np.abs(want).max())
+
+
+SHAPE_BF = si.ModelShape("op-bf16", 1, 256, 8, 2, 128, 512, 64, "bf16", rope_theta=500000.0)
+SHAPE_F32 = si.ModelShape("op-f32", 1, 256, 4, 4, 64, 688, 64, "f32")
+
+
+@pytest.mark.parametrize("kind", ["f32", "bf16"])
+def test_rmsnorm(kind):
+    import torch
+    shape = SHAPE_F32 if kind == "f32" else SHAPE_BF
+    eng = _engine(shape, 256, 256, 64)
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal((37, 1000)).astype(np.float32) * 3
+    g = (1 + 0.3 * rng.standard_normal(1000)).astype(np.float32)
+    got = eng.op_rmsnorm(torch.from_numpy(x).cuda(), torch.from_numpy(g).cuda()).float().cpu().numpy()
+    want = otf.rmsnorm(x.astype(np.float64), g.astype(np.float64), shape.rms_eps)
+    assert _rel(got, want) < (1e-6 if kind == "f32" else 2.0 ** -8)
+
+
+@pytest.mark.parametrize("kind,path,M,N,K", [
+    ("f32", 0, 130, 100, 72), ("f32", 0, 256, 688, 256),
+    ("bf16", 1, 130, 100, 72),                      # generic kernel on bf16
+    ("bf16", 0, 300, 256, 512), ("bf16", 0, 1024, 384, 4096), ("bf16", 0, 1, 128, 64),
+])
+def test_gemm_variants(kind, path, M, N, K):
+    import torch
+    shape = SHAPE_F32 if kind == "f32" else SHAPE_BF
+    eng = _engine(shape, 256, 256, 64)
+    eng.set_tuning(kernel_path=path)
+    rng = np.random.default_rng(M + N + K)
+    mk = (lambda s, sc=1.0: _bf16_vals(rng, s, sc)) if kind == "bf16" else (lambda s, sc=1.0: (rng.standard_normal(s) * sc).astype(np.float32))
+    a, w, w2 = mk((M, K)), mk((N, K), 0.05), mk((N, K), 0.05)
+    x0 = rng.standard_normal((M, N)).astype(np.float32)
+    td = torch.float32 if kind == "f32" else torch.bfloat16
+    A, W, W2 = (torch.from_numpy(t).cuda().to(td) for t in (a, w, w2))
+    a64, w64, w264 = a.astype(np.float64), w.astype(np.float64), w2.astype(np.float64)
+    want = a64 @ w64.T
+    got = eng.op_gemm(A, W).cpu().numpy()
+    assert _rel(got, want) < 2e-6 * max(1, K / 256)
+    X = torch.from_numpy(x0.copy()).cuda()
+    got = eng.op_gemm_residual(A, W, X).cpu().numpy()
+    assert _rel(got, x0 + want) < 2e-6 * max(1, K / 256)
+    want = otf.silu(want) * (a64 @ w264.T)
+    got = eng.op_gemm_swiglu(A, W, W2).float().cpu().numpy()
+    tol = 1e-5 if kind == "f32" else 2.0 ** -8 * 1.01
+    assert np.all(np.abs(got - want) <= tol * np.abs(want) + 1e-6 * np.abs(want).max())
+
+
+@pytest.mark.parametrize("kind", ["f32", "bf16"])
+@pytest.mark.parametrize("tok_begin,rows", [(0, 200), (192, 100), (100, 157), (65400, 136)])
+def test_rope_and_page_write(kind, tok_begin, rows):
+    import torch
+    shape = SHAPE_F32 if kind == "f32" else SHAPE_BF
+    pt, T = 128, tok_begin + rows
+    n_log = (T + pt - 1) // pt
+    bt = np.random.default_rng(1).permutation(n_log).astype(np.int32)      # scattered physical pages
+    eng = _engine(shape, n_log * pt, 256, pt, block_table=bt)
+    rng = np.random.default_rng(2)
+    nq, nkv, hd = shape.n_q, shape.n_kv, shape.head_dim
+    qkv = rng.standard_normal((rows, (nq + 2 * nkv) * hd)).astype(np.float32)
+    q = eng.op_rope_kv_write(torch.from_numpy(qkv).cuda(), 0, tok_begin).float().cpu().numpy()   # [nq][rows][hd]
+    pos = np.arange(tok_begin, tok_begin + rows)
+    q64 = qkv[:, :nq * hd].astype(np.float64).reshape(rows, nq, hd)
+    k64 = qkv[:, nq * hd:(nq + nkv) * hd].astype(np.float64).reshape(rows, nkv, hd)
+    v64 = qkv[:, (nq + nkv) * hd:].astype(np.float64).reshape(rows, nkv, hd)
+    want_q = otf.rope(q64, pos, shape.rope_theta).transpose(1, 0, 2)
+    tol = 2e-6 if kind == "f32" else 2.0 ** -8 * 1.01
+    assert np.all(np.abs(q - want_q) <= tol * np.abs(want_q) + 1e-6)
+    cache = otf.KVCache(1, T, nkv, hd)
+    cache.k[0, tok_begin:] = otf.rope(k64, pos, shape.rope_theta)
+    cache.v[0, tok_begin:] = v64
+    want = ostore.decode_words(ostore.pack_store(_rounded(cache, kind), pt, kind), kind)
+    got = eng.pool_images(T)
+    assert np.all(np.abs(got - want) <= tol * np.abs(want) + 1e-6)
+    # V is a pure copy: exact after storage rounding; untouched slots stay zero
+    np.testing.assert_array_equal(got[:, :, 1], want[:, :, 1])
+    assert np.all(got[want == 0] == 0)
+
+
+def _rounded(cache, kind):
+    out = otf.KVCache(*cache.k.shape[:1], cache.k.shape[1], cache.k.shape[2], cache.k.shape[3])
+    out.k[:] = otf.round_storage(cache.k, kind)
+    out.v[:] = otf.round_storage(cache.v, kind)
+    return out
+
+
+@pytest.mark.parametrize("kind,path", [("f32", 0), ("bf16", 1), ("bf16", 0)])
+@pytest.mark.parametrize("tok_begin,rows", [(0, 130), (256, 256), (448, 77), (1, 1)])
+def test_attention(kind, path, tok_begin, rows):
+    import torch
+    shape = SHAPE_F32 if kind == "f32" else SHAPE_BF
+    pt, T = 128, tok_begin + rows
+    n_log = (T + pt - 1) // pt
+    bt = np.random.default_rng(3).permutation(n_log).astype(np.int32)
+    eng = _engine(shape, n_log * pt, 256, pt, block_table=bt)
+    eng.set_tuning(kernel_path=path)
+    rng = np.random.default_rng(4 + rows)
+    nq, nkv, hd = shape.n_q, shape.n_kv, shape.head_dim
+    cache = otf.KVCache(1, T, nkv, hd)
+    cache.k[0] = rng.standard_normal((T, nkv, hd)) * 1.5          # peaked softmax rows
+    cache.v[0] = rng.standard_normal((T, nkv, hd))
+    cache = _rounded(cache, kind)
+    images = ostore.pack_store(cache, pt, kind)
+    eng.set_store(images)
+    eng.load_chunk(0, T)
+    q = otf.round_storage(rng.standard_normal((rows, nq, hd)), kind)
+    td = torch.float32 if kind == "f32" else torch.bfloat16
+    Q = torch.from_numpy(q.transpose(1, 0, 2).astype(np.float32).copy()).cuda().to(td)
+    got = eng.op_attention(Q, 0, tok_begin).float().cpu().numpy().reshape(rows, nq, hd)
+    want = otf.attention(q, cache.k[0], cache.v[0], np.arange(tok_begin, T), np.arange(T))
+    # bf16: probabilities and the output are rounded to bf16 (2^-9 each, relative to the row's scale)
+    tol = 2e-5 if kind == "f32" else 1.2e-2
+    assert _rel(got, want) < tol, _rel(got, want)
