@@ -1,0 +1,205 @@
+"""End-to-end GPU parity: the KV cache produced through the C ABI against the CPU oracle,
+for every split of the prompt between computed and loaded chunks.
+
+Tolerances (max |gpu - oracle| / max |oracle| per layer and per K|V tensor): 1e-4 for
+float32 models, 2e-2 for bf16 models.  Loaded chunks must equal the stored bytes; computed
+chunks must be the same bytes whatever the split."""
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from oracle import meet_point as mp
+from oracle import store as ostore
+from oracle import transformer as otf
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def _errs(got, want):
+    """max-abs error over max-abs reference, per (layer, K|V)."""
+    num = np.abs(got - want).max(axis=(0, 3))
+    den = np.abs(want).max(axis=(0, 3))
+    return num / den
+
+
+def _setup(shape, T, C, pt, seed=0, scramble=False, std=0.02):
+    import paper_2410_03065_amd as cake
+    w = si.make_weights(shape, seed=seed, std=std)
+    toks = si.make_tokens(T, shape.vocab, seed=seed + 1)
+    n_log = (T + pt - 1) // pt
+    bt = np.random.default_rng(seed).permutation(n_log).astype(np.int32) if scramble else None
+    eng = cake.Engine(shape, w, max_tokens=n_log * pt, max_chunk=C, page_tokens=pt, block_table=bt)
+    return w, toks, eng
+
+
+def _check_decisions(res, shape, T, C, pt):
+    """Every logged look at the range is the brute-force optimum of its own logged inputs."""
+    n = (T + C - 1) // C
+    flops = [mp.range_flops(shape.n_layers, shape.d_model, shape.n_q, shape.n_kv, shape.head_dim, shape.ffn,
+                            i * C, min((i + 1) * C, T)) for i in range(n)]
+    per_page = pt * otf.kv_bytes_per_token(shape.n_layers, shape.n_kv, shape.head_dim, shape.elem_bytes)
+    byts = [((min((i + 1) * C, T) - i * C + pt - 1) // pt) * per_page for i in range(n)]
+    assert len(res.decisions) > 0
+    claimed = {0: [], 1: []}
+    for d in res.decisions:
+        e = mp.Estimator(d["est_compute_ns"], d["est_compute_flops"], d["est_load_ns"], d["est_load_bytes"])
+        ce = [e.est_compute(flops[i]) for i in range(d["f"], d["b"] + 1)]
+        le = [e.est_load(byts[i]) for i in range(d["f"], d["b"] + 1)]
+        assert d["m_star"] == d["f"] + mp.brute_force_meet_point(ce, le, d["o_c"], d["o_l"])[0], d
+        want_claim = d["f"] if (d["who"] == 0 and d["f"] < d["m_star"]) else \
+            d["b"] if (d["who"] == 1 and d["b"] >= d["m_star"]) else -1
+        assert d["claimed"] == want_claim, d
+        if d["claimed"] >= 0:
+            claimed[d["who"]].append(d["claimed"])
+    m = res.meet_point
+    assert claimed[0] == list(range(m)) and claimed[1] == list(range(n - 1, m - 1, -1))
+    assert [c["source"] for c in res.chunks] == [0] * m + [1] * (n - m)
+    for c, fl, by in zip(res.chunks, flops, byts):
+        assert c["work"] == (fl if c["source"] == 0 else by)
+
+
+def test_config1_tiny_fp32_all_splits():
+    """Tiny decoder, fp32, 2048 tokens, chunk 256, stored KV from the oracle's full prefill,
+    1 GB/s: every forced split, the two baselines and the planned race."""
+    shape, T, C, pt = si.TINY, 2048, 256, 128
+    w, toks, eng = _setup(shape, T, C, pt, scramble=True)
+    ref = otf.prefill_monolithic(w, shape, toks, kv_dtype="f32")
+    images = ostore.pack_store(ref, pt, "f32")
+    want = ostore.decode_words(images, "f32")
+    eng.set_store(images)
+    n = T // C
+    ppc = C // pt
+    raw_computed = None
+    for m in list(range(n + 1)):
+        eng.clear_pool()
+        res = eng.bidirectional_prefill(toks, C, 1.0, mode="forced", forced_m=m)
+        assert res.meet_point == m and res.n_chunks == n
+        got, raw = eng.pool_images(T), eng.pool_raw(T)
+        assert _errs(got, want).max() < TOL["f32"]
+        np.testing.assert_array_equal(raw[m * ppc:].view(np.uint32), images[m * ppc:])      # loaded = stored bytes
+        if m == n:
+            raw_computed = raw
+    for m in range(1, n):                                                       # computed bytes do not depend on m
+        eng.clear_pool()
+        eng.bidirectional_prefill(toks, C, 1.0, mode="forced", forced_m=m)
+        np.testing.assert_array_equal(eng.pool_raw(T)[:m * ppc], raw_computed[:m * ppc])
+    for mode, m_want in (("compute_only", n), ("load_only", 0)):
+        eng.clear_pool()
+        res = eng.bidirectional_prefill(toks, C, 1.0, mode=mode)
+        assert res.meet_point == m_want
+        assert _errs(eng.pool_images(T), want).max() < TOL["f32"]
+    eng.clear_pool()
+    res = eng.bidirectional_prefill(toks, C, 1.0, mode="bidir")
+    _check_decisions(res, shape, T, C, pt)
+    assert _errs(eng.pool_images(T), want).max() < TOL["f32"]
+    raw = eng.pool_raw(T)
+    np.testing.assert_array_equal(raw[:res.meet_point * ppc], raw_computed[:res.meet_point * ppc])
+    np.testing.assert_array_equal(raw[res.meet_point * ppc:].view(np.uint32), images[res.meet_point * ppc:])
+    # load side ran at the configured rate (never above it)
+    if res.load_bytes:
+        assert res.achieved_gbps <= 1.0 * 1.001
+
+
+def test_fp32_ragged_prompt_and_chunk_prefill_calls():
+    """Prompt length that is neither a multiple of the chunk nor of the page; cake_prefill_chunk
+    and cake_load_chunk called directly with odd ranges."""
+    shape, T, C, pt = si.TINY.with_(vocab=1000), 1000, 256, 64
+    w, toks, eng = _setup(shape, T, C, pt, seed=3)
+    ref = otf.prefill_chunked(w, shape, toks, 333, kv_dtype="f32")
+    images = ostore.pack_store(ref, pt, "f32")
+    want = ostore.decode_words(images, "f32")
+    eng.set_store(images)
+    for m in (0, 2, 4):
+        eng.clear_pool()
+        res = eng.bidirectional_prefill(toks, C, 2.0, mode="forced", forced_m=m)
+        assert res.n_chunks == 4 and res.chunks[3]["tok_count"] == 1000 - 768
+        assert _errs(eng.pool_images(T), want).max() < TOL["f32"]
+    # direct calls: four uneven compute steps, then the tail loaded from page 12 on
+    eng.clear_pool()
+    eng.prefill_chunk(toks, 0, 100)
+    eng.prefill_chunk(toks, 100, 256)
+    eng.prefill_chunk(toks, 356, 256)
+    eng.prefill_chunk(toks, 612, 768 - 612)
+    eng.load_chunk(768, T - 768, gbps=0.5)
+    assert _errs(eng.pool_images(T), want).max() < TOL["f32"]
+
+
+BF_NARROW_GQA4 = si.ModelShape("bf16-gqa4", 4, 1024, 8, 2, 128, 2816, 2048, "bf16", rope_theta=500000.0)
+BF_NARROW_GQA8 = si.ModelShape("bf16-gqa8", 2, 1024, 8, 1, 128, 3584, 2048, "bf16")
+BF_NARROW_MHA = si.ModelShape("bf16-mha", 2, 1024, 8, 8, 128, 2752, 2048, "bf16")
+BF_DEEP = si.ModelShape("bf16-deep", 32, 512, 4, 1, 128, 1408, 2048, "bf16", rope_theta=500000.0)
+
+
+@pytest.mark.parametrize("shape,T,C,pt", [
+    (BF_NARROW_GQA4, 4096, 1024, 256),     # GQA 4:1, KV longer than several key tiles, 4 chunks
+    (BF_NARROW_GQA8, 3000, 1024, 256),     # GQA 8:1, ragged last chunk and page
+    (BF_NARROW_MHA, 2048, 512, 128),       # MHA, chunk 512
+    (BF_DEEP, 1024, 512, 256),             # 32 layers: error growth through depth
+])
+def test_bf16_reduced_shapes(shape, T, C, pt):
+    w, toks, eng = _setup(shape, T, C, pt, seed=5, scramble=True)
+    ref = otf.prefill_chunked(w, shape, toks, C, kv_dtype="bf16")
+    images = ostore.pack_store(ref, pt, "bf16")
+    want = ostore.decode_words(images, "bf16")
+    eng.set_store(images)
+    n = (T + C - 1) // C
+    ppc = C // pt
+    res = eng.bidirectional_prefill(toks, C, 4.0, mode="compute_only")
+    assert res.meet_point == n
+    e = _errs(eng.pool_images(T), want)
+    assert e.max() < TOL["bf16"], e
+    raw_full = eng.pool_raw(T)
+    # generic kernels give the same result within the same tolerance
+    eng.clear_pool()
+    eng.set_tuning(kernel_path=1)
+    eng.bidirectional_prefill(toks, C, 4.0, mode="compute_only")
+    assert _errs(eng.pool_images(T), want).max() < TOL["bf16"]
+    eng.set_tuning(kernel_path=0)
+    for m in (0, n // 2):
+        eng.clear_pool()
+        res = eng.bidirectional_prefill(toks, C, 4.0, mode="forced", forced_m=m)
+        raw = eng.pool_raw(T)
+        np.testing.assert_array_equal(raw[m * ppc:].view(np.uint16), images[m * ppc:])
+        np.testing.assert_array_equal(raw[:m * ppc], raw_full[:m * ppc])
+    eng.clear_pool()
+    res = eng.bidirectional_prefill(toks, C, 4.0, mode="bidir")
+    _check_decisions(res, shape, T, C, pt)
+    assert _errs(eng.pool_images(T), want).max() < TOL["bf16"]
+
+
+def test_bf16_full_width_llama3_8b_two_layers():
+    """Llama3-8B widths (d 4096, 32 query / 8 KV heads x 128, FFN 14336), 2 layers, 2048 tokens."""
+    shape = si.LLAMA3_8B.with_(n_layers=2, vocab=4096)
+    T, C, pt = 2048, 1024, 256
+    w, toks, eng = _setup(shape, T, C, pt, seed=7)
+    ref = otf.prefill_chunked(w, shape, toks, C, kv_dtype="bf16")
+    want = ostore.decode_words(ostore.pack_store(ref, pt, "bf16"), "bf16")
+    eng.bidirectional_prefill(toks, C, 4.0, mode="compute_only")
+    e = _errs(eng.pool_images(T), want)
+    assert e.max() < TOL["bf16"], e
+
+
+def test_bandwidth_step_moves_the_meet_point():
+    """Sec. 5.6: when the I/O rate drops mid-run the planned merge point shifts towards
+    more computed chunks; the throttle follows the new rate."""
+    shape, T, C, pt = BF_NARROW_GQA4, 16384, 1024, 256
+    import paper_2410_03065_amd as cake
+    eng = cake.Engine(shape, None, max_tokens=T, max_chunk=C, page_tokens=pt, seed=1)
+    toks = si.make_tokens(T, shape.vocab, seed=2)
+    eng.bidirectional_prefill(toks, C, 4.0, mode="compute_only")
+    eng.store_from_pool(T)
+    kv_bytes = T * otf.kv_bytes_per_token(shape.n_layers, shape.n_kv, shape.head_dim, 2)
+    # pick a rate at which load-only takes about as long as compute-only, so the race is balanced
+    res_c = eng.bidirectional_prefill(toks, C, 4.0, mode="compute_only")
+    rate = kv_bytes / res_c.ttft_ns
+    res_a = eng.bidirectional_prefill(toks, C, rate, mode="bidir")
+    eng.schedule_bandwidth_step(2, rate / 10)
+    res_b = eng.bidirectional_prefill(toks, C, rate, mode="bidir")
+    _check_decisions(res_a, shape, T, C, pt)
+    _check_decisions(res_b, shape, T, C, pt)
+    assert 0 < res_a.meet_point < 16
+    assert res_b.meet_point > res_a.meet_point
+    stars = [d["m_star"] for d in res_b.decisions]
+    assert max(stars[len(stars) // 2:]) > min(stars[:3])
