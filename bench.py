@@ -1,0 +1,166 @@
+#!/usr/bin/env python3
+"""Benchmark of the bidirectional KV-cache producer on one MI355X.
+
+Workload (default): Llama3-8B-shaped decoder (32 layers, d 4096, 32 query / 8 KV heads x 128,
+FFN 14336, vocab 128256), bf16, random weights N(0, 0.02); one 32768-token uniform-random
+prompt, chunk 1024; stored KV for every chunk in pinned host memory acting as the storage
+tier, throttled to 4 GB/s.  A "step" is one whole bidirectional prefill (every chunk of the
+prompt either computed on the compute stream or loaded on the copy stream, planner running).
+All inputs (weights, token ids, stored KV, KV pool) are resident before the timed region.
+
+Prints ONE JSON line.  `value` is the mean time-to-first-token of the timed bidirectional
+steps in seconds (entry of cake_bidirectional_prefill -> every chunk's KV resident).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def cpu_baseline(shape, chunk, n_tokens, total_flops):
+    """Times the oracle (as it stands) on a bounded sample: the first chunk of the prompt
+    through 2 layers of the same widths, then scales to the whole job by FLOP count."""
+    import numpy as np
+    import synth_inputs as si
+    from oracle import transformer as otf
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count()
+    small = shape.with_(n_layers=2, vocab=4096)
+    w = si.make_weights(small, seed=0)
+    toks = si.make_tokens(chunk, small.vocab, seed=1)
+    t0 = time.perf_counter()
+    otf.prefill_chunked(w, small, toks, chunk, kv_dtype="bf16")
+    dt = time.perf_counter() - t0
+    fl = otf.chunk_flops(small, 0, chunk)
+    return {
+        "value": dt * total_flops / fl, "unit": "s (TTFT, compute-only, extrapolated by FLOPs)",
+        "cores": int(threads), "kind": "oracle",
+        "sample": "oracle.prefill_chunked: first %d-token chunk through 2 of %d layers at full width, "
+                  "%.1f s measured, %.3f TFLOP; scaled x%.0f to the %d-token, %d-layer job"
+                  % (chunk, shape.n_layers, dt, fl / 1e12, total_flops / fl, n_tokens, shape.n_layers),
+        "measured_s": dt, "measured_tflops": fl / dt / 1e12,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--shape", default="llama3-8b-shape")
+    ap.add_argument("--tokens", type=int, default=32768)
+    ap.add_argument("--chunk", type=int, default=1024)
+    ap.add_argument("--page-tokens", type=int, default=256)
+    ap.add_argument("--gbps", type=float, default=4.0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with events in the timed region")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "--gpus %d is not supported. Run with --gpus 1." % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import synth_inputs as si
+    import paper_2410_03065_amd as cake
+
+    shape = si.SHAPES[args.shape]
+    T, C, pt = args.tokens, args.chunk, args.page_tokens
+    n = (T + C - 1) // C
+    eng = cake.Engine(shape, None, max_tokens=T, max_chunk=C, page_tokens=pt, seed=0)
+    toks = si.make_tokens(T, shape.vocab, seed=1)
+    total_flops = sum(cake.range_flops(shape, i * C, min(C, T - i * C)) for i in range(n))
+    kv_bytes = n * (C // pt) * cake.page_image_bytes(shape, pt)
+
+    # stored KV = our own compute-only pass, copied into pinned host memory (the storage tier)
+    eng.bidirectional_prefill(toks, C, args.gbps, mode="compute_only", log=False)
+    eng.store_from_pool(T)
+
+    for _ in range(args.warmup):
+        eng.bidirectional_prefill(toks, C, args.gbps, mode="bidir", log=False)
+    if not args.no_profile:
+        eng.profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    runs = [eng.bidirectional_prefill(toks, C, args.gbps, mode="bidir") for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    stats = eng.profile_read() if not args.no_profile else {}
+    eng.profile_enable(False)
+
+    r_c = eng.bidirectional_prefill(toks, C, args.gbps, mode="compute_only")
+    r_l = eng.bidirectional_prefill(toks, C, args.gbps, mode="load_only")
+
+    ttft = float(np.mean([r.ttft_ns for r in runs])) / 1e9
+    comp_flops = sum(r.compute_flops for r in runs)
+    comp_dev_ns = sum(r.compute_device_ns for r in runs)
+    load_bytes = sum(r.load_bytes for r in runs)
+    load_ns = sum(r.load_busy_ns for r in runs)
+    prefill_tflops = comp_flops / comp_dev_ns / 1e3 if comp_dev_ns else 0.0
+
+    kernels = {}
+    roofline = None
+    if stats:
+        for name, s in stats.items():
+            if not s["launches"]:
+                continue
+            avg_us = s["total_ns"] / s["launches"] / 1e3
+            k = {"launches": s["launches"], "avg_us": round(avg_us, 2), "share": 0.0}
+            if s["flops"]:
+                k["tflops"] = round(s["flops"] / s["total_ns"] / 1e3, 1)
+            k["gbs"] = round(s["bytes"] / s["total_ns"], 1)
+            kernels[name] = k
+        tot = sum(s["total_ns"] for s in stats.values())
+        for name in kernels:
+            kernels[name]["share"] = round(stats[name]["total_ns"] / tot, 3)
+        dom = max(kernels, key=lambda k: stats[k]["total_ns"])
+        s = stats[dom]
+        achieved = s["flops"] / s["total_ns"] / 1e3
+        roofline = {"kernel": dom, "bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS,
+                    "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                    "avg_launch_us": kernels[dom]["avg_us"], "flops_per_launch": s["flops"] // s["launches"]}
+
+    out = {
+        "metric": "ttft_s_32k_prompt_bidirectional", "value": round(ttft, 5), "unit": "s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(wall / args.steps * 1e3, 3), "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if shape.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": "%s, %d random tokens, chunk %d, page %d, stored KV in pinned host memory at %.3g GB/s"
+                               % (shape.name, T, C, pt, args.gbps),
+                   "global_batch": 1, "seq_len": T, "parallelism": "single-gpu"},
+        "ttft_s": {"bidirectional": round(ttft, 5), "compute_only": round(r_c.ttft_ns / 1e9, 5),
+                   "load_only": round(r_l.ttft_ns / 1e9, 5)},
+        "speedup": {"over_load_only": round(r_l.ttft_ns / 1e9 / ttft, 3),
+                    "over_compute_only": round(r_c.ttft_ns / 1e9 / ttft, 3)},
+        "sum_ttft_over_baselines": round(ttft / (r_c.ttft_ns / 1e9) + ttft / (r_l.ttft_ns / 1e9), 4),
+        "meet_point": [r.meet_point for r in runs], "n_chunks": n,
+        "prefill_tflops": {"bidirectional_compute_side": round(prefill_tflops, 1),
+                           "compute_only": round(r_c.compute_tflops, 1), "algorithmic_total_tflop": round(total_flops / 1e12, 1)},
+        "mfma_util": {"bidirectional_compute_side": round(prefill_tflops / PEAK_BF16_TFLOPS, 4),
+                      "compute_only": round(r_c.compute_tflops / PEAK_BF16_TFLOPS, 4), "peak_tflops": PEAK_BF16_TFLOPS},
+        "load_gbps": {"configured": args.gbps, "achieved_bidirectional": round(load_bytes / load_ns, 4) if load_ns else None,
+                      "achieved_load_only": round(r_l.achieved_gbps, 4), "kv_bytes": kv_bytes},
+        "kernels": kernels,
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(shape, C, T, total_flops)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -266,6 +266,20 @@ int32_t cake_simulate_race(int32_t n_chunks, const uint64_t* chunk_flops,
                            cake_decision_log* decisions, int32_t decisions_cap,
                            int32_t* n_decisions_out);
 
+/* Per-kernel-class timing of the compute stream, for roofline reports.  While enabled, every
+ * kernel launch of cake_prefill_chunk / cake_bidirectional_prefill is bracketed by a pair of
+ * HIP events on the compute stream.  cake_profile_read drains the stream, adds the elapsed
+ * times of all pairs recorded since the last read into `out[CAKE_K_COUNT]` (overwritten) and
+ * forgets them.  flops / bytes are the algorithmic work of the launches (bytes: operands read
+ * once + results written once). */
+typedef enum {
+    CAKE_K_EMBED = 0, CAKE_K_RMSNORM = 1, CAKE_K_GEMM_QKV = 2, CAKE_K_ROPE_KV = 3, CAKE_K_ATTENTION = 4,
+    CAKE_K_GEMM_O = 5, CAKE_K_GEMM_GATEUP = 6, CAKE_K_GEMM_DOWN = 7, CAKE_K_COUNT = 8
+} cake_kernel_class;
+typedef struct { uint64_t launches, total_ns, flops, bytes; } cake_kernel_stats;
+int32_t cake_profile_enable(cake_ctx* ctx, int32_t on);
+int32_t cake_profile_read(cake_ctx* ctx, cake_kernel_stats* out);
+
 /* Single kernels, exposed for parity tests and profiling.  All asynchronous on the compute
  * stream; all pointers device; element type = the context's dtype unless stated. */
 int32_t cake_op_rmsnorm(cake_ctx* ctx, const float* x, const float* gain, void* out,

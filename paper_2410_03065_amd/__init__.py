@@ -30,8 +30,9 @@ EXPORTS = [
     "cake_schedule_bandwidth_step", "cake_chunk_state", "cake_sync_compute", "cake_sync_load",
     "cake_range_flops", "cake_page_image_bytes", "cake_simulate_race", "cake_op_rmsnorm",
     "cake_op_gemm", "cake_op_gemm_residual", "cake_op_gemm_swiglu", "cake_op_rope_kv_write",
-    "cake_op_attention",
+    "cake_op_attention", "cake_profile_enable", "cake_profile_read",
 ]
+KERNEL_CLASSES = ["embed", "rmsnorm", "gemm_qkv", "rope_kv", "attention", "gemm_o", "gemm_gateup", "gemm_down"]
 
 
 class CakeError(RuntimeError):
@@ -84,6 +85,10 @@ class Result(C.Structure):
                 ("load_bytes", C.c_uint64)]
 
 
+class KernelStats(C.Structure):
+    _fields_ = [("launches", C.c_uint64), ("total_ns", C.c_uint64), ("flops", C.c_uint64), ("bytes", C.c_uint64)]
+
+
 class Tuning(C.Structure):
     _fields_ = [("prior_compute_ns", C.c_uint64), ("prior_compute_flops", C.c_uint64), ("piece_bytes", C.c_uint64),
                 ("kernel_path", C.c_int32), ("pad_", C.c_int32)]
@@ -117,6 +122,8 @@ def load_library():
         "cake_page_image_bytes": (u64, [P(ModelDesc), i32]),
         "cake_simulate_race": (i32, [i32, vp, vp, vp, vp, u64, u64, u64, u64, i32, i32, i32, vp, P(u64),
                                      P(DecisionLog), i32, P(i32)]),
+        "cake_profile_enable": (i32, [vp, i32]),
+        "cake_profile_read": (i32, [vp, P(KernelStats)]),
         "cake_op_rmsnorm": (i32, [vp, vp, vp, vp, i32, i32]),
         "cake_op_gemm": (i32, [vp, vp, vp, vp, i32, i32, i32]),
         "cake_op_gemm_residual": (i32, [vp, vp, vp, vp, i32, i32, i32]),
@@ -401,6 +408,16 @@ class Engine:
     def schedule_bandwidth_step(self, after_loaded_chunks, gbps):
         self._check(self.lib.cake_schedule_bandwidth_step(self.ctx, after_loaded_chunks, float(gbps)),
                     "cake_schedule_bandwidth_step")
+
+    def profile_enable(self, on=True):
+        self._check(self.lib.cake_profile_enable(self.ctx, 1 if on else 0), "cake_profile_enable")
+
+    def profile_read(self):
+        """{class name: dict(launches, total_ns, flops, bytes)} since the last read."""
+        arr = (KernelStats * len(KERNEL_CLASSES))()
+        self._check(self.lib.cake_profile_read(self.ctx, arr), "cake_profile_read")
+        return {n: dict(launches=arr[i].launches, total_ns=arr[i].total_ns, flops=arr[i].flops, bytes=arr[i].bytes)
+                for i, n in enumerate(KERNEL_CLASSES)}
 
     def chunk_state(self, i):
         return self.lib.cake_chunk_state(self.ctx, i)

@@ -43,6 +43,11 @@ struct cake_ctx {
     std::string err;
     std::unique_ptr<std::atomic<int32_t>[]> status;
     int n_status = 0;
+    // per-kernel-class timing (compute thread only)
+    bool prof_on = false;
+    struct ProfRec { int cls; uint64_t flops, bytes; };
+    std::vector<hipEvent_t> prof_events;  // pairs: [2i] before, [2i+1] after
+    std::vector<ProfRec> prof_recs;
 };
 
 static int fail(cake_ctx* ctx, int code, const char* fmt, ...) {
@@ -104,23 +109,56 @@ static hipError_t attention(cake_ctx* c, const void* q, void* out, int tok_begin
     return launch_attention_generic(c->m.dtype, q, out, c->m.n_q_heads, tok_begin, rows, kv, c->cs);
 }
 
+static hipError_t prof_before(cake_ctx* c, int cls, uint64_t flops, uint64_t bytes) {
+    if (!c->prof_on) return hipSuccess;
+    size_t i = c->prof_recs.size();
+    while (c->prof_events.size() < 2 * (i + 1)) {
+        hipEvent_t e;
+        hipError_t rc = hipEventCreate(&e);
+        if (rc != hipSuccess) return rc;
+        c->prof_events.push_back(e);
+    }
+    c->prof_recs.push_back({cls, flops, bytes});
+    return hipEventRecord(c->prof_events[2 * i], c->cs);
+}
+static hipError_t prof_after(cake_ctx* c) {
+    if (!c->prof_on) return hipSuccess;
+    return hipEventRecord(c->prof_events[2 * c->prof_recs.size() - 1], c->cs);
+}
+#define KLAUNCH(c, cls, fl, by, expr)                       \
+    do {                                                    \
+        HIP_TRY(c, prof_before(c, cls, fl, by));            \
+        HIP_TRY(c, expr);                                   \
+        HIP_TRY(c, prof_after(c));                          \
+    } while (0)
+
 // Enqueues the prefill of [tok_begin, tok_begin+rows); token ids already in c->d_ids.
 static int enqueue_prefill(cake_ctx* c, int tok_begin, int rows, const cake_kv* kv) {
     const cake_model_desc& m = c->m;
-    const int d = m.d_model, hq = m.n_q_heads * m.head_dim, nqkv = (m.n_q_heads + 2 * m.n_kv_heads) * m.head_dim;
-    HIP_TRY(c, launch_embed(m.dtype, c->embed, c->d_ids + tok_begin, c->x, rows, d, m.vocab, c->cs));
+    const uint64_t d = m.d_model, hq = uint64_t(m.n_q_heads) * m.head_dim, hkv = uint64_t(m.n_kv_heads) * m.head_dim;
+    const uint64_t nqkv = hq + 2 * hkv, ff = m.ffn_dim, R = rows, e = esize(c);
+    const uint64_t t0 = tok_begin;
+    // algorithmic work per launch: flops of the contraction; bytes = operands once + result once
+    const uint64_t attn_flops = 4 * hq * (t0 * R + R * (R + 1) / 2);
+    const uint64_t attn_bytes = (2 * R * hq + 2 * hkv * (t0 + R)) * e;
+    KLAUNCH(c, CAKE_K_EMBED, 0, R * d * (e + 4), launch_embed(m.dtype, c->embed, c->d_ids + tok_begin, c->x, rows, d, m.vocab, c->cs));
     HIP_TRY(c, launch_rope_table(c->rope_cs, tok_begin, rows, m.head_dim, m.rope_theta, c->cs));
     for (int l = 0; l < m.n_layers; ++l) {
         const cake_layer_weights& w = c->layers[l];
         KvView view = make_view(c, kv, l);
-        HIP_TRY(c, launch_rmsnorm(m.dtype, c->x, w.attn_norm, c->h, rows, d, m.rms_eps, c->cs));
-        HIP_TRY(c, gemm(c, EPI_STORE_F32, c->h, w.wqkv, nullptr, c->qkv, rows, nqkv, d));
-        HIP_TRY(c, launch_rope_kv_write(m.dtype, c->qkv, c->rope_cs, c->q, m.n_q_heads, tok_begin, rows, view, c->cs));
-        HIP_TRY(c, attention(c, c->q, c->ao, tok_begin, rows, view));
-        HIP_TRY(c, gemm(c, EPI_RESIDUAL_F32, c->ao, w.wo, nullptr, c->x, rows, d, hq));
-        HIP_TRY(c, launch_rmsnorm(m.dtype, c->x, w.ffn_norm, c->h, rows, d, m.rms_eps, c->cs));
-        HIP_TRY(c, gemm(c, EPI_SWIGLU, c->h, w.w_gate, w.w_up, c->act, rows, m.ffn_dim, d));
-        HIP_TRY(c, gemm(c, EPI_RESIDUAL_F32, c->act, w.w_down, nullptr, c->x, rows, d, m.ffn_dim));
+        KLAUNCH(c, CAKE_K_RMSNORM, 0, R * d * (4 + e), launch_rmsnorm(m.dtype, c->x, w.attn_norm, c->h, rows, d, m.rms_eps, c->cs));
+        KLAUNCH(c, CAKE_K_GEMM_QKV, 2 * R * nqkv * d, (R * d + nqkv * d) * e + R * nqkv * 4,
+                gemm(c, EPI_STORE_F32, c->h, w.wqkv, nullptr, c->qkv, rows, nqkv, d));
+        KLAUNCH(c, CAKE_K_ROPE_KV, 0, R * nqkv * (4 + e),
+                launch_rope_kv_write(m.dtype, c->qkv, c->rope_cs, c->q, m.n_q_heads, tok_begin, rows, view, c->cs));
+        KLAUNCH(c, CAKE_K_ATTENTION, attn_flops, attn_bytes, attention(c, c->q, c->ao, tok_begin, rows, view));
+        KLAUNCH(c, CAKE_K_GEMM_O, 2 * R * d * hq, (R * hq + d * hq) * e + 2 * R * d * 4,
+                gemm(c, EPI_RESIDUAL_F32, c->ao, w.wo, nullptr, c->x, rows, d, hq));
+        KLAUNCH(c, CAKE_K_RMSNORM, 0, R * d * (4 + e), launch_rmsnorm(m.dtype, c->x, w.ffn_norm, c->h, rows, d, m.rms_eps, c->cs));
+        KLAUNCH(c, CAKE_K_GEMM_GATEUP, 4 * R * ff * d, (R * d + 2 * ff * d + R * ff) * e,
+                gemm(c, EPI_SWIGLU, c->h, w.w_gate, w.w_up, c->act, rows, m.ffn_dim, d));
+        KLAUNCH(c, CAKE_K_GEMM_DOWN, 2 * R * d * ff, (R * ff + d * ff) * e + 2 * R * d * 4,
+                gemm(c, EPI_RESIDUAL_F32, c->act, w.w_down, nullptr, c->x, rows, d, m.ffn_dim));
     }
     return CAKE_OK;
 }
@@ -259,6 +297,7 @@ int32_t cake_destroy(cake_ctx* c) {
     if (c->cs || c->ls) (void)hipDeviceSynchronize();
     (void)hipFree(c->x); (void)hipFree(c->h); (void)hipFree(c->qkv); (void)hipFree(c->q);
     (void)hipFree(c->ao); (void)hipFree(c->act); (void)hipFree(c->rope_cs); (void)hipFree(c->d_ids);
+    for (hipEvent_t e : c->prof_events) (void)hipEventDestroy(e);
     if (c->ev_a) (void)hipEventDestroy(c->ev_a);
     if (c->ev_b) (void)hipEventDestroy(c->ev_b);
     delete c;
@@ -424,6 +463,31 @@ int32_t cake_sync_compute(cake_ctx* c) {
 int32_t cake_sync_load(cake_ctx* c) {
     if (!c) return CAKE_E_INVAL;
     HIP_TRY(c, hipStreamSynchronize(c->ls));
+    return CAKE_OK;
+}
+
+int32_t cake_profile_enable(cake_ctx* c, int32_t on) {
+    if (!c) return CAKE_E_INVAL;
+    HIP_TRY(c, hipStreamSynchronize(c->cs));
+    c->prof_on = on != 0;
+    c->prof_recs.clear();
+    return CAKE_OK;
+}
+
+int32_t cake_profile_read(cake_ctx* c, cake_kernel_stats* out) {
+    if (!c || !out) return CAKE_E_INVAL;
+    HIP_TRY(c, hipStreamSynchronize(c->cs));
+    for (int k = 0; k < CAKE_K_COUNT; ++k) out[k] = cake_kernel_stats{0, 0, 0, 0};
+    for (size_t i = 0; i < c->prof_recs.size(); ++i) {
+        float ms = 0.f;
+        HIP_TRY(c, hipEventElapsedTime(&ms, c->prof_events[2 * i], c->prof_events[2 * i + 1]));
+        cake_kernel_stats& s = out[c->prof_recs[i].cls];
+        s.launches += 1;
+        s.total_ns += uint64_t(double(ms) * 1e6);
+        s.flops += c->prof_recs[i].flops;
+        s.bytes += c->prof_recs[i].bytes;
+    }
+    c->prof_recs.clear();
     return CAKE_OK;
 }
 
