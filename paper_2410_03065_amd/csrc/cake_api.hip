@@ -38,7 +38,7 @@ struct cake_ctx {
     std::atomic<double> gbps{0.0};
     int step_after = -1;
     double step_gbps = 0.0;
-    cake_tuning tun{1000000000ull, 500000000000000ull, 4ull << 20, 0, 0};
+    cake_tuning tun{1000000000ull, 500000000000000ull, 4ull << 20, 0, 0};  // gemm_config 0 = automatic
     std::mutex err_mu;
     std::string err;
     std::unique_ptr<std::atomic<int32_t>[]> status;
@@ -99,7 +99,7 @@ static KvView make_view(const cake_ctx* c, const cake_kv* kv, int layer) {
 // ------------------------------------------------------------------ kernel dispatch
 static hipError_t gemm(cake_ctx* c, int epi, const void* a, const void* w, const void* w2, void* out, int M, int N, int K) {
     if (c->m.dtype == CAKE_BF16 && c->tun.kernel_path == 0 && gemm_mfma_supported(epi, M, N, K))
-        return launch_gemm_mfma(epi, a, w, w2, out, M, N, K, c->cs);
+        return launch_gemm_mfma(epi, a, w, w2, out, M, N, K, c->cs, c->tun.gemm_config - 1);
     return launch_gemm_generic(c->m.dtype, epi, a, w, w2, out, M, N, K, c->cs);
 }
 
@@ -318,6 +318,8 @@ int32_t cake_set_tuning(cake_ctx* c, const cake_tuning* t) {
     }
     if (t->kernel_path < 0 || t->kernel_path > 1) return fail(c, CAKE_E_INVAL, "kernel_path must be 0 or 1");
     c->tun.kernel_path = t->kernel_path;
+    if (t->gemm_config < 0 || t->gemm_config > 3) return fail(c, CAKE_E_INVAL, "gemm_config must be 0..3");
+    c->tun.gemm_config = t->gemm_config;
     return CAKE_OK;
 }
 

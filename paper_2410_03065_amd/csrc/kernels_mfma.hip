@@ -19,116 +19,172 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 
 // =====================================================================================
 // GEMM: out[M][N] = a[M][K] * w[N][K]^T, bf16 in, float32 accumulate.
-// 128x128 tile per 256-thread workgroup, 64-deep K slices staged through LDS (double
-// buffered, 16-byte chunks XOR-swizzled by row so the 16-byte operand reads of the 32
-// rows a half-wave touches fall in different banks).  Wave (wm, wn) owns a 64x64
-// quadrant = 2x2 MFMA tiles.
 //
-// Epilogues: store float32; add into a float32 residual stream; SwiGLU, where the B tile is
-// built from 32 gate rows + 32 up rows per wave column so that silu(gate) * up of one output
-// column is formed in registers (the tile then yields 64 output columns).
+// Workgroup tile BM x BN = (WAVES_M*WTM*32) x (WAVES_N*WTN*32); each wave owns WTM x WTN MFMA
+// tiles.  K is consumed in 32-deep slices held in a ring of STAGES LDS buffers that are filled
+// by direct global->LDS loads (global_load_lds_dwordx4: 64 lanes x 16 B land contiguously, so
+// the bank swizzle is applied by choosing which global chunk each lane fetches).  A slice row
+// is 64 B = four 16-byte chunks; chunk c of row r is stored at position c ^ ((r >> 2) & 3), so
+// the 16 rows that one quarter-wave reads with ds_read_b128 cover all 64 LDS banks once.
+//
+// Software pipeline per slice (two 16-deep MFMA steps): while step 0's MFMAs issue, step 1's
+// operands are read; then the wave waits for the NEXT slice's loads (vmcnt), meets the other
+// waves at a bare s_barrier (no fence: a fence would drain every load in flight), refills the
+// buffer freed one slice ago, and runs step 1's MFMAs while reading the next slice's step 0
+// operands.  sched_group_barrier pins the 2-MFMA / 1-ds_read interleave.
+//
+// The block index is remapped so that workgroups that share a weight panel (the tiles_m tiles
+// of one n-panel) sit on the same XCD and run at the same time: the panel is then fetched from
+// HBM once and hit in that XCD's L2 by the others.
+//
+// Epilogues: store float32; add into a float32 residual stream; SwiGLU, where each wave's
+// n-tiles alternate gate / up rows of the two weight matrices, so silu(gate) * up of one
+// output column is formed in registers and the tile yields BN/2 output columns.
 // =====================================================================================
-constexpr int GBM = 128, GBN = 128, GBK = 64;
+#define CAKE_GLOBAL_AS __attribute__((address_space(1)))
+#define CAKE_LDS_AS __attribute__((address_space(3)))
 
-template <int EPI>
-__global__ void __launch_bounds__(256)
+__device__ __forceinline__ int gemm_swz(int row) { return (row >> 2) & 3; }
+
+template <int WTM, int WTN, int WAVES_M, int WAVES_N, int STAGES, int EPI>
+__global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
 gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, const bf16_t* __restrict__ W2,
-                 void* __restrict__ outv, int M, int N, int K) {
-    __shared__ __attribute__((aligned(16))) unsigned char lds[2][(GBM + GBN) * GBK * 2];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
-    const int m0 = blockIdx.y * GBM;
-    const int n0 = blockIdx.x * (EPI == EPI_SWIGLU ? GBN / 2 : GBN);
+                 void* __restrict__ outv, int M, int N, int K, int tiles_m, int tiles_n) {
+    constexpr int BK = 32;
+    constexpr int NW = WAVES_M * WAVES_N;
+    constexpr int BM = WAVES_M * WTM * 32, BN = WAVES_N * WTN * 32;
+    constexpr int ROWB = BK * 2, CPR = BK / 8, RPL = 64 / CPR;
+    constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB, STAGE = A_BYTES + B_BYTES;
+    constexpr int A_PER = A_BYTES / 1024 / NW, B_PER = B_BYTES / 1024 / NW, PER_TILE = A_PER + B_PER;
+    static_assert((A_BYTES / 1024) % NW == 0 && (B_BYTES / 1024) % NW == 0, "slice loads must divide among the waves");
+    static_assert(STAGES >= 3 && (STAGES - 2) * PER_TILE < 64, "vmcnt range");
+    static_assert(EPI != EPI_SWIGLU || WTN % 2 == 0, "gate/up pairs");
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
 
-    // global -> register staging: thread loads 16-byte chunk `c` of rows r, r+32, r+64, r+96
-    const int c = tid & 7, r = tid >> 3;
-    const bf16_t* ap[4];
-    const bf16_t* bp[4];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+    const int lrow = lane & 31, lhalf = lane >> 5;
+
+    const int nb = tiles_m * tiles_n;
+    const int bid = blockIdx.x;
+    const int t = (nb % 8 == 0) ? (bid % 8) * (nb / 8) + bid / 8 : bid;
+    const int tm = t % tiles_m, tn = t / tiles_m;
+    const int m0 = tm * BM;
+    const int n0 = tn * (EPI == EPI_SWIGLU ? BN / 2 : BN);   // first output column of the tile
+
+    // global source of this lane for each 1 KB wave-load (16 rows x 64 B)
+    const int lr = lane / CPR, lpos = lane % CPR;
+    const bf16_t* ag[A_PER];
+    const bf16_t* bg[B_PER];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        int row = r + 32 * i;
-        int am = min(m0 + row, M - 1);
-        ap[i] = A + size_t(am) * K + c * 8;
-        if (EPI == EPI_SWIGLU) {
-            // tile row -> (wave column, gate|up, column): rows [64*wn + 32*t + j], t = 0 gate, 1 up
-            int wcol = row >> 6, t = (row >> 5) & 1, j = row & 31;
-            const bf16_t* src = t ? W2 : W;
-            bp[i] = src + size_t(n0 + wcol * 32 + j) * K + c * 8;
-        } else {
-            bp[i] = W + size_t(n0 + row) * K + c * 8;
-        }
+    for (int i = 0; i < A_PER; ++i) {
+        int row = (wave + i * NW) * RPL + lr;
+        ag[i] = A + size_t(min(m0 + row, M - 1)) * K + (lpos ^ gemm_swz(row)) * 8;
     }
-    uint4 ra[4], rb[4];
-    auto gload = [&](int k0) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            ra[i] = *(const uint4*)(ap[i] + k0);
-            rb[i] = *(const uint4*)(bp[i] + k0);
+    for (int i = 0; i < B_PER; ++i) {
+        int row = (wave + i * NW) * RPL + lr;
+        const bf16_t* src = W;
+        int grow;
+        if (EPI == EPI_SWIGLU) {
+            int wcol = row / (WTN * 32), j = (row / 32) % WTN, c = row % 32;
+            src = (j & 1) ? W2 : W;
+            grow = n0 + wcol * (WTN / 2) * 32 + (j >> 1) * 32 + c;
+        } else {
+            grow = n0 + row;
         }
-    };
-    auto lstore = [&](int buf) {
+        bg[i] = src + size_t(grow) * K + (lpos ^ gemm_swz(row)) * 8;
+    }
+    auto issue = [&](int stage, int k0) {
+        unsigned char* sa = lds + stage * STAGE;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            int row = r + 32 * i;
-            int off = row * (GBK * 2) + ((c ^ (row & 7)) << 4);
-            *(uint4*)(&lds[buf][off]) = ra[i];
-            *(uint4*)(&lds[buf][GBM * GBK * 2 + off]) = rb[i];
-        }
+        for (int i = 0; i < A_PER; ++i)
+            __builtin_amdgcn_global_load_lds((const CAKE_GLOBAL_AS void*)(ag[i] + k0),
+                                             (CAKE_LDS_AS void*)(sa + (wave + i * NW) * 1024), 16, 0, 0);
+#pragma unroll
+        for (int i = 0; i < B_PER; ++i)
+            __builtin_amdgcn_global_load_lds((const CAKE_GLOBAL_AS void*)(bg[i] + k0),
+                                             (CAKE_LDS_AS void*)(sa + A_BYTES + (wave + i * NW) * 1024), 16, 0, 0);
     };
 
-    f32x16 acc[2][2];
+    f32x16 acc[WTM][WTN];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < WTM; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < WTN; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    const int nk = K / GBK;
-    gload(0);
-    lstore(0);
-    __syncthreads();
-    const int lrow = lane & 31, lhalf = lane >> 5;
-    for (int kt = 0; kt < nk; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < nk) gload((kt + 1) * GBK);
-        const unsigned char* la = &lds[buf][0];
-        const unsigned char* lb = &lds[buf][GBM * GBK * 2];
+    const int sw = gemm_swz(lrow);  // tile rows start at multiples of 32, so the swizzle depends on lrow only
+    const int koff0 = ((0 + lhalf) ^ sw) << 4, koff1 = ((2 + lhalf) ^ sw) << 4;
+    const int a_row_off = (wm * WTM * 32 + lrow) * ROWB;
+    const int b_row_off = A_BYTES + (wn * WTN * 32 + lrow) * ROWB;
+    auto rd = [&](bf16x8* a, bf16x8* bb, int stage, int koff) {
+        const unsigned char* st = lds + stage * STAGE;
 #pragma unroll
-        for (int ks = 0; ks < GBK / 16; ++ks) {
-            bf16x8 a[2], b[2];
+        for (int i = 0; i < WTM; ++i) a[i] = *(const bf16x8*)(st + a_row_off + i * 32 * ROWB + koff);
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                int arow = wm * 64 + t * 32 + lrow;
-                int brow = wn * 64 + t * 32 + lrow;
-                int chunk = 2 * ks + lhalf;
-                a[t] = *(const bf16x8*)(la + arow * (GBK * 2) + ((chunk ^ (arow & 7)) << 4));
-                b[t] = *(const bf16x8*)(lb + brow * (GBK * 2) + ((chunk ^ (brow & 7)) << 4));
-            }
+        for (int j = 0; j < WTN; ++j) bb[j] = *(const bf16x8*)(st + b_row_off + j * 32 * ROWB + koff);
+    };
+    auto mm = [&](const bf16x8* a, const bf16x8* bb) {
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < WTM; ++i)
 #pragma unroll
-                for (int j = 0; j < 2; ++j) acc[i][j] = mfma32(a[i], b[j], acc[i][j]);
+            for (int j = 0; j < WTN; ++j) acc[i][j] = mfma32(a[i], bb[j], acc[i][j]);
+    };
+    auto interleave = [&]() {
+#pragma unroll
+        for (int i = 0; i < WTM + WTN; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, (WTM * WTN) / (WTM + WTN), 0);  // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                          // DS read
         }
-        if (kt + 1 < nk) lstore(buf ^ 1);
-        __syncthreads();
+    };
+
+    const int nk = K / BK;
+    // prologue: STAGES-1 slices in flight; slice 0 landed; its step-0 operands in registers
+#pragma unroll
+    for (int st = 0; st < STAGES - 1; ++st)
+        if (st < nk) issue(st, st * BK);
+    if (nk >= STAGES - 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((STAGES - 2) * PER_TILE));
+    else asm volatile("s_waitcnt vmcnt(0)");
+    __builtin_amdgcn_s_barrier();
+    bf16x8 a0[WTM], b0[WTN], a1[WTM], b1[WTN];
+    rd(a0, b0, 0, koff0);
+    for (int kt = 0; kt < nk; ++kt) {
+        const int cur = kt % STAGES;
+        rd(a1, b1, cur, koff1);
+        mm(a0, b0);
+        interleave();
+        // slice kt+1 must have landed before phase B reads its first operands
+        if (kt + STAGES - 1 <= nk) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((STAGES - 3) * PER_TILE));
+        else asm volatile("s_waitcnt vmcnt(0)");
+        __builtin_amdgcn_s_barrier();
+        // every wave has finished reading slice kt-1: refill its buffer
+        if (kt + STAGES - 1 < nk) issue((kt + STAGES - 1) % STAGES, (kt + STAGES - 1) * BK);
+        rd(a0, b0, (kt + 1) % STAGES, koff0);  // past the last slice this reads stale LDS that is never used
+        mm(a1, b1);
+        interleave();
     }
 
     // epilogue
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < WTM; ++i) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            int row = m0 + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * lhalf + (v & 3);
+            int row = m0 + (wm * WTM + i) * 32 + 8 * (v >> 2) + 4 * lhalf + (v & 3);
             if (row >= M) continue;
             if (EPI == EPI_SWIGLU) {
-                int col = n0 + wn * 32 + lrow;
-                float g = acc[i][0][v], u = acc[i][1][v];
-                ((bf16_t*)outv)[size_t(row) * N + col] = bf16_t(g / (1.0f + __expf(-g)) * u);
+#pragma unroll
+                for (int j = 0; j < WTN; j += 2) {
+                    int col = n0 + wn * (WTN / 2) * 32 + (j >> 1) * 32 + lrow;
+                    float g = acc[i][j][v], u = acc[i][j + 1][v];
+                    ((bf16_t*)outv)[size_t(row) * N + col] = bf16_t(g / (1.0f + __expf(-g)) * u);
+                }
             } else {
 #pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    int col = n0 + wn * 64 + j * 32 + lrow;
+                for (int j = 0; j < WTN; ++j) {
+                    int col = n0 + (wn * WTN + j) * 32 + lrow;
                     float* o = (float*)outv + size_t(row) * N + col;
                     if (EPI == EPI_RESIDUAL_F32) *o += acc[i][j][v];
                     else *o = acc[i][j][v];
@@ -138,27 +194,75 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
     }
 }
 
-bool gemm_mfma_supported(int epi, int M, int N, int K) {
-    const int ncols = epi == EPI_SWIGLU ? GBN / 2 : GBN;
-    return M > 0 && N > 0 && K > 0 && (K % GBK) == 0 && (N % ncols) == 0;
+// Tile configurations.  Chosen per GEMM by gemm_pick() from how well the grid fills 256 CUs.
+struct GemmCfg { int bm, bn, lds_bytes; };
+enum { GCFG_256x256 = 0, GCFG_256x128 = 1, GCFG_128x128 = 2, GCFG_COUNT = 3 };
+static const GemmCfg kGemmCfg[GCFG_COUNT] = {
+    {256, 256, (256 + 256) * 64 * 5}, {256, 128, (256 + 128) * 64 * 4}, {128, 128, (128 + 128) * 64 * 4}};
+
+static int out_cols_per_tile(int cfg, int epi) { return epi == EPI_SWIGLU ? kGemmCfg[cfg].bn / 2 : kGemmCfg[cfg].bn; }
+
+static bool gemm_cfg_ok(int cfg, int epi, int M, int N, int K) {
+    return M > 0 && N > 0 && K >= 32 && (K % 32) == 0 && (N % out_cols_per_tile(cfg, epi)) == 0;
+}
+
+bool gemm_mfma_supported(int epi, int M, int N, int K) { return gemm_cfg_ok(GCFG_128x128, epi, M, N, K); }
+
+// Cost model: the busiest CU runs ceil(tiles / 256) tiles one after another, each costing its
+// area divided by a per-shape efficiency (measured: larger tiles feed the MFMAs better because
+// they pull fewer bytes per flop through L2).
+static int gemm_pick(int epi, int M, int N, int K) {
+    static const double eff[GCFG_COUNT] = {1.0, 0.85, 0.80};
+    int best = GCFG_128x128;
+    double best_cost = 1e30;
+    for (int cfg = GCFG_COUNT - 1; cfg >= 0; --cfg) {
+        if (!gemm_cfg_ok(cfg, epi, M, N, K)) continue;
+        const GemmCfg& c = kGemmCfg[cfg];
+        long tiles = long((M + c.bm - 1) / c.bm) * (N / out_cols_per_tile(cfg, epi));
+        double cost = double((tiles + 255) / 256) * double(c.bm) * c.bn / eff[cfg];
+        if (cost < best_cost) { best_cost = cost; best = cfg; }
+    }
+    return best;
+}
+
+template <int WTM, int WTN, int WAVES_M, int WAVES_N, int STAGES, int EPI>
+static hipError_t gemm_launch_t(const bf16_t* A, const bf16_t* W, const bf16_t* W2, void* out, int M, int N, int K,
+                                hipStream_t st) {
+    constexpr int BM = WAVES_M * WTM * 32, BN = WAVES_N * WTN * 32;
+    constexpr int LDS = (BM + BN) * 64 * STAGES;
+    auto kern = gemm_mfma_kernel<WTM, WTN, WAVES_M, WAVES_N, STAGES, EPI>;
+    static bool attr_set = false;   // one flag per instantiation
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int tiles_m = (M + BM - 1) / BM, tiles_n = N / (EPI == EPI_SWIGLU ? BN / 2 : BN);
+    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(64 * WAVES_M * WAVES_N), LDS, st, A, W, W2, out, M, N, K,
+                       tiles_m, tiles_n);
+    return hipGetLastError();
+}
+
+template <int EPI>
+static hipError_t gemm_launch_cfg(int cfg, const bf16_t* A, const bf16_t* W, const bf16_t* W2, void* out, int M, int N,
+                                  int K, hipStream_t st) {
+    switch (cfg) {
+        case GCFG_256x256: return gemm_launch_t<4, 2, 2, 4, 5, EPI>(A, W, W2, out, M, N, K, st);
+        case GCFG_256x128: return gemm_launch_t<4, 2, 2, 2, 4, EPI>(A, W, W2, out, M, N, K, st);
+        default: return gemm_launch_t<2, 2, 2, 2, 4, EPI>(A, W, W2, out, M, N, K, st);
+    }
 }
 
 hipError_t launch_gemm_mfma(int epi, const void* a, const void* w, const void* w2, void* out, int M, int N, int K,
-                            hipStream_t st) {
-    // N is the number of output columns; the SwiGLU tile yields GBN/2 of them
+                            hipStream_t st, int cfg_override) {
     const bf16_t *A = (const bf16_t*)a, *W = (const bf16_t*)w, *W2 = (const bf16_t*)w2;
-    dim3 block(256);
-    if (epi == EPI_SWIGLU) {
-        if (N % (GBN / 2)) return hipErrorInvalidValue;
-        dim3 grid(N / (GBN / 2), (M + GBM - 1) / GBM);
-        hipLaunchKernelGGL((gemm_mfma_kernel<EPI_SWIGLU>), grid, block, 0, st, A, W, W2, out, M, N, K);
-    } else {
-        dim3 grid(N / GBN, (M + GBM - 1) / GBM);
-        if (epi == EPI_STORE_F32) hipLaunchKernelGGL((gemm_mfma_kernel<EPI_STORE_F32>), grid, block, 0, st, A, W, W2, out, M, N, K);
-        else if (epi == EPI_RESIDUAL_F32) hipLaunchKernelGGL((gemm_mfma_kernel<EPI_RESIDUAL_F32>), grid, block, 0, st, A, W, W2, out, M, N, K);
-        else return hipErrorInvalidValue;
-    }
-    return hipGetLastError();
+    int cfg = cfg_override >= 0 && cfg_override < GCFG_COUNT && gemm_cfg_ok(cfg_override, epi, M, N, K)
+                  ? cfg_override : gemm_pick(epi, M, N, K);
+    if (!gemm_cfg_ok(cfg, epi, M, N, K)) return hipErrorInvalidValue;
+    if (epi == EPI_SWIGLU) return gemm_launch_cfg<EPI_SWIGLU>(cfg, A, W, W2, out, M, N, K, st);
+    if (epi == EPI_RESIDUAL_F32) return gemm_launch_cfg<EPI_RESIDUAL_F32>(cfg, A, W, W2, out, M, N, K, st);
+    if (epi == EPI_STORE_F32) return gemm_launch_cfg<EPI_STORE_F32>(cfg, A, W, W2, out, M, N, K, st);
+    return hipErrorInvalidValue;
 }
 
 // =====================================================================================

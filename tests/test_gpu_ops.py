@@ -42,16 +42,19 @@ def test_rmsnorm(kind):
     assert _rel(got, want) < (1e-6 if kind == "f32" else 2.0 ** -8)
 
 
-@pytest.mark.parametrize("kind,path,M,N,K", [
-    ("f32", 0, 130, 100, 72), ("f32", 0, 256, 688, 256),
-    ("bf16", 1, 130, 100, 72),                      # generic kernel on bf16
-    ("bf16", 0, 300, 256, 512), ("bf16", 0, 1024, 384, 4096), ("bf16", 0, 1, 128, 64),
+@pytest.mark.parametrize("kind,path,M,N,K,cfg", [
+    ("f32", 0, 130, 100, 72, 0), ("f32", 0, 256, 688, 256, 0),
+    ("bf16", 1, 130, 100, 72, 0),                      # generic kernel on bf16
+    ("bf16", 0, 300, 256, 512, 0), ("bf16", 0, 1024, 384, 4096, 0), ("bf16", 0, 1, 128, 64, 0),
+    ("bf16", 0, 700, 512, 96, 1), ("bf16", 0, 700, 512, 96, 2), ("bf16", 0, 700, 512, 96, 3),   # each tile shape,
+    ("bf16", 0, 257, 256, 32, 1), ("bf16", 0, 257, 256, 64, 2), ("bf16", 0, 129, 256, 160, 3),  # short K, ragged M
+    ("bf16", 0, 1024, 2048, 1024, 1),
 ])
-def test_gemm_variants(kind, path, M, N, K):
+def test_gemm_variants(kind, path, M, N, K, cfg):
     import torch
     shape = SHAPE_F32 if kind == "f32" else SHAPE_BF
     eng = _engine(shape, 256, 256, 64)
-    eng.set_tuning(kernel_path=path)
+    eng.set_tuning(kernel_path=path, gemm_config=cfg)
     rng = np.random.default_rng(M + N + K)
     mk = (lambda s, sc=1.0: _bf16_vals(rng, s, sc)) if kind == "bf16" else (lambda s, sc=1.0: (rng.standard_normal(s) * sc).astype(np.float32))
     a, w, w2 = mk((M, K)), mk((N, K), 0.05), mk((N, K), 0.05)
