@@ -1,0 +1,364 @@
+// bf16 MFMA attention for gfx950: chunk-vs-prefix causal attention over paged KV
+// (Sec. 3 "Attention and KV cache", "Chunk Prefill": a chunk's queries attend to every cached
+// key before and inside it).  Built with MFMA results kept in ordinary VGPRs, because the
+// softmax reads every score on the vector ALUs.
+//
+// MFMA shape used throughout: v_mfma_f32_32x32x16_bf16.  For D[32x32] += A[32x16] * B[16x32]
+// lane l supplies A[l%32][8*(l/32) .. +7] and B[8*(l/32) .. +7][l%32], and holds
+// D[8*(v/4) + 4*(l/32) + v%4][l%32] in accumulator register v (0..15).
+#include <type_traits>
+
+#include "kernels.hpp"
+
+namespace cake {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+#define CAKE_GLOBAL_AS __attribute__((address_space(1)))
+#define CAKE_LDS_AS __attribute__((address_space(3)))
+
+// =====================================================================================
+// Attention: out[row][h*128 + :] = softmax_s(q_row . k_s / sqrt(128)) v_s over keys s <= tok_begin+row.
+//
+// Workgroup = 4 waves x 32 queries of one query head; keys are visited in tiles of 64 held in a
+// ring of LDS stages filled by direct global->LDS loads from the K pages ([key][hd]) and the
+// transposed V pages ([hd][key]).
+//
+// The score tile is formed transposed, S^T[key][query] = K[key][:] . Q[query][:], so a lane
+// holds 32 keys of ONE query: the online-softmax statistics are per-lane scalars (one exchange
+// with lane^32 for the max) and the probabilities are already laid out as the B operand
+// P^T[key][query] of the second product O^T[hd][query] += V^T[hd][key] P^T[key][query].
+// The K rows fed to the first MFMA are permuted within each group of 16 (rows 4-7 and 8-11
+// swapped).  With that, accumulator registers v = 8*(j&1) .. +7 of key tile j>>1 hold, in the
+// low / high half-wave, keys 16j + 0..7 / 16j + 8..15 -- exactly the 8 consecutive k-slots each
+// half-wave must supply for 16-key step j, so P needs no shuffle and the V^T operand is one
+// aligned 16-byte read.
+//
+// Pipeline per key tile: wait for the next tile's loads, barrier, refill the stage freed one
+// tile ago, then issue the NEXT tile's score MFMAs and, in their shadow, run this tile's
+// softmax on the vector ALUs, then this tile's P V MFMAs.  The output accumulators are rescaled
+// only when some lane's running maximum moved (wave-uniform test).
+// =====================================================================================
+constexpr int AQ = 128;   // queries per workgroup
+constexpr int AK = 64;    // keys per tile
+constexpr int AHD = 128;  // head dim
+constexpr int A_STAGES = 4;
+constexpr int A_KBYTES = AK * AHD * 2, A_STAGE = 2 * A_KBYTES;
+constexpr int A_PER_TILE = 8;  // wave-loads per wave per tile (4 K + 4 V)
+
+__device__ __forceinline__ int sigma16(int x) { return (x & 3) | ((x & 4) << 1) | ((x & 8) >> 1); }
+
+__global__ void __launch_bounds__(256)
+attention_mfma_kernel(const bf16_t* __restrict__ q, bf16_t* __restrict__ out, int n_q, int tok_begin, int rows,
+                      KvView kv, int q_tiles) {
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    const int G = kv.n_kv, r = n_q / G;
+    // Workgroups that share a KV head go to the same XCD (block b runs on XCD b % 8).
+    int g, rest;
+    if ((G & 7) == 0) {
+        const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3, gpx = G >> 3;
+        g = xcd + 8 * (idx % gpx);
+        rest = idx / gpx;
+    } else {
+        g = blockIdx.x % G;
+        rest = blockIdx.x / G;
+    }
+    const int h = g * r + rest % r;
+    const int q0 = (rest / r) * AQ;
+    const int pt = kv.page_tokens;
+
+    const int my_row = min(q0 + wave * 32 + lrow, rows - 1);
+    const int my_pos = tok_begin + my_row;
+    const int wave_first_pos = tok_begin + min(q0 + wave * 32, rows - 1);
+    const int wg_last_pos = tok_begin + min(q0 + AQ, rows) - 1;
+    const int n_tiles = wg_last_pos / AK + 1;
+
+    // Q^T operand: lane supplies q[my_row][16*ks + 8*lhalf .. +7]
+    bf16x8 qreg[AHD / 16];
+    {
+        const bf16_t* qp = q + (size_t(h) * rows + my_row) * AHD + 8 * lhalf;
+#pragma unroll
+        for (int ks = 0; ks < AHD / 16; ++ks) qreg[ks] = *(const bf16x8*)(qp + 16 * ks);
+    }
+
+    // global->LDS sources.  K wave-load j covers rows 4j..4j+3 (256 B each, chunk c stored at c ^ (row & 15));
+    // V^T wave-load j covers rows 8j..8j+7 (128 B each, chunk c stored at c ^ ((row >> 1) & 7)).
+    unsigned koffg[4], voffg[4];   // byte offsets from the tile's K / V^T base
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int j = wave + 4 * i;
+        int krow = 4 * j + (lane >> 4), kpos = lane & 15;
+        koffg[i] = unsigned(krow * AHD + ((kpos ^ (krow & 15)) << 3)) * 2u;
+        int vrow = 8 * j + (lane >> 3), vpos = lane & 7;
+        voffg[i] = unsigned(vrow * pt + ((vpos ^ ((vrow >> 1) & 7)) << 3)) * 2u;
+    }
+    // Byte offset of every logical page this workgroup needs (this layer, this KV head's K block)
+    // is put into LDS once: a global load in the issue path would share the vmcnt counter with
+    // the tile loads and drain the whole ring.  The entry for the tile issued next is read one
+    // tile ahead, so its LDS latency is off the issue path too.
+    const int last_page = wg_last_pos / pt;
+    unsigned long long* pg_lds = (unsigned long long*)(lds + A_STAGES * A_STAGE);
+    {
+        const size_t layer_base = size_t(kv.layer) * kv.n_physical_pages;
+        const size_t page_bytes = kv.page_elems() * 2, k_head = size_t(g) * pt * AHD * 2;
+        for (int i = tid; i <= last_page; i += 256) pg_lds[i] = (layer_base + kv.block_table[i]) * page_bytes + k_head;
+    }
+    __syncthreads();
+    // from a page's K block of head g to its V^T block of head g
+    const unsigned long long k_to_v = (size_t(G - g) * pt * AHD + size_t(g) * AHD * pt) * 2;
+    unsigned long long pg_next = pg_lds[0];
+    auto issue = [&](int stage, int kt) {
+        const int key0 = kt * AK;
+        const int lpage = key0 / pt;
+        const unsigned in_page0 = unsigned(key0 - lpage * pt);
+        // readfirstlane returns a signed int: go through unsigned, or offsets with bit 31 set sign-extend
+        const unsigned long long lo = (unsigned)__builtin_amdgcn_readfirstlane((int)unsigned(pg_next));
+        const unsigned long long hi = (unsigned)__builtin_amdgcn_readfirstlane((int)unsigned(pg_next >> 32));
+        const char* kp = (const char*)kv.pool + ((hi << 32) | lo) + size_t(in_page0) * (AHD * 2);
+        const char* vp = (const char*)kv.pool + ((hi << 32) | lo) + k_to_v + size_t(in_page0) * 2;
+        pg_next = pg_lds[min((key0 + AK) / pt, last_page)];
+        unsigned char* sa = lds + stage * A_STAGE;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            __builtin_amdgcn_global_load_lds((const CAKE_GLOBAL_AS void*)(kp + size_t(koffg[i])),
+                                             (CAKE_LDS_AS void*)(sa + (wave + 4 * i) * 1024), 16, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            __builtin_amdgcn_global_load_lds((const CAKE_GLOBAL_AS void*)(vp + size_t(voffg[i])),
+                                             (CAKE_LDS_AS void*)(sa + A_KBYTES + (wave + 4 * i) * 1024), 16, 0, 0);
+    };
+
+    // operand read offsets (per lane, in bytes from the start of a stage)
+    const int sk = sigma16(lrow & 15);
+    const int krow_base = (16 * (lrow >> 4) + sk) * (AHD * 2);   // + 32*t rows
+    int kaddr[AHD / 16];
+#pragma unroll
+    for (int ks = 0; ks < AHD / 16; ++ks) kaddr[ks] = krow_base + (((2 * ks + lhalf) ^ sk) << 4);
+    const int sv = (lrow >> 1) & 7;
+    int vaddr[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) vaddr[j] = A_KBYTES + lrow * (AK * 2) + (((2 * j + lhalf) ^ sv) << 4);
+
+    f32x16 o[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[t][v] = 0.f;
+    float m_run = -INFINITY, l_part = 0.f;
+    const float sl2 = 0.08838834764831845f * 1.4426950408889634f;  // 1/sqrt(128) * log2(e)
+    const f32x16 zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+
+    // Running maximum of a score tile, in pieces so that it can be spread over MFMA groups:
+    // (masking of the diagonal tiles), max over the lane's 32 scores, exchange with the partner
+    // half-wave, correction factor for the old accumulators.
+    float mx_cur = 0.f, corr_cur = 0.f;
+    bool moved_cur = false;
+    auto mask_tile = [&](f32x16* s, int kt) {
+        const int key0 = kt * AK;
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                int key = key0 + 32 * t + (v & 7) + 8 * lhalf + 16 * (v >> 3);
+                if (key > my_pos) s[t][v] = -INFINITY;
+            }
+    };
+    auto part_max = [&](const f32x16* s, int part, float acc) {   // elements [8*part, 8*part+8) of the 32
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc = fmaxf(acc, s[part >> 1][8 * (part & 1) + i]);
+        return acc;
+    };
+    // The exponentials use a reference value m_run per query that follows the running maximum
+    // lazily: it is moved (and O, l rescaled) only when some lane's maximum has outgrown it by more
+    // than 2^RESCALE_LOG2, so probabilities may reach 2^RESCALE_LOG2 instead of 1 -- harmless in
+    // bf16 / fp32, and softmax is invariant to the reference.  Without this the rescale of the 64
+    // accumulator registers would run on roughly every other tile.
+    constexpr float RESCALE_LOG2 = 6.0f;
+    auto finish_max = [&](float raw) {
+        float mx = raw * sl2;
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));   // key 0 is visible to every query, so mx is finite
+        moved_cur = mx > m_run + RESCALE_LOG2;    // -inf + 6 = -inf: the first tile always moves
+        if (__builtin_amdgcn_ballot_w64(moved_cur) != 0) {
+            mx = fmaxf(mx, m_run);
+            corr_cur = __builtin_amdgcn_exp2f(m_run - mx);
+            m_run = mx;
+            moved_cur = true;
+        } else {
+            corr_cur = 1.0f;
+        }
+        mx_cur = m_run;
+    };
+
+    // One key tile = two MFMA phases of four groups each (4 LDS reads feeding 4 MFMAs per group);
+    // a group's operands are read while the previous group's MFMAs run, and the vector-ALU work
+    // is dealt out group by group so that it executes in the MFMAs' shadow:
+    //   phase 1: S^T of tile kt+1  ||  exponentials + bf16 packing of tile kt (8 per group)
+    //   phase 2: O^T += V^T P^T of tile kt  ||  (mask and) running max of tile kt+1
+    // then the (rare) rescale of O by the correction of tile kt+1.
+    auto step = [&](int kt, f32x16* s_cur, f32x16* s_nxt, auto masked_tag) {
+        constexpr bool masked_next = decltype(masked_tag)::value;
+        if (kt + A_STAGES - 2 < n_tiles) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((A_STAGES - 3) * A_PER_TILE));
+        else asm volatile("s_waitcnt vmcnt(0)");
+        __builtin_amdgcn_s_barrier();
+        if (kt + A_STAGES - 1 < n_tiles) issue((kt + A_STAGES - 1) % A_STAGES, kt + A_STAGES - 1);
+
+        const float mx = mx_cur;
+        // past the last tile the score MFMAs read a stale stage; that result is never used
+        const unsigned char* stk = lds + ((kt + 1) % A_STAGES) * A_STAGE;
+        const unsigned char* stv = lds + (kt % A_STAGES) * A_STAGE;
+        bf16x8 opa[4], opb[4], p[4];
+        auto read_k = [&](bf16x8* dst, int grp) {   // ks = 2*grp, 2*grp+1 ; t = 0, 1
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                dst[i] = *(const bf16x8*)(stk + (i & 1) * 32 * (AHD * 2) + kaddr[2 * grp + (i >> 1)]);
+        };
+        auto read_v = [&](bf16x8* dst, int j) {      // t = 0..3
+#pragma unroll
+            for (int i = 0; i < 4; ++i) dst[i] = *(const bf16x8*)(stv + i * 32 * (AK * 2) + vaddr[j]);
+        };
+        auto mma_k = [&](const bf16x8* src, int grp) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int ks = 2 * grp + (i >> 1), t = i & 1;
+                s_nxt[t] = mfma32(src[i], qreg[ks], ks == 0 ? zero16 : s_nxt[t]);
+            }
+        };
+        auto expo = [&](int grp) {                   // p[grp]: 8 probabilities of tile kt
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                float e = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[grp >> 1][8 * (grp & 1) + i], sl2, -mx));
+                l_part += e;
+                p[grp][i] = bf16_t(e);
+            }
+        };
+        // ---- phase 1
+        read_k(opa, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        read_k(opb, 1); mma_k(opa, 0); expo(0);
+        __builtin_amdgcn_sched_barrier(0);
+        read_k(opa, 2); mma_k(opb, 1); expo(1);
+        __builtin_amdgcn_sched_barrier(0);
+        read_k(opb, 3); mma_k(opa, 2); expo(2);
+        __builtin_amdgcn_sched_barrier(0);
+        read_v(opa, 0); mma_k(opb, 3); expo(3);
+        __builtin_amdgcn_sched_barrier(0);
+        // ---- phase 2
+        float raw;
+        if (masked_next) mask_tile(s_nxt, kt + 1);
+        read_v(opb, 1);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) o[t] = mfma32(opa[t], p[0], o[t]);
+        raw = part_max(s_nxt, 0, s_nxt[0][0]);
+        raw = part_max(s_nxt, 1, raw);
+        __builtin_amdgcn_sched_barrier(0);
+        read_v(opa, 2);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) o[t] = mfma32(opb[t], p[1], o[t]);
+        raw = part_max(s_nxt, 2, raw);
+        raw = part_max(s_nxt, 3, raw);
+        __builtin_amdgcn_sched_barrier(0);
+        read_v(opb, 3);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) o[t] = mfma32(opa[t], p[2], o[t]);
+        finish_max(raw);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) o[t] = mfma32(opb[t], p[3], o[t]);
+        __builtin_amdgcn_sched_barrier(0);
+        if (__builtin_amdgcn_ballot_w64(moved_cur) != 0) {
+            l_part *= corr_cur;
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) o[t][v] *= corr_cur;
+        }
+    };
+
+    // prologue
+#pragma unroll
+    for (int st = 0; st < A_STAGES - 1; ++st)
+        if (st < n_tiles) issue(st, st);
+    if (n_tiles >= A_STAGES - 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((A_STAGES - 2) * A_PER_TILE));
+    else asm volatile("s_waitcnt vmcnt(0)");
+    __builtin_amdgcn_s_barrier();
+    f32x16 s_a[2], s_b[2];
+    {
+        const unsigned char* stk = lds;
+#pragma unroll
+        for (int ks = 0; ks < AHD / 16; ++ks)
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                bf16x8 a = *(const bf16x8*)(stk + t * 32 * (AHD * 2) + kaddr[ks]);
+                s_a[t] = mfma32(a, qreg[ks], ks == 0 ? zero16 : s_a[t]);
+            }
+    }
+    // tiles below first_masked hold only keys every query of this wave may see
+    const int first_masked = (wave_first_pos + 1) / AK;   // first tile with key0 + AK - 1 > wave_first_pos
+    if (first_masked <= 0) mask_tile(s_a, 0);
+    {
+        float raw = s_a[0][0];
+#pragma unroll
+        for (int part = 0; part < 4; ++part) raw = part_max(s_a, part, raw);
+        finish_max(raw);
+    }
+    // two tiles per trip so the score buffers alternate without copies
+    int kt = 0;
+    for (; kt + 2 < first_masked && kt + 1 < n_tiles; kt += 2) {
+        step(kt, s_a, s_b, std::false_type{});
+        step(kt + 1, s_b, s_a, std::false_type{});
+    }
+    for (; kt < n_tiles; kt += 2) {   // the few tiles on and past the diagonal
+        step(kt, s_a, s_b, std::true_type{});
+        if (kt + 1 < n_tiles) step(kt + 1, s_b, s_a, std::true_type{});
+    }
+    // finish: total row sum = this lane's partial + the partner half-wave's
+    const float l_tot = l_part + __shfl_xor(l_part, 32, 64);
+    const float inv = 1.0f / l_tot;
+    const int row = q0 + wave * 32 + lrow;
+    if (row < rows) {
+        bf16_t* op = out + size_t(row) * n_q * AHD + h * AHD;
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int v4 = 0; v4 < 4; ++v4) {
+                bf16x4 w;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) w[e] = bf16_t(o[t][4 * v4 + e] * inv);
+                *(bf16x4*)(op + t * 32 + 8 * v4 + 4 * lhalf) = w;
+            }
+    }
+}
+
+bool attention_mfma_supported(int head_dim, int page_tokens) {
+    return head_dim == AHD && page_tokens % AK == 0;
+}
+
+hipError_t launch_attention_mfma(const void* q, void* out, int n_q, int tok_begin, int rows, const KvView& kv,
+                                 hipStream_t st) {
+    if (rows <= 0) return hipSuccess;
+    static bool attr_set = false;
+    constexpr int LDS_MAX = 160 * 1024;
+    // ring of key/value tiles + one 8-byte page offset per logical page of this launch
+    const int LDS = A_STAGES * A_STAGE + 8 * ((tok_begin + rows - 1) / kv.page_tokens + 1);
+    if (LDS > LDS_MAX) return hipErrorInvalidValue;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)attention_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_MAX);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int q_tiles = (rows + AQ - 1) / AQ;
+    hipLaunchKernelGGL(attention_mfma_kernel, dim3(q_tiles * n_q), dim3(256), LDS, st, (const bf16_t*)q, (bf16_t*)out, n_q,
+                       tok_begin, rows, kv, q_tiles);
+    return hipGetLastError();
+}
+
+}  // namespace cake

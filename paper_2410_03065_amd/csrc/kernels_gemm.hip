@@ -1,6 +1,5 @@
-// bf16 MFMA kernels for gfx950: the four projection GEMMs of the decoder block and the
-// chunk-vs-prefix causal attention over paged KV (Sec. 3 "Attention and KV cache",
-// "Chunk Prefill": a chunk's queries attend to every cached key before and inside it).
+// bf16 MFMA GEMMs for gfx950: the four projections of the decoder block
+// (Sec. 3: Q = X W_Q, K = X W_K, V = X W_V, and the block's output and feed-forward products).
 //
 // MFMA shape used throughout: v_mfma_f32_32x32x16_bf16.  For D[32x32] += A[32x16] * B[16x32]
 // lane l supplies A[l%32][8*(l/32) .. +7] and B[8*(l/32) .. +7][l%32], and holds
@@ -263,178 +262,6 @@ hipError_t launch_gemm_mfma(int epi, const void* a, const void* w, const void* w
     if (epi == EPI_RESIDUAL_F32) return gemm_launch_cfg<EPI_RESIDUAL_F32>(cfg, A, W, W2, out, M, N, K, st);
     if (epi == EPI_STORE_F32) return gemm_launch_cfg<EPI_STORE_F32>(cfg, A, W, W2, out, M, N, K, st);
     return hipErrorInvalidValue;
-}
-
-// =====================================================================================
-// Attention: out[row][h*128 + :] = softmax_s(q_row . k_s / sqrt(128)) v_s over keys s <= tok_begin+row.
-//
-// Workgroup = 4 waves x 32 queries of one query head; keys are visited in tiles of 64.  The
-// score tile is formed transposed, S^T[key][query] = K[key][:] . Q[query][:], so that in the
-// accumulator a lane holds 32 keys of ONE query: the online-softmax row statistics are per-lane
-// scalars (one exchange with lane^32 for the max), and the probabilities are already in the
-// layout the next MFMA wants for its B operand, P^T[key][query].  The second product is
-// O^T[hd][query] += V^T[hd][key] * P^T[key][query], whose A operand reads the transposed V pages
-// directly (8 consecutive keys = 16 bytes).  The accumulator puts keys {0-3, 8-11} of each
-// 16-key step in the low half-wave and {4-7, 12-15} in the high one; the V^T operand is read
-// with the same permutation, which is legal because the contraction sums over keys.
-// =====================================================================================
-constexpr int AQ = 128;   // queries per workgroup
-constexpr int AK = 64;    // keys per tile
-constexpr int AHD = 128;  // head dim
-constexpr int KROW = AHD * 2;      // bytes per K row in LDS (swizzled 16-byte chunks)
-constexpr int VROW = AK * 2 + 8;   // bytes per V^T row in LDS (+8 pad: rows shift by two banks)
-
-__global__ void __launch_bounds__(256)
-attention_mfma_kernel(const bf16_t* __restrict__ q, bf16_t* __restrict__ out, int n_q, int tok_begin, int rows,
-                      KvView kv) {
-    __shared__ __attribute__((aligned(16))) unsigned char ldsK[AK * KROW];
-    __shared__ __attribute__((aligned(16))) unsigned char ldsV[AHD * VROW];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int lrow = lane & 31, lhalf = lane >> 5;
-    const int h = blockIdx.y;
-    const int g = h / (n_q / kv.n_kv);
-    const int q0 = blockIdx.x * AQ;                 // first query row of the workgroup
-    const int my_row = min(q0 + wave * 32 + lrow, rows - 1);
-    const int my_pos = tok_begin + my_row;          // this lane's query position
-    const int wg_last_pos = tok_begin + min(q0 + AQ, rows) - 1;
-    const int wave_first_pos = tok_begin + min(q0 + wave * 32, rows - 1);
-    const int pt = kv.page_tokens;
-
-    // Q^T operand: lane supplies q[my_row][16*ks + 8*lhalf .. +7]
-    bf16x8 qreg[AHD / 16];
-    {
-        const bf16_t* qp = q + (size_t(h) * rows + my_row) * AHD + 8 * lhalf;
-#pragma unroll
-        for (int ks = 0; ks < AHD / 16; ++ks) qreg[ks] = *(const bf16x8*)(qp + 16 * ks);
-    }
-
-    f32x16 o[4];
-#pragma unroll
-    for (int t = 0; t < 4; ++t)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) o[t][v] = 0.f;
-    float m_run = -INFINITY, l_part = 0.f;
-    const float sl2 = 0.08838834764831845f * 1.4426950408889634f;  // 1/sqrt(128) * log2(e)
-
-    const int n_tiles = wg_last_pos / AK + 1;
-    for (int kt = 0; kt < n_tiles; ++kt) {
-        const int key0 = kt * AK;
-        const int lpage = key0 / pt;
-        const int in_page0 = key0 - lpage * pt;
-        const bf16_t* page = (const bf16_t*)kv.pool +
-                             (size_t(kv.layer) * kv.n_physical_pages + kv.block_table[lpage]) * kv.page_elems();
-        const bf16_t* kp = page + (size_t(g) * pt + in_page0) * AHD;                       // [64][128]
-        const bf16_t* vp = page + size_t(kv.n_kv) * pt * AHD + size_t(g) * AHD * pt + in_page0;  // [128][pt]
-        __syncthreads();  // previous tile fully consumed
-        // K tile: 64 rows x 16 chunks of 16 B = 1024 chunks, 4 per thread
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            int idx = tid + 256 * i, row = idx >> 4, ch = idx & 15;
-            uint4 v = *(const uint4*)(kp + size_t(row) * AHD + ch * 8);
-            *(uint4*)(ldsK + row * KROW + ((ch ^ (row & 7)) << 4)) = v;
-        }
-        // V^T tile: 128 rows x 8 chunks of 16 B (8 keys) = 1024 chunks, 4 per thread
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            int idx = tid + 256 * i, row = idx >> 3, ch = idx & 7;
-            uint4 v = *(const uint4*)(vp + size_t(row) * pt + ch * 8);
-            uint2* dst = (uint2*)(ldsV + row * VROW + ch * 16);
-            dst[0] = make_uint2(v.x, v.y);
-            dst[1] = make_uint2(v.z, v.w);
-        }
-        __syncthreads();
-        if (key0 > tok_begin + min(q0 + wave * 32 + 31, rows - 1)) continue;  // tile entirely in this wave's future
-
-        // S^T = K Q^T : two 32-key tiles x 32 queries
-        f32x16 s[2];
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) s[t][v] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < AHD / 16; ++ks) {
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                int row = t * 32 + lrow, ch = 2 * ks + lhalf;
-                bf16x8 a = *(const bf16x8*)(ldsK + row * KROW + ((ch ^ (row & 7)) << 4));
-                s[t] = mfma32(a, qreg[ks], s[t]);
-            }
-        }
-        // causal mask (only tiles that reach past the wave's first query need it)
-        if (key0 + AK - 1 > wave_first_pos) {
-#pragma unroll
-            for (int t = 0; t < 2; ++t)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    int key = key0 + t * 32 + 8 * (v >> 2) + 4 * lhalf + (v & 3);
-                    if (key > my_pos) s[t][v] = -INFINITY;
-                }
-        }
-        float mx = m_run;
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[t][v] * sl2);
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        // every query sees key 0 in tile 0, so mx is finite from the first visited tile on
-        const float corr = exp2f(m_run - mx);
-        m_run = mx;
-        l_part *= corr;
-        bf16x8 p[4];
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                float e = exp2f(s[t][v] * sl2 - mx);
-                l_part += e;
-                p[2 * t + (v >> 3)][v & 7] = bf16_t(e);
-            }
-#pragma unroll
-        for (int t = 0; t < 4; ++t)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) o[t][v] *= corr;
-        // O^T += V^T P^T : 4 tiles of 32 head dims, 4 steps of 16 keys
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const unsigned char* vr = ldsV + (t * 32 + lrow) * VROW + j * 32 + 8 * lhalf;
-                uint2 lo = *(const uint2*)(vr);        // keys 16j + 4*lhalf + 0..3
-                uint2 hi = *(const uint2*)(vr + 16);   // keys 16j + 8 + 4*lhalf + 0..3
-                uint4 both = make_uint4(lo.x, lo.y, hi.x, hi.y);
-                bf16x8 a = *(bf16x8*)&both;
-                o[t] = mfma32(a, p[j], o[t]);
-            }
-        }
-    }
-    // finish: total row sum = this lane's partial + the partner half-wave's
-    float l_tot = l_part + __shfl_xor(l_part, 32, 64);
-    float inv = 1.0f / l_tot;
-    const int row = q0 + wave * 32 + lrow;
-    if (row < rows) {
-        bf16_t* op = out + size_t(row) * n_q * AHD + h * AHD;
-#pragma unroll
-        for (int t = 0; t < 4; ++t)
-#pragma unroll
-            for (int v4 = 0; v4 < 4; ++v4) {
-                bf16x4 w;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) w[e] = bf16_t(o[t][4 * v4 + e] * inv);
-                *(bf16x4*)(op + t * 32 + 8 * v4 + 4 * lhalf) = w;
-            }
-    }
-}
-
-bool attention_mfma_supported(int head_dim, int page_tokens) {
-    return head_dim == AHD && page_tokens % AK == 0;
-}
-
-hipError_t launch_attention_mfma(const void* q, void* out, int n_q, int tok_begin, int rows, const KvView& kv,
-                                 hipStream_t st) {
-    if (rows <= 0) return hipSuccess;
-    dim3 grid((rows + AQ - 1) / AQ, n_q), block(256);
-    hipLaunchKernelGGL(attention_mfma_kernel, grid, block, 0, st, (const bf16_t*)q, (bf16_t*)out, n_q, tok_begin, rows, kv);
-    return hipGetLastError();
 }
 
 }  // namespace cake

@@ -139,3 +139,34 @@ def test_attention(kind, path, tok_begin, rows):
     # bf16: probabilities and the output are rounded to bf16 (2^-9 each, relative to the row's scale)
     tol = 2e-5 if kind == "f32" else 1.2e-2
     assert _rel(got, want) < tol, _rel(got, want)
+
+
+def test_attention_and_page_write_above_2_and_4_gib():
+    """Physical pages whose byte offset in the pool has bit 31 / bit 32 set (a 4 GiB pool is what
+    the 32K-token benchmark uses): offsets must be formed in unsigned 64-bit arithmetic."""
+    import torch
+    import paper_2410_03065_amd as cake
+    shape = si.ModelShape("op-bf16-big", 1, 256, 32, 8, 128, 512, 64, "bf16", rope_theta=500000.0)
+    pt, T = 256, 1024
+    n_phys = 4200                                         # 1 MiB per page and layer -> 4.1 GiB pool
+    bt = np.array([2047, 2048, 4199, 3], dtype=np.int32)  # just below / above 2 GiB, above 4 GiB, low
+    w = si.make_weights(shape, seed=0)
+    eng = cake.Engine(shape, w, max_tokens=T, max_chunk=T, page_tokens=pt, block_table=bt, n_physical_pages=n_phys)
+    rng = np.random.default_rng(11)
+    nq, nkv, hd = shape.n_q, shape.n_kv, shape.head_dim
+    qkv = rng.standard_normal((T, (nq + 2 * nkv) * hd)).astype(np.float32)
+    q_dev = eng.op_rope_kv_write(torch.from_numpy(qkv).cuda(), 0, 0)
+    pos = np.arange(T)
+    cache = otf.KVCache(1, T, nkv, hd)
+    cache.k[0] = otf.rope(qkv[:, nq * hd:(nq + nkv) * hd].astype(np.float64).reshape(T, nkv, hd), pos, shape.rope_theta)
+    cache.v[0] = qkv[:, (nq + nkv) * hd:].astype(np.float64).reshape(T, nkv, hd)
+    cache = _rounded(cache, "bf16")
+    want_img = ostore.decode_words(ostore.pack_store(cache, pt, "bf16"), "bf16")
+    got_img = eng.pool_images(T)
+    assert np.abs(got_img - want_img).max() <= 2.0 ** -7 * np.abs(want_img).max()
+    got = eng.op_attention(q_dev, 0, 0).float().cpu().numpy().reshape(T, nq, hd)
+    q64 = q_dev.float().cpu().numpy().astype(np.float64).transpose(1, 0, 2)
+    # attention over what the pages actually hold (already checked against the oracle above)
+    held = ostore.unpack_store(eng.pool_raw(T).view(np.uint16), T, nkv, hd, pt, "bf16")
+    want = otf.attention(q64, held.k[0], held.v[0], pos, pos)
+    assert _rel(got, want) < 1.2e-2
