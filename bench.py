@@ -55,6 +55,22 @@ def cpu_baseline(shape, chunk, n_tokens, total_flops):
     }
 
 
+def recorded_traffic(kernel_class, default_workload):
+    """HBM bytes per launch of a kernel class as measured with rocprofv3 --pmc FETCH_SIZE /
+    WRITE_SIZE on the default workload (summary kept under profiles/); None if not recorded."""
+    if not default_workload:
+        return None
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_llama3_8b_32k.md")
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) == 3 and f[0] == "traffic_bytes_per_launch" and f[1] == kernel_class:
+                return int(f[2])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -67,6 +83,8 @@ def main():
     ap.add_argument("--gbps", type=float, default=4.0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with events in the timed region")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 1 GiB device-to-device copy, so a counter run has a kernel of known traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -85,6 +103,13 @@ def main():
     toks = si.make_tokens(T, shape.vocab, seed=1)
     total_flops = sum(cake.range_flops(shape, i * C, min(C, T - i * C)) for i in range(n))
     kv_bytes = n * (C // pt) * cake.page_image_bytes(shape, pt)
+
+    if args.calibrate_copy:   # 2^28 float32 read + written once: 1 GiB each way
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # stored KV = our own compute-only pass, copied into pinned host memory (the storage tier)
     eng.bidirectional_prefill(toks, C, args.gbps, mode="compute_only", log=False)
@@ -131,7 +156,8 @@ def main():
         s = stats[dom]
         achieved = s["flops"] / s["total_ns"] / 1e3
         roofline = {"kernel": dom, "bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS,
-                    "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                    "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                    "traffic": recorded_traffic(dom, (args.shape, T, C, pt) == ("llama3-8b-shape", 32768, 1024, 256)),
                     "avg_launch_us": kernels[dom]["avg_us"], "flops_per_launch": s["flops"] // s["launches"]}
 
     out = {
