@@ -162,3 +162,18 @@ def test_engine_refuses_to_run_without_gpu():
         pytest.skip("GPU present")
     with pytest.raises(cake.CakeError):
         cake.Engine(si.TINY.with_(vocab=64), None, max_tokens=64, max_chunk=64, page_tokens=64)
+
+
+def test_threaded_executor_under_thread_sanitizer(tmp_path):
+    """The two-worker executor with a fake backend (sleeps instead of GPU work), built with
+    ThreadSanitizer: exclusive claims, prefix/suffix sources, a failed load recomputed, no data race."""
+    import shutil
+    import subprocess
+    if shutil.which("g++") is None:
+        pytest.skip("no g++")
+    exe = str(tmp_path / "race_tsan")
+    src = os.path.join(ROOT, "tests", "host", "race_tsan.cpp")
+    subprocess.run(["g++", "-std=c++17", "-O1", "-g", "-fsanitize=thread", "-pthread", src, "-o", exe], check=True)
+    env = dict(os.environ, TSAN_OPTIONS="halt_on_error=1")
+    p = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=300)
+    assert p.returncode == 0 and "ok" in p.stdout, p.stdout + p.stderr
