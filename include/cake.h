@@ -136,11 +136,14 @@ typedef struct {
     int32_t f, b;    /* unclaimed chunks before the decision */
     int32_t m_star;  /* planned meet point (absolute chunk index) */
     int32_t claimed; /* chunk claimed, or -1 (wait) */
-    int32_t pad_;
+    int32_t f_off;   /* tokens of chunk f already claimed by compute before this look (0 unless steps are
+                        smaller than a chunk); when > 0 chunk f is compute's and the plan covers [f+1, b]
+                        with partial_ns added to the compute offset */
     uint64_t now_ns;
-    uint64_t o_c, o_l;                            /* predicted remaining ns of the chunk in flight on each side */
+    uint64_t o_c, o_l;                            /* predicted remaining ns of the work in flight on each side */
     uint64_t est_compute_ns, est_compute_flops;   /* throughput sample: last <= 4 computed chunks, or the prior */
     uint64_t est_load_ns, est_load_bytes;         /* last loaded chunk, or the prior */
+    uint64_t partial_ns;                          /* estimate of the unclaimed rest of chunk f when f_off > 0, else 0 */
 } cake_decision_log;
 
 typedef struct {
@@ -229,6 +232,47 @@ int32_t cake_bidirectional_prefill(cake_ctx* ctx, const int32_t* token_ids, int3
                                    const cake_kv_store* store, int32_t chunk, double gbps,
                                    int32_t mode, int32_t forced_m, const cake_kv* kv,
                                    cake_result* res);
+
+/* ---- adaptive scheduling (Sec. 4 Part 3; Sec. 5.7) ---------------------- */
+
+/* One request of a serving mix.  in: prompt, arrival, its own KV pages, and for a prefix-cached
+ * request the store that holds its KV.  out: when all of its KV was resident. */
+typedef struct {
+    const int32_t* token_ids;   /* host */
+    int32_t n_tokens;
+    int32_t has_prefix_cache;   /* 1: KV stored in `store`; produced by the bidirectional race */
+    uint64_t arrival_ns;        /* after the start of the call */
+    const cake_kv* kv;          /* this request's pages (block table + pool) */
+    const cake_kv_store* store; /* prefix-cached requests only */
+    uint64_t ttft_ns;           /* out: arrival -> all KV resident */
+    int32_t tokens_computed;    /* out */
+    int32_t tokens_loaded;      /* out */
+} cake_request;
+
+/* One engine step: how the token budget was dealt out. */
+typedef struct {
+    uint64_t start_ns, end_ns;  /* start = the instant the budget was dealt (requests with arrival <= start count) */
+    int32_t decode_tokens;      /* priority 1 (always 0 here: requests leave once their KV is complete) */
+    int32_t nonprefix_tokens;   /* priority 2 */
+    int32_t prefix_tokens;      /* priority 3: what was left for the prefix-cached request */
+    int32_t prefix_tok_begin;   /* first token of the prefix request's part, or -1 */
+    int32_t first_nonprefix_req; /* index of the first non-prefix request served, or -1 */
+    int32_t pad_;
+} cake_step_log;
+
+/* Serves a mix of requests on one GPU with the paper's adaptive mode: every engine step fills a
+ * budget of `token_budget` tokens in the order decoding requests, chunked prefill of requests
+ * without a stored prefix (arrival order), chunked prefill of the prefix-cached request with
+ * whatever budget is left; meanwhile that request's stored chunks of `fetch_chunk` tokens are
+ * loaded back-to-front at `gbps` and the two meet where the planner says, re-planned at every
+ * step from the rate the request actually gets.  At most one request may have has_prefix_cache.
+ * Blocking; returns when every request's KV is resident.  `res` describes the prefix request's
+ * race (decision log included); `steps`/`n_steps_out` may be NULL.
+ * Errors: CAKE_E_INVAL, CAKE_E_HIP, CAKE_E_STORE_MISS, CAKE_E_CAPACITY (logs truncated). */
+int32_t cake_adaptive_serve(cake_ctx* ctx, cake_request* requests, int32_t n_requests,
+                            int32_t token_budget, int32_t fetch_chunk, double gbps,
+                            cake_result* res, cake_step_log* steps, int32_t steps_cap,
+                            int32_t* n_steps_out);
 
 /* ---- small helpers ---------------------------------------------------- */
 

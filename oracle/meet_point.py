@@ -266,3 +266,37 @@ def simulate_claims(n_chunks: int, chunk_flops: Sequence[int], chunk_bytes: Sequ
     if f <= b:
         raise RuntimeError("claim protocol stalled with chunks left")
     return t, sources, log
+
+
+# --------------------------------------------------------------------------- #
+# adaptive scheduling mode (Sec. 4 Part 3; evaluated in Sec. 5.7)
+# --------------------------------------------------------------------------- #
+def fill_token_budget(budget: int, n_decoding: int, nonprefix_remaining: Sequence[int],
+                      prefix_offer: int):
+    """One engine step of the adaptive mode.  The budget is dealt out in the paper's order:
+    1. decoding requests (one token each), 2. chunked prefill of requests without a stored
+    prefix, oldest first, 3. chunked prefill of the prefix-cached request with what is left.
+    ``nonprefix_remaining`` lists the unprefilled tokens of the arrived non-prefix requests in
+    arrival order; ``prefix_offer`` is how many tokens the prefix request could use.
+    Returns (decode_tokens, [tokens per non-prefix request], prefix_tokens)."""
+    left = budget
+    dec = min(left, n_decoding)
+    left -= dec
+    grants = []
+    for rem in nonprefix_remaining:
+        g = min(left, rem)
+        grants.append(g)
+        left -= g
+    return dec, grants, min(left, prefix_offer)
+
+
+def expected_meet_point(f: int, b: int, f_off: int, o_c: int, o_l: int, partial_ns: int,
+                        est: Estimator, chunk_flops: Sequence[int], chunk_bytes: Sequence[int]) -> int:
+    """The split a planned look at the range [f, b] must log.  When the compute side has
+    already taken f_off tokens of chunk f, that chunk stays with it: the plan covers
+    [f+1, b] and the estimate of the rest of chunk f counts as compute-side offset."""
+    lo = f + 1 if f_off > 0 else f
+    ce = [est.est_compute(chunk_flops[i]) for i in range(lo, b + 1)]
+    le = [est.est_load(chunk_bytes[i]) for i in range(lo, b + 1)]
+    extra = partial_ns if f_off > 0 else 0
+    return lo + brute_force_meet_point(ce, le, o_c + extra, o_l)[0]

@@ -30,7 +30,7 @@ EXPORTS = [
     "cake_schedule_bandwidth_step", "cake_chunk_state", "cake_sync_compute", "cake_sync_load",
     "cake_range_flops", "cake_page_image_bytes", "cake_simulate_race", "cake_op_rmsnorm",
     "cake_op_gemm", "cake_op_gemm_residual", "cake_op_gemm_swiglu", "cake_op_rope_kv_write",
-    "cake_op_attention", "cake_profile_enable", "cake_profile_read",
+    "cake_op_attention", "cake_profile_enable", "cake_profile_read", "cake_adaptive_serve",
 ]
 KERNEL_CLASSES = ["embed", "rmsnorm", "gemm_qkv", "rope_kv", "attention", "gemm_o", "gemm_gateup", "gemm_down"]
 
@@ -71,9 +71,21 @@ class ChunkLog(C.Structure):
 
 class DecisionLog(C.Structure):
     _fields_ = [("who", C.c_int32), ("f", C.c_int32), ("b", C.c_int32), ("m_star", C.c_int32),
-                ("claimed", C.c_int32), ("pad_", C.c_int32), ("now_ns", C.c_uint64), ("o_c", C.c_uint64),
+                ("claimed", C.c_int32), ("f_off", C.c_int32), ("now_ns", C.c_uint64), ("o_c", C.c_uint64),
                 ("o_l", C.c_uint64), ("est_compute_ns", C.c_uint64), ("est_compute_flops", C.c_uint64),
-                ("est_load_ns", C.c_uint64), ("est_load_bytes", C.c_uint64)]
+                ("est_load_ns", C.c_uint64), ("est_load_bytes", C.c_uint64), ("partial_ns", C.c_uint64)]
+
+
+class Request(C.Structure):
+    _fields_ = [("token_ids", C.c_void_p), ("n_tokens", C.c_int32), ("has_prefix_cache", C.c_int32),
+                ("arrival_ns", C.c_uint64), ("kv", C.c_void_p), ("store", C.c_void_p), ("ttft_ns", C.c_uint64),
+                ("tokens_computed", C.c_int32), ("tokens_loaded", C.c_int32)]
+
+
+class StepLog(C.Structure):
+    _fields_ = [("start_ns", C.c_uint64), ("end_ns", C.c_uint64), ("decode_tokens", C.c_int32),
+                ("nonprefix_tokens", C.c_int32), ("prefix_tokens", C.c_int32), ("prefix_tok_begin", C.c_int32),
+                ("first_nonprefix_req", C.c_int32), ("pad_", C.c_int32)]
 
 
 class Result(C.Structure):
@@ -122,6 +134,7 @@ def load_library():
         "cake_page_image_bytes": (u64, [P(ModelDesc), i32]),
         "cake_simulate_race": (i32, [i32, vp, vp, vp, vp, u64, u64, u64, u64, i32, i32, i32, vp, P(u64),
                                      P(DecisionLog), i32, P(i32)]),
+        "cake_adaptive_serve": (i32, [vp, P(Request), i32, i32, i32, dbl, P(Result), P(StepLog), i32, P(i32)]),
         "cake_profile_enable": (i32, [vp, i32]),
         "cake_profile_read": (i32, [vp, P(KernelStats)]),
         "cake_op_rmsnorm": (i32, [vp, vp, vp, vp, i32, i32]),
@@ -158,7 +171,7 @@ def plan_meet_point(compute_ns, load_ns, compute_offset_ns=0, load_offset_ns=0):
 
 
 def _decisions_to_list(arr, n):
-    keys = [f[0] for f in DecisionLog._fields_ if f[0] != "pad_"]
+    keys = [f[0] for f in DecisionLog._fields_]
     return [{k: getattr(arr[i], k) for k in keys} for i in range(n)]
 
 
@@ -401,6 +414,58 @@ class Engine:
             out.chunks = [{k: getattr(chunks[i], k) for k in ck} for i in range(min(n, res.n_chunks))]
             out.decisions = _decisions_to_list(dec, res.n_decisions)
         return out
+
+    def new_kv(self, n_tokens):
+        """A further KV pool + block table of this shape (one per concurrent request)."""
+        torch = self.torch
+        n_log = (n_tokens + self.page_tokens - 1) // self.page_tokens
+        bt_host = np.arange(n_log, dtype=np.int32)
+        bt_dev = torch.from_numpy(bt_host).to(self.dev)
+        pool = torch.zeros((self.shape.n_layers, n_log, self.layer_page_elems), dtype=self.tdtype, device=self.dev)
+        kv = Kv(pool.data_ptr(), bt_host.ctypes.data, bt_dev.data_ptr(), self.page_tokens, n_log, n_log)
+        self._tensors.append((bt_host, bt_dev, pool))
+        return kv, pool
+
+    def adaptive_serve(self, requests, token_budget, fetch_chunk, gbps):
+        """requests: list of dicts {tokens, arrival_ns, prefix (bool), kv (Kv or None = the engine's own)}.
+        Returns (PrefillResult for the prefix request, per-request dicts, step list)."""
+        n = len(requests)
+        arr = (Request * n)()
+        keep = []
+        for i, r in enumerate(requests):
+            ids = self._ids(r["tokens"])
+            keep.append(ids)
+            kv = r.get("kv") or self.kv
+            keep.append(kv)
+            arr[i].token_ids = ids.ctypes.data
+            arr[i].n_tokens = len(ids)
+            arr[i].has_prefix_cache = 1 if r.get("prefix") else 0
+            arr[i].arrival_ns = int(r.get("arrival_ns", 0))
+            arr[i].kv = C.addressof(kv)
+            arr[i].store = C.addressof(self.store) if r.get("prefix") else None
+        nc = max(1, max((len(r["tokens"]) + fetch_chunk - 1) // fetch_chunk for r in requests))
+        res = Result()
+        chunks = (ChunkLog * nc)()
+        total_tokens = sum(len(r["tokens"]) for r in requests)
+        scap = 4 * (total_tokens // max(1, min(token_budget, 64)) + n) + 64
+        dcap = 4 * scap
+        dec = (DecisionLog * dcap)()
+        steps = (StepLog * scap)()
+        res.chunks, res.chunks_cap, res.decisions, res.decisions_cap = chunks, nc, dec, dcap
+        ns = C.c_int32()
+        rc = self.lib.cake_adaptive_serve(self.ctx, arr, n, token_budget, fetch_chunk, float(gbps), C.byref(res), steps,
+                                          scap, C.byref(ns))
+        self._check(rc, "cake_adaptive_serve", allow=(E_CAPACITY,))
+        out = PrefillResult(res.meet_point, res.ttft_ns, res.n_chunks, res.load_failed_chunk, res.compute_busy_ns,
+                            res.compute_device_ns, res.compute_flops, res.load_busy_ns, res.load_bytes, status=rc)
+        ck = [f[0] for f in ChunkLog._fields_]
+        out.chunks = [{k: getattr(chunks[i], k) for k in ck} for i in range(res.n_chunks)]
+        out.decisions = _decisions_to_list(dec, res.n_decisions)
+        per_req = [dict(ttft_ns=arr[i].ttft_ns, tokens_computed=arr[i].tokens_computed, tokens_loaded=arr[i].tokens_loaded)
+                   for i in range(n)]
+        sk = [f[0] for f in StepLog._fields_ if f[0] != "pad_"]
+        step_list = [{k: getattr(steps[i], k) for k in sk} for i in range(ns.value)]
+        return out, per_req, step_list
 
     def set_bandwidth(self, gbps):
         self._check(self.lib.cake_set_bandwidth(self.ctx, float(gbps)), "cake_set_bandwidth")

@@ -2,6 +2,7 @@
 // See include/cake.h for the contract of every entry point.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <atomic>
 #include <cmath>
 #include <cstdarg>
@@ -433,6 +434,213 @@ int32_t cake_bidirectional_prefill(cake_ctx* c, const int32_t* token_ids, int32_
         return rc;
     }
     if ((res->chunks && res->chunks_cap < n) || ex.core.log_overflow) return CAKE_E_CAPACITY;
+    return CAKE_OK;
+}
+
+// Adaptive mode (Sec. 4 Part 3): the engine loop that deals a token budget out per step.
+int32_t cake_adaptive_serve(cake_ctx* c, cake_request* reqs, int32_t n_reqs, int32_t token_budget, int32_t fetch_chunk,
+                            double gbps, cake_result* res, cake_step_log* steps, int32_t steps_cap,
+                            int32_t* n_steps_out) {
+    if (!c || !reqs || n_reqs <= 0 || !res) return CAKE_E_INVAL;
+    if (token_budget <= 0 || token_budget > c->max_chunk) return fail(c, CAKE_E_INVAL, "token_budget %d outside (0, %d]", token_budget, c->max_chunk);
+    int P = -1;
+    for (int i = 0; i < n_reqs; ++i) {
+        cake_request& r = reqs[i];
+        if (!r.token_ids || r.n_tokens <= 0 || r.n_tokens > c->max_tokens) return fail(c, CAKE_E_INVAL, "request %d: bad prompt", i);
+        int rc = check_kv(c, r.kv, r.n_tokens);
+        if (rc != CAKE_OK) return rc;
+        for (int t = 0; t < r.n_tokens; ++t)
+            if (r.token_ids[t] < 0 || r.token_ids[t] >= c->m.vocab) return fail(c, CAKE_E_INVAL, "request %d: token id outside the vocabulary", i);
+        if (r.has_prefix_cache) {
+            if (P >= 0) return fail(c, CAKE_E_INVAL, "more than one prefix-cached request");
+            P = i;
+        }
+        r.ttft_ns = 0; r.tokens_computed = 0; r.tokens_loaded = 0;
+    }
+    std::vector<int32_t> tb, tc;
+    std::vector<uint64_t> flops, bytes;
+    Executor ex;
+    int nc = 0;
+    if (P >= 0) {
+        const cake_request& r = reqs[P];
+        if (!r.store || !r.store->base) return fail(c, CAKE_E_INVAL, "prefix request without a store");
+        if (fetch_chunk <= 0 || fetch_chunk % r.kv->page_tokens) return fail(c, CAKE_E_INVAL, "fetch_chunk must be a multiple of page_tokens");
+        if (r.store->page_tokens != r.kv->page_tokens || r.store->page_stride_bytes < cake::page_image_bytes(c->m, r.kv->page_tokens))
+            return fail(c, CAKE_E_INVAL, "store does not match the page layout");
+        if (!(gbps > 0)) return fail(c, CAKE_E_INVAL, "gbps must be positive");
+        nc = (r.n_tokens + fetch_chunk - 1) / fetch_chunk;
+        tb.resize(nc); tc.resize(nc); flops.resize(nc); bytes.resize(nc);
+        const uint64_t image = cake::page_image_bytes(c->m, r.kv->page_tokens);
+        for (int i = 0; i < nc; ++i) {
+            tb[i] = i * fetch_chunk;
+            tc[i] = std::min(fetch_chunk, r.n_tokens - tb[i]);
+            flops[i] = cake::range_flops(c->m, tb[i], tc[i]);
+            bytes[i] = uint64_t((tc[i] + r.kv->page_tokens - 1) / r.kv->page_tokens) * image;
+        }
+    }
+    c->status.reset(new std::atomic<int32_t>[std::max(nc, 1)]);
+    c->n_status = nc;
+    for (int i = 0; i < nc; ++i) c->status[i].store(CAKE_CHUNK_EMPTY);
+    c->gbps.store(gbps > 0 ? gbps : 0.0);
+    ex.core.est.prior_c_ns = c->tun.prior_compute_ns;
+    ex.core.est.prior_c_flops = c->tun.prior_compute_flops;
+    ex.core.est.prior_l_ns = 1000000000ull;
+    ex.core.est.prior_l_bytes = gbps > 0 ? std::max<uint64_t>(1, uint64_t(gbps * 1e9)) : 4000000000ull;
+    ex.core.init(nc, flops.data(), bytes.data(), CAKE_BIDIR, 0);
+    ex.core.tok_begin = tb.data(); ex.core.tok_count = tc.data(); ex.core.model = &c->m;
+    ex.core.log = res->decisions;
+    ex.core.log_cap = res->decisions ? res->decisions_cap : 0;
+    ex.status = c->status.get();
+    ex.tok_begin = tb.data(); ex.tok_count = tc.data();
+    ex.chunk_log.assign(size_t(nc), cake_chunk_log{CAKE_SRC_NONE, 0, 0, 0, 0, 0, 0});
+    HipBackend be(c, P >= 0 ? reqs[P].store : nullptr, P >= 0 ? reqs[P].kv : nullptr, tb.data(), tc.data());
+
+    // requests in arrival order (stable)
+    std::vector<int> order(n_reqs);
+    for (int i = 0; i < n_reqs; ++i) order[i] = i;
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return reqs[a].arrival_ns < reqs[b].arrival_ns; });
+    std::vector<int32_t> next_tok(n_reqs, 0);
+    std::vector<char> done(n_reqs, 0);
+    int n_done = 0, n_steps = 0, hard = CAKE_OK;
+    bool steps_overflow = false, loader_started = false;
+    std::thread loader;
+    uint64_t prefix_compute_end = 0, starved_ns = 0;
+    ex.t0 = mono_ns();
+
+    struct Part { int req, first, count; };
+    std::vector<Part> parts;
+    while (n_done < n_reqs && hard == CAKE_OK) {
+        uint64_t now = ex.now();
+        if (P >= 0 && !loader_started && reqs[P].arrival_ns <= now) {
+            loader = std::thread([&] { ex.worker(W_LOAD, be); });
+            loader_started = true;
+        }
+        // ---- deal the budget out: (1) decoding requests: none, a request leaves once its KV is
+        // complete; (2) prefill of requests without a stored prefix, oldest first; (3) the rest to
+        // the prefix-cached request, as far as the plan gives it to the compute side
+        parts.clear();
+        int left = token_budget, np_tokens = 0, first_np = -1;
+        for (int k = 0; k < n_reqs && left > 0; ++k) {
+            int i = order[k];
+            if (i == P || done[i] || reqs[i].arrival_ns > now) continue;
+            int nt = std::min(left, reqs[i].n_tokens - next_tok[i]);
+            parts.push_back({i, next_tok[i], nt});
+            if (first_np < 0) first_np = i;
+            left -= nt; np_tokens += nt;
+        }
+        int got = 0, first = -1;
+        const bool prefix_live = P >= 0 && !done[P] && reqs[P].arrival_ns <= now;
+        if (prefix_live && left > 0) {
+            std::lock_guard<std::mutex> g(ex.mu);
+            got = ex.core.claim_front(now, left, &first);
+            if (got > 0) { ++ex.gen; ex.cv.notify_all(); }
+        }
+        if (got > 0) parts.push_back({P, first, got});
+
+        if (parts.empty()) {
+            // idle: the prefix request may be finished by the loader, or nothing has arrived yet
+            std::unique_lock<std::mutex> lk(ex.mu);
+            if (prefix_live && ex.core.range_empty() && !ex.core.w[W_LOAD].busy) {
+                uint64_t end = prefix_compute_end;
+                for (int i = 0; i < nc; ++i) if (ex.chunk_log[i].source == CAKE_SRC_LOAD) end = std::max(end, ex.chunk_log[i].end_ns);
+                reqs[P].ttft_ns = end - reqs[P].arrival_ns;
+                done[P] = 1; ++n_done;
+                continue;
+            }
+            if (ex.first_error != CAKE_OK) { hard = ex.first_error; break; }
+            uint64_t wake = ~uint64_t(0);
+            for (int i = 0; i < n_reqs; ++i)
+                if (!done[i] && reqs[i].arrival_ns > now) wake = std::min(wake, reqs[i].arrival_ns);
+            const uint64_t seen = ex.gen;
+            if (wake == ~uint64_t(0)) ex.cv.wait(lk, [&] { return ex.gen != seen || ex.first_error != CAKE_OK; });
+            else ex.cv.wait_for(lk, std::chrono::nanoseconds(wake - now), [&] { return ex.gen != seen || ex.first_error != CAKE_OK; });
+            continue;
+        }
+        // ---- run the step
+        const uint64_t t_start = ex.now();
+        for (const Part& p : parts) {
+            const cake_request& r = reqs[p.req];
+            if (hipMemcpyAsync(c->d_ids + p.first, r.token_ids + p.first, size_t(p.count) * 4, hipMemcpyHostToDevice, c->cs) != hipSuccess) { hard = CAKE_E_HIP; break; }
+            int rc = enqueue_prefill(c, p.first, p.count, r.kv);
+            if (rc != CAKE_OK) { hard = rc; break; }
+        }
+        if (hard == CAKE_OK && hipStreamSynchronize(c->cs) != hipSuccess) hard = fail(c, CAKE_E_HIP, "compute stream failed in an adaptive step");
+        const uint64_t t_end = ex.now();
+        if (hard != CAKE_OK) break;
+        for (const Part& p : parts) {
+            if (p.req == P) continue;
+            next_tok[p.req] += p.count;
+            reqs[p.req].tokens_computed += p.count;
+            if (next_tok[p.req] == reqs[p.req].n_tokens) {
+                reqs[p.req].ttft_ns = t_end - reqs[p.req].arrival_ns;
+                done[p.req] = 1; ++n_done;
+            }
+        }
+        if (prefix_live) {
+            std::lock_guard<std::mutex> g(ex.mu);
+            if (got > 0) {
+                // the sample spans the steps since the request last got tokens: the rate it actually gets
+                ex.core.complete_front(t_end - t_start + starved_ns, cake::range_flops(c->m, first, got));
+                starved_ns = 0;
+                reqs[P].tokens_computed += got;
+                prefix_compute_end = t_end;
+                // chunks the compute side has now finished
+                for (int i = 0; i < nc; ++i) {
+                    if (ex.chunk_log[i].source != CAKE_SRC_NONE) continue;
+                    const bool finished = i < ex.core.f;
+                    if (!finished) break;
+                    cake_chunk_log& cl = ex.chunk_log[i];
+                    cl.source = CAKE_SRC_COMPUTE; cl.tok_begin = tb[i]; cl.tok_count = tc[i];
+                    cl.start_ns = t_start; cl.end_ns = t_end; cl.work = flops[i]; cl.device_ns = 0;
+                    c->status[i].store(CAKE_CHUNK_RESIDENT);
+                }
+            } else {
+                starved_ns += t_end - t_start;   // a step the prefix request got nothing of
+            }
+            ++ex.gen;
+            ex.cv.notify_all();
+        }
+        if (steps) {
+            if (n_steps < steps_cap) {
+                cake_step_log& sl = steps[n_steps];
+                sl.start_ns = now; sl.end_ns = t_end; sl.decode_tokens = 0; sl.nonprefix_tokens = np_tokens;
+                sl.prefix_tokens = got; sl.prefix_tok_begin = got > 0 ? first : -1; sl.first_nonprefix_req = first_np; sl.pad_ = 0;
+            } else steps_overflow = true;
+        }
+        ++n_steps;
+    }
+    if (hard != CAKE_OK) {
+        std::lock_guard<std::mutex> g(ex.mu);
+        if (ex.first_error == CAKE_OK) ex.first_error = hard;
+        ++ex.gen;
+        ex.cv.notify_all();
+    }
+    if (loader_started) loader.join();
+    if (hard == CAKE_OK && ex.first_error != CAKE_OK) hard = ex.first_error;
+    (void)hipStreamSynchronize(c->cs);
+    c->step_after = -1;
+
+    res->n_chunks = nc;
+    res->n_decisions = ex.core.log_n;
+    res->load_failed_chunk = ex.load_failed_chunk;
+    res->ttft_ns = P >= 0 ? reqs[P].ttft_ns : 0;
+    res->meet_point = 0;
+    res->compute_busy_ns = res->compute_device_ns = res->compute_flops = res->load_busy_ns = res->load_bytes = 0;
+    for (int i = 0; i < nc; ++i) {
+        const cake_chunk_log& cl = ex.chunk_log[i];
+        if (cl.source == CAKE_SRC_COMPUTE) { ++res->meet_point; res->compute_flops += cl.work; }
+        else if (cl.source == CAKE_SRC_LOAD) {
+            res->load_busy_ns += cl.end_ns - cl.start_ns; res->load_bytes += cl.work;
+            reqs[P].tokens_loaded += tc[i];
+        }
+        if (res->chunks && i < res->chunks_cap) res->chunks[i] = cl;
+    }
+    if (n_steps_out) *n_steps_out = std::min(n_steps, steps ? steps_cap : n_steps);
+    if (hard != CAKE_OK) {
+        if (c->err.empty()) fail(c, hard, "adaptive run ended with status %d", hard);
+        return hard;
+    }
+    if ((res->chunks && res->chunks_cap < nc) || ex.core.log_overflow || steps_overflow) return CAKE_E_CAPACITY;
     return CAKE_OK;
 }
 

@@ -58,6 +58,21 @@ inline uint64_t muldiv(uint64_t a, uint64_t b, uint64_t d) {
     return q > kCostCap ? kCostCap : uint64_t(q);
 }
 
+inline uint64_t range_flops(const cake_model_desc& m, int64_t t0, int64_t cnt) {
+    unsigned __int128 hq = (unsigned __int128)m.n_q_heads * m.head_dim, hkv = (unsigned __int128)m.n_kv_heads * m.head_dim;
+    unsigned __int128 d = m.d_model, ff = m.ffn_dim, L = m.n_layers;
+    unsigned __int128 p_lin = L * (d * hq + 2 * d * hkv + hq * d + 3 * d * ff);
+    unsigned __int128 n = cnt;
+    unsigned __int128 pairs = (unsigned __int128)t0 * n + n * (n + 1) / 2;
+    unsigned __int128 r = 2 * p_lin * n + L * 4 * hq * pairs;
+    return r > kCostCap ? kCostCap : uint64_t(r);
+}
+
+inline uint64_t page_image_bytes(const cake_model_desc& m, int page_tokens) {
+    uint64_t e = m.dtype == CAKE_F32 ? 4 : 2;
+    return uint64_t(m.n_layers) * 2 * m.n_kv_heads * page_tokens * m.head_dim * e;
+}
+
 // Running integer estimates (rules stated at cake_decision_log in cake.h).
 struct Estimator {
     uint64_t prior_c_ns = 1000000000ull, prior_c_flops = 500000000000000ull;
@@ -100,6 +115,12 @@ struct RaceCore {
     int mode = CAKE_BIDIR, forced_m = 0;
     const uint64_t* flops = nullptr;  // per chunk
     const uint64_t* bytes = nullptr;  // per chunk
+    // token-granular compute claims (adaptive mode): tokens of chunk f already claimed, and what is
+    // needed to price a partial chunk
+    int f_off = 0;
+    const int32_t* tok_begin = nullptr;
+    const int32_t* tok_count = nullptr;
+    const cake_model_desc* model = nullptr;
     Estimator est;
     struct Worker {
         bool busy = false, retired = false;
@@ -112,7 +133,7 @@ struct RaceCore {
     std::vector<uint64_t> ce, le, scratch;
 
     void init(int n_chunks, const uint64_t* fl, const uint64_t* by, int md, int fm) {
-        n = n_chunks; f = 0; b = n_chunks - 1; flops = fl; bytes = by; mode = md; forced_m = fm;
+        n = n_chunks; f = 0; b = n_chunks - 1; flops = fl; bytes = by; mode = md; forced_m = fm; f_off = 0;
         w[0] = Worker(); w[1] = Worker(); log_n = 0; log_overflow = false;
         if (mode == CAKE_COMPUTE_ONLY) w[W_LOAD].retired = true;
         if (mode == CAKE_LOAD_ONLY) w[W_COMPUTE].retired = true;
@@ -120,50 +141,106 @@ struct RaceCore {
     bool range_empty() const { return f > b; }
     bool all_done() const { return f > b && !w[0].busy && !w[1].busy; }
 
-    // A free worker looks at the range.  Returns the claimed chunk or -1 (wait).
-    int decide(int who, uint64_t now) {
-        if (f > b || w[who].retired || w[who].busy) return -1;
-        uint64_t D, F, LN, LB;
-        est.compute_state(&D, &F);
-        est.load_state(&LN, &LB);
-        uint64_t oc = (w[W_COMPUTE].busy && w[W_COMPUTE].pred_end > now) ? w[W_COMPUTE].pred_end - now : 0;
-        uint64_t ol = (w[W_LOAD].busy && w[W_LOAD].pred_end > now) ? w[W_LOAD].pred_end - now : 0;
-        int m_star;
-        if (mode == CAKE_COMPUTE_ONLY) m_star = n;
-        else if (mode == CAKE_LOAD_ONLY) m_star = 0;
-        else if (mode == CAKE_FORCED_SPLIT) m_star = forced_m;
-        else if (mode == CAKE_GREEDY || w[1 - who].retired) m_star = (who == W_COMPUTE) ? b + 1 : f;
+    struct Plan { int m_star; uint64_t oc, ol, D, F, LN, LB, partial; };
+
+    // Where should the sweeps meet, seen by worker `who` at `now`?  When compute has already taken
+    // part of chunk f (f_off > 0) that chunk is compute's: the plan covers [f+1, b] and the rest of
+    // chunk f is added to the compute side's offset.
+    Plan plan(int who, uint64_t now) {
+        Plan p{};
+        est.compute_state(&p.D, &p.F);
+        est.load_state(&p.LN, &p.LB);
+        p.oc = (w[W_COMPUTE].busy && w[W_COMPUTE].pred_end > now) ? w[W_COMPUTE].pred_end - now : 0;
+        p.ol = (w[W_LOAD].busy && w[W_LOAD].pred_end > now) ? w[W_LOAD].pred_end - now : 0;
+        const int lo = f_off > 0 ? f + 1 : f;   // first chunk the loader could still take
+        if (f_off > 0) p.partial = est.est_compute(range_flops(*model, tok_begin[f] + f_off, tok_count[f] - f_off));
+        if (mode == CAKE_COMPUTE_ONLY) p.m_star = n;
+        else if (mode == CAKE_LOAD_ONLY) p.m_star = lo;
+        else if (mode == CAKE_FORCED_SPLIT) p.m_star = forced_m > lo ? forced_m : lo;
+        else if (mode == CAKE_GREEDY || w[1 - who].retired) p.m_star = (who == W_COMPUTE) ? b + 1 : lo;
         else {
-            int cnt = b - f + 1;
-            ce.resize(cnt); le.resize(cnt);
+            int cnt = b - lo + 1;
+            ce.resize(cnt > 0 ? cnt : 0); le.resize(cnt > 0 ? cnt : 0);
             for (int k = 0; k < cnt; ++k) {
-                ce[k] = est.est_compute(flops[f + k]);
-                le[k] = est.est_load(bytes[f + k]);
+                ce[k] = est.est_compute(flops[lo + k]);
+                le[k] = est.est_load(bytes[lo + k]);
             }
             int m_rel = 0; uint64_t t = 0;
-            if (plan_meet_point(ce.data(), le.data(), cnt, oc, ol, &m_rel, &t, scratch) != CAKE_OK) {
+            if (cnt <= 0) m_rel = 0;
+            else if (plan_meet_point(ce.data(), le.data(), cnt, sat_add(p.oc, p.partial), p.ol, &m_rel, &t, scratch) != CAKE_OK) {
                 // sums beyond 2^63 ns: fall back to the greedy rule rather than fail the run
                 m_rel = (who == W_COMPUTE) ? cnt : 0;
             }
-            m_star = f + m_rel;
+            p.m_star = lo + m_rel;
         }
-        int f0 = f, b0 = b, claim = -1;
-        if (who == W_COMPUTE && f < m_star) claim = f++;
-        else if (who == W_LOAD && b >= m_star) claim = b--;
-        if (log) {
-            if (log_n < log_cap) {
-                cake_decision_log& d = log[log_n++];
-                d.who = who; d.f = f0; d.b = b0; d.m_star = m_star; d.claimed = claim; d.pad_ = 0;
-                d.now_ns = now; d.o_c = oc; d.o_l = ol;
-                d.est_compute_ns = D; d.est_compute_flops = F; d.est_load_ns = LN; d.est_load_bytes = LB;
-            } else log_overflow = true;
+        return p;
+    }
+
+    void record(int who, uint64_t now, const Plan& p, int f0, int b0, int off0, int claim) {
+        if (!log) return;
+        if (log_n < log_cap) {
+            cake_decision_log& d = log[log_n++];
+            d.who = who; d.f = f0; d.b = b0; d.m_star = p.m_star; d.claimed = claim; d.f_off = off0;
+            d.now_ns = now; d.o_c = p.oc; d.o_l = p.ol;
+            d.est_compute_ns = p.D; d.est_compute_flops = p.F; d.est_load_ns = p.LN; d.est_load_bytes = p.LB;
+            d.partial_ns = p.partial;
+        } else log_overflow = true;
+    }
+
+    // A free worker looks at the range.  Returns the claimed chunk or -1 (wait).  Compute claims
+    // the whole (rest of) chunk f; see claim_front for smaller compute steps.
+    int decide(int who, uint64_t now) {
+        if (f > b || w[who].retired || w[who].busy) return -1;
+        const Plan p = plan(who, now);
+        int f0 = f, b0 = b, off0 = f_off, claim = -1;
+        uint64_t cost = 0;
+        if (who == W_COMPUTE && f < p.m_star) {
+            cost = f_off > 0 ? p.partial : est.est_compute(flops[f]);
+            claim = f++;
+            f_off = 0;
+        } else if (who == W_LOAD && b >= p.m_star && !(b == f && f_off > 0)) {
+            cost = est.est_load(bytes[b]);
+            claim = b--;
         }
+        record(who, now, p, f0, b0, off0, claim);
         if (claim >= 0) {
             Worker& me = w[who];
             me.busy = true; me.inflight = claim; me.started = now;
-            me.pred_end = sat_add(now, who == W_COMPUTE ? est.est_compute(flops[claim]) : est.est_load(bytes[claim]));
+            me.pred_end = sat_add(now, cost);
         }
         return claim;
+    }
+
+    // Compute side, token granular: claims up to max_tokens tokens from the front of the range,
+    // never past the planned meet point and never past the end of chunk f.  Returns the number of
+    // tokens claimed (0 = wait) and their first token.  The compute worker is marked busy until
+    // complete_front().
+    int claim_front(uint64_t now, int max_tokens, int* first_token) {
+        if (f > b || w[W_COMPUTE].retired || w[W_COMPUTE].busy || max_tokens <= 0) return 0;
+        const Plan p = plan(W_COMPUTE, now);
+        const int f0 = f, b0 = b, off0 = f_off;
+        int got = 0;
+        if (f < p.m_star) {
+            got = tok_count[f] - f_off;
+            if (got > max_tokens) got = max_tokens;
+            *first_token = tok_begin[f] + f_off;
+            Worker& me = w[W_COMPUTE];
+            me.busy = true; me.inflight = f; me.started = now;
+            me.pred_end = sat_add(now, est.est_compute(range_flops(*model, *first_token, got)));
+            f_off += got;
+            if (f_off == tok_count[f]) { ++f; f_off = 0; }
+        }
+        record(W_COMPUTE, now, p, f0, b0, off0, got > 0 ? f0 : -1);
+        return got;
+    }
+
+    // The compute step holding a claim_front() part has ended; the sample is the wall time since
+    // the request last got tokens against its FLOPs in this step (the rate it actually gets when
+    // the GPU is shared).
+    void complete_front(uint64_t step_ns, uint64_t prefix_flops) {
+        w[W_COMPUTE].busy = false;
+        w[W_COMPUTE].inflight = -1;
+        est.add_compute(step_ns, prefix_flops);
     }
 
     // The worker's chunk in flight has ended at `now`.  A failed load gives the chunk
@@ -218,21 +295,6 @@ inline int simulate_race(RaceCore& core, const uint64_t* actual_c, const uint64_
     }
     *ttft = t;
     return core.range_empty() ? CAKE_OK : CAKE_E_STATE;
-}
-
-inline uint64_t range_flops(const cake_model_desc& m, int64_t t0, int64_t cnt) {
-    unsigned __int128 hq = (unsigned __int128)m.n_q_heads * m.head_dim, hkv = (unsigned __int128)m.n_kv_heads * m.head_dim;
-    unsigned __int128 d = m.d_model, ff = m.ffn_dim, L = m.n_layers;
-    unsigned __int128 p_lin = L * (d * hq + 2 * d * hkv + hq * d + 3 * d * ff);
-    unsigned __int128 n = cnt;
-    unsigned __int128 pairs = (unsigned __int128)t0 * n + n * (n + 1) / 2;
-    unsigned __int128 r = 2 * p_lin * n + L * 4 * hq * pairs;
-    return r > kCostCap ? kCostCap : uint64_t(r);
-}
-
-inline uint64_t page_image_bytes(const cake_model_desc& m, int page_tokens) {
-    uint64_t e = m.dtype == CAKE_F32 ? 4 : 2;
-    return uint64_t(m.n_layers) * 2 * m.n_kv_heads * page_tokens * m.head_dim * e;
 }
 
 }  // namespace cake

@@ -45,16 +45,20 @@ def _check_decisions(res, shape, T, C, pt):
     claimed = {0: [], 1: []}
     for d in res.decisions:
         e = mp.Estimator(d["est_compute_ns"], d["est_compute_flops"], d["est_load_ns"], d["est_load_bytes"])
-        ce = [e.est_compute(flops[i]) for i in range(d["f"], d["b"] + 1)]
-        le = [e.est_load(byts[i]) for i in range(d["f"], d["b"] + 1)]
-        assert d["m_star"] == d["f"] + mp.brute_force_meet_point(ce, le, d["o_c"], d["o_l"])[0], d
-        want_claim = d["f"] if (d["who"] == 0 and d["f"] < d["m_star"]) else \
-            d["b"] if (d["who"] == 1 and d["b"] >= d["m_star"]) else -1
+        assert d["m_star"] == mp.expected_meet_point(d["f"], d["b"], d["f_off"], d["o_c"], d["o_l"], d["partial_ns"],
+                                                     e, flops, byts), d
+        if d["f_off"] > 0:      # the logged estimate of the rest of chunk f is the estimator's, on the oracle's FLOP count
+            t0 = d["f"] * C + d["f_off"]
+            rest = mp.range_flops(shape.n_layers, shape.d_model, shape.n_q, shape.n_kv, shape.head_dim, shape.ffn,
+                                  t0, min((d["f"] + 1) * C, T))
+            assert d["partial_ns"] == e.est_compute(rest), d
+        loader_may = d["b"] >= d["m_star"] and not (d["b"] == d["f"] and d["f_off"] > 0)
+        want_claim = d["f"] if (d["who"] == 0 and d["f"] < d["m_star"]) else d["b"] if (d["who"] == 1 and loader_may) else -1
         assert d["claimed"] == want_claim, d
         if d["claimed"] >= 0:
             claimed[d["who"]].append(d["claimed"])
     m = res.meet_point
-    assert claimed[0] == list(range(m)) and claimed[1] == list(range(n - 1, m - 1, -1))
+    assert sorted(set(claimed[0])) == list(range(m)) and claimed[1] == list(range(n - 1, m - 1, -1))
     assert [c["source"] for c in res.chunks] == [0] * m + [1] * (n - m)
     for c, fl, by in zip(res.chunks, flops, byts):
         assert c["work"] == (fl if c["source"] == 0 else by)
@@ -285,3 +289,73 @@ def test_full_size_llama3_8b_32k_properties():
     assert r_b.ttft_ns < 1.02 * min(r_c.ttft_ns, r_l.ttft_ns)
     assert 0.97 * 4.0 <= r_l.achieved_gbps <= 4.0 * 1.001
     assert r_b.ttft_ns / r_c.ttft_ns + r_b.ttft_ns / r_l.ttft_ns < 1.10      # convex compute cost: sum <= 1 + discretisation
+
+
+def test_adaptive_scheduling_mix():
+    """Sec. 4 Part 3 / Sec. 5.7 at reduced size: one prefix-cached request races its loader while
+    requests without a stored prefix arrive; every step deals a 1024-token budget out in the order
+    (decode,) non-prefix prefill, prefix prefill.  Checks every request's KV against the oracle, the
+    budget order of every step against the oracle's rule, every planner decision by replay, and that
+    a bandwidth drop mid-run moves the meet point right."""
+    import paper_2410_03065_amd as cake
+    shape, T, C, pt, budget = BF_NARROW_GQA4, 8192, 1024, 256, 1024
+    w = si.make_weights(shape, seed=21)
+    eng = cake.Engine(shape, w, max_tokens=T, max_chunk=budget, page_tokens=pt)
+    toks = si.make_tokens(T, shape.vocab, seed=22)
+    ref = otf.prefill_chunked(w, shape, toks, C, kv_dtype="bf16")
+    images = ostore.pack_store(ref, pt, "bf16")
+    want = ostore.decode_words(images, "bf16")
+    eng.set_store(images)
+    r_c = eng.bidirectional_prefill(toks, C, 4.0, mode="compute_only")
+    kv_bytes = T * otf.kv_bytes_per_token(shape.n_layers, shape.n_kv, shape.head_dim, 2)
+    rate = kv_bytes / r_c.ttft_ns * 0.6            # a tier somewhat slower than this GPU computes
+    others = []
+    for j, (n_tok, arr_ms) in enumerate(((2048, 0.0), (1500, 1.0), (2048, 6.0))):
+        kv, pool = eng.new_kv(n_tok)
+        others.append(dict(tokens=si.make_tokens(n_tok, shape.vocab, seed=30 + j), arrival_ns=int(arr_ms * 1e6),
+                           prefix=False, kv=kv, pool=pool))
+    reqs = others + [dict(tokens=toks, arrival_ns=int(0.5e6), prefix=True)]
+
+    def run(step_after=None):
+        eng.clear_pool()
+        for o in others:
+            o["pool"].zero_()
+        if step_after is not None:
+            eng.schedule_bandwidth_step(step_after, rate / 10)
+        return eng.adaptive_serve(reqs, budget, C, rate)
+
+    res, per_req, steps = run()
+    # KV of every request
+    assert _errs(eng.pool_images(T), want).max() < TOL["bf16"]
+    m = res.meet_point
+    np.testing.assert_array_equal(eng.pool_raw(T)[m * (C // pt):].view(np.uint16), images[m * (C // pt):])
+    for o in others:
+        n_tok = len(o["tokens"])
+        r = otf.prefill_chunked(w, shape, o["tokens"], 512, kv_dtype="bf16")
+        w_img = ostore.decode_words(ostore.pack_store(r, pt, "bf16"), "bf16")
+        g_img = o["pool"].float().cpu().numpy().astype(np.float64).transpose(1, 0, 2).reshape(w_img.shape)
+        assert _errs(g_img, w_img).max() < TOL["bf16"]
+    assert per_req[3]["tokens_computed"] + per_req[3]["tokens_loaded"] == T
+    assert [p["tokens_computed"] for p in per_req[:3]] == [2048, 1500, 2048]
+    assert all(p["ttft_ns"] > 0 for p in per_req)
+    assert 0 < m < T // C
+    # budget order of every step, replayed with the oracle's rule
+    remaining = [len(o["tokens"]) for o in others]
+    arrival = [o["arrival_ns"] for o in others]
+    for s in steps:
+        arrived = [j for j in range(3) if arrival[j] <= s["start_ns"] and remaining[j] > 0]
+        dec, grants, pref = mp.fill_token_budget(budget, 0, [remaining[j] for j in arrived], 10**9)
+        assert s["decode_tokens"] == dec == 0
+        assert s["nonprefix_tokens"] == sum(grants)
+        assert s["prefix_tokens"] <= pref                      # the plan may give the prefix request less, never more
+        assert s["first_nonprefix_req"] == (arrived[0] if arrived else -1)
+        for j, g in zip(arrived, grants):
+            remaining[j] -= g
+    assert remaining == [0, 0, 0]
+    assert any(0 < s["prefix_tokens"] < budget for s in steps)  # partial steps happened
+    _check_decisions(res, shape, T, C, pt)
+    # bandwidth drop after the loader's 2nd chunk: more chunks end up computed
+    res2, _, _ = run(step_after=2)
+    assert _errs(eng.pool_images(T), want).max() < TOL["bf16"]
+    _check_decisions(res2, shape, T, C, pt)
+    assert res2.meet_point > res.meet_point

@@ -28,7 +28,9 @@ def test_library_exports_every_declared_symbol():
 
 def test_struct_sizes_match_the_header_layout():
     assert ctypes.sizeof(cake.ChunkLog) == 48
-    assert ctypes.sizeof(cake.DecisionLog) == 80
+    assert ctypes.sizeof(cake.DecisionLog) == 88
+    assert ctypes.sizeof(cake.Request) == 56
+    assert ctypes.sizeof(cake.StepLog) == 40
     assert ctypes.sizeof(cake.ModelDesc) == 40
     assert ctypes.sizeof(cake.Tuning) == 32
     assert ctypes.sizeof(cake.Kv) == 40
@@ -74,6 +76,7 @@ def _shape_costs(shape, T, C, page_tokens):
 def _same_log(lib_log, ora_log):
     assert len(lib_log) == len(ora_log)
     for a, b in zip(lib_log, ora_log):
+        assert a["f_off"] == 0 and a["partial_ns"] == 0        # whole-chunk claims only
         assert (a["who"], a["now_ns"], a["f"], a["b"], a["o_c"], a["o_l"], a["est_compute_ns"],
                 a["est_compute_flops"], a["est_load_ns"], a["est_load_bytes"], a["m_star"], a["claimed"]) == \
                (b.who, b.now, b.f, b.b, b.o_c, b.o_l, b.D, b.F, b.load_ns, b.load_bytes, b.m_star, b.claimed)

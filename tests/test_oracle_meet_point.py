@@ -179,3 +179,24 @@ def test_range_flops_matches_chunk_formula():
     # additivity over a ragged split is exact
     a = mp.range_flops(2, 8, 2, 1, 4, 12, 0, 7) + mp.range_flops(2, 8, 2, 1, 4, 12, 7, 10)
     assert a == mp.range_flops(2, 8, 2, 1, 4, 12, 0, 10)
+
+
+def test_token_budget_priority_order():
+    """Sec. 4 Part 3: decode first, then non-prefix prefill (oldest first), then the prefix request."""
+    assert mp.fill_token_budget(1024, 0, [], 5000) == (0, [], 1024)
+    assert mp.fill_token_budget(1024, 0, [4096], 5000) == (0, [1024], 0)
+    assert mp.fill_token_budget(1024, 0, [300], 5000) == (0, [300], 724)
+    assert mp.fill_token_budget(1024, 0, [300, 4096], 5000) == (0, [300, 724], 0)
+    assert mp.fill_token_budget(1024, 24, [300, 200], 100) == (24, [300, 200], 100)
+    assert mp.fill_token_budget(512, 600, [300], 100) == (512, [0], 0)
+    # the paper's utilisation example (Sec. 5.1): a 512 budget with 256 tokens taken by others leaves 256 (50 %)
+    assert mp.fill_token_budget(512, 0, [256], 10**6)[2] == 256
+
+
+def test_expected_meet_point_with_a_partial_chunk():
+    est = mp.Estimator(1, 1, 1, 1)
+    c, l = [10, 10, 10, 10], [9, 9, 9, 9]
+    assert mp.expected_meet_point(0, 3, 0, 0, 0, 0, est, c, l) == mp.brute_force_meet_point(c, l)[0] == 2
+    # 4 tokens-worth of chunk 0 already taken: chunk 0 is compute's, 6 ns of it left
+    assert mp.expected_meet_point(0, 3, 4, 0, 0, 6, est, c, l) == 1 + mp.brute_force_meet_point(c[1:], l[1:], 6, 0)[0]
+    assert mp.expected_meet_point(3, 3, 1, 0, 0, 5, est, c, l) == 4          # nothing left for the loader
