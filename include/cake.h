@@ -130,7 +130,9 @@ typedef struct {
 /* One record per look at the unclaimed range [f,b] by a free worker.  The
  * estimates the planner used are reproducible from these integers:
  *   compute estimate of chunk i = floor(flops_i * est_compute_ns / est_compute_flops)
- *   load estimate of chunk j    = floor(bytes_j * est_load_ns    / est_load_bytes)   */
+ *   load estimate of chunk j    = floor(bytes_j * est_load_ns    / est_load_bytes)
+ * (est_load_*: the last loaded chunk, or the progress of the chunk in flight once its first piece
+ * has been released, or the prior; with progress known, o_l = floor(bytes left * ns / bytes done)). */
 typedef struct {
     int32_t who;     /* cake_source of the worker */
     int32_t f, b;    /* unclaimed chunks before the decision */

@@ -44,6 +44,8 @@ struct cake_ctx {
     std::string err;
     std::unique_ptr<std::atomic<int32_t>[]> status;
     int n_status = 0;
+    // progress of the paced load in flight (written by the load thread, read by planners)
+    std::atomic<uint64_t> load_start_ns{0}, load_bytes_done{0};
     // per-kernel-class timing (compute thread only)
     bool prof_on = false;
     struct ProfRec { int cls; uint64_t flops, bytes; };
@@ -191,6 +193,8 @@ static int enqueue_load(cake_ctx* c, const cake_kv_store* st, int tok_begin, int
     if (p1 > st->n_pages) return fail(c, CAKE_E_STORE_MISS, "store holds %d pages, page %d requested", st->n_pages, p1 - 1);
     const uint64_t piece_max = c->tun.piece_bytes ? c->tun.piece_bytes : (4ull << 20);
     const uint64_t start = mono_ns();
+    c->load_bytes_done.store(0);
+    c->load_start_ns.store(start);
     double release = 0.0;  // ns after start at which the tier has delivered everything issued so far
     for (int p = p0; p < p1; ++p) {
         const char* img = (const char*)st->base + uint64_t(p) * st->page_stride_bytes;
@@ -206,6 +210,7 @@ static int enqueue_load(cake_ctx* c, const cake_kv_store* st, int tok_begin, int
                     wait_until_ns(start + uint64_t(release));
                 }
                 HIP_TRY(c, hipMemcpyAsync(dst + off, src + off, n, hipMemcpyHostToDevice, c->ls));
+                c->load_bytes_done.fetch_add(n, std::memory_order_relaxed);
             }
         }
     }
@@ -242,6 +247,13 @@ struct HipBackend : Backend {
     }
     void on_load_completed(int n_loaded) override {
         if (c->step_after >= 0 && n_loaded == c->step_after) c->gbps.store(c->step_gbps);
+    }
+    bool load_progress(uint64_t* elapsed_ns, uint64_t* bytes_done) override {
+        const uint64_t st = c->load_start_ns.load(), by = c->load_bytes_done.load(), now = mono_ns();
+        if (!st || now <= st) return false;
+        *elapsed_ns = now - st;
+        *bytes_done = by;
+        return by > 0;
     }
 };
 }  // namespace
@@ -532,6 +544,7 @@ int32_t cake_adaptive_serve(cake_ctx* c, cake_request* reqs, int32_t n_reqs, int
         const bool prefix_live = P >= 0 && !done[P] && reqs[P].arrival_ns <= now;
         if (prefix_live && left > 0) {
             std::lock_guard<std::mutex> g(ex.mu);
+            ex.refresh_load_progress(be);
             got = ex.core.claim_front(now, left, &first);
             if (got > 0) { ++ex.gen; ex.cv.notify_all(); }
         }

@@ -21,6 +21,8 @@ struct Backend {
     virtual int compute_chunk(int chunk, uint64_t* device_ns) = 0;
     virtual int load_chunk(int chunk) = 0;
     virtual void on_load_completed(int n_loaded_so_far) { (void)n_loaded_so_far; }
+    // Progress of the load in flight: ns since it started and bytes the tier has delivered so far.
+    virtual bool load_progress(uint64_t* elapsed_ns, uint64_t* bytes_done) { (void)elapsed_ns; (void)bytes_done; return false; }
 };
 
 inline uint64_t mono_ns() {
@@ -44,6 +46,13 @@ struct Executor {
 
     uint64_t now() const { return mono_ns() - t0; }
 
+    // call with the mutex held, before planning
+    void refresh_load_progress(Backend& be) {
+        uint64_t ns = 0, by = 0;
+        if (core.w[W_LOAD].busy && be.load_progress(&ns, &by) && by > 0 && ns > 0) { core.load_prog_ns = ns; core.load_prog_bytes = by; }
+        else { core.load_prog_ns = core.load_prog_bytes = 0; }
+    }
+
     void worker(int who, Backend& be) {
         std::unique_lock<std::mutex> lk(mu);
         for (;;) {
@@ -54,6 +63,7 @@ struct Executor {
                 // has landed: a failed load hands its chunk back to the range.
                 if (core.range_empty() && !core.w[1 - who].busy) return;
                 uint64_t seen = gen;
+                refresh_load_progress(be);
                 c = core.range_empty() ? -1 : core.decide(who, now());
                 if (c >= 0) break;
                 cv.wait(lk, [&] { return gen != seen || first_error != CAKE_OK; });

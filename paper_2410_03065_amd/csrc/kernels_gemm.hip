@@ -20,17 +20,18 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 // GEMM: out[M][N] = a[M][K] * w[N][K]^T, bf16 in, float32 accumulate.
 //
 // Workgroup tile BM x BN = (WAVES_M*WTM*32) x (WAVES_N*WTN*32); each wave owns WTM x WTN MFMA
-// tiles.  K is consumed in 32-deep slices held in a ring of STAGES LDS buffers that are filled
+// tiles.  K is consumed in BK-deep slices (32 or 64) held in a ring of STAGES LDS buffers that are filled
 // by direct global->LDS loads (global_load_lds_dwordx4: 64 lanes x 16 B land contiguously, so
 // the bank swizzle is applied by choosing which global chunk each lane fetches).  A slice row
-// is 64 B = four 16-byte chunks; chunk c of row r is stored at position c ^ ((r >> 2) & 3), so
-// the 16 rows that one quarter-wave reads with ds_read_b128 cover all 64 LDS banks once.
+// is 64 B or 128 B of 16-byte chunks; chunk c of row r is stored at c ^ ((r >> 2) & 3) resp.
+// c ^ ((r >> 1) & 7), so the 16 rows that one quarter-wave reads with ds_read_b128 cover all
+// 64 LDS banks once.  64-deep slices ask L2 for whole 128-byte lines (half as many requests).
 //
-// Software pipeline per slice (two 16-deep MFMA steps): while step 0's MFMAs issue, step 1's
-// operands are read; then the wave waits for the NEXT slice's loads (vmcnt), meets the other
-// waves at a bare s_barrier (no fence: a fence would drain every load in flight), refills the
-// buffer freed one slice ago, and runs step 1's MFMAs while reading the next slice's step 0
-// operands.  sched_group_barrier pins the 2-MFMA / 1-ds_read interleave.
+// Software pipeline per slice (BK/16 MFMA steps of depth 16): while a step's MFMAs issue, the
+// next step's operands are read; before the last step the wave waits for the NEXT slice's loads
+// (vmcnt), meets the other waves at a bare s_barrier (no fence: a fence would drain every load in
+// flight), refills the buffer freed one slice ago, and runs the last step's MFMAs while reading
+// the next slice's first operands.  sched_group_barrier pins the 2-MFMA / 1-ds_read interleave.
 //
 // The block index is remapped so that workgroups that share a weight panel (the tiles_m tiles
 // of one n-panel) sit on the same XCD and run at the same time: the panel is then fetched from
@@ -43,14 +44,15 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 #define CAKE_GLOBAL_AS __attribute__((address_space(1)))
 #define CAKE_LDS_AS __attribute__((address_space(3)))
 
-__device__ __forceinline__ int gemm_swz(int row) { return (row >> 2) & 3; }
+// 16 consecutive rows must fall into 16 different 16-byte slots of a 256-byte bank window
+template <int BK> __device__ __forceinline__ int gemm_swz(int row) { return BK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3); }
 
-template <int WTM, int WTN, int WAVES_M, int WAVES_N, int STAGES, int EPI>
+template <int WTM, int WTN, int WAVES_M, int WAVES_N, int BK, int STAGES, int EPI>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
 gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, const bf16_t* __restrict__ W2,
                  void* __restrict__ outv, int M, int N, int K, int tiles_m, int tiles_n) {
-    constexpr int BK = 32;
     constexpr int NW = WAVES_M * WAVES_N;
+    constexpr int KS = BK / 16;   // 16-deep MFMA steps per slice
     constexpr int BM = WAVES_M * WTM * 32, BN = WAVES_N * WTN * 32;
     constexpr int ROWB = BK * 2, CPR = BK / 8, RPL = 64 / CPR;
     constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB, STAGE = A_BYTES + B_BYTES;
@@ -79,7 +81,7 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
 #pragma unroll
     for (int i = 0; i < A_PER; ++i) {
         int row = (wave + i * NW) * RPL + lr;
-        ag[i] = A + size_t(min(m0 + row, M - 1)) * K + (lpos ^ gemm_swz(row)) * 8;
+        ag[i] = A + size_t(min(m0 + row, M - 1)) * K + (lpos ^ gemm_swz<BK>(row)) * 8;
     }
 #pragma unroll
     for (int i = 0; i < B_PER; ++i) {
@@ -93,7 +95,7 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
         } else {
             grow = n0 + row;
         }
-        bg[i] = src + size_t(grow) * K + (lpos ^ gemm_swz(row)) * 8;
+        bg[i] = src + size_t(grow) * K + (lpos ^ gemm_swz<BK>(row)) * 8;
     }
     auto issue = [&](int stage, int k0) {
         unsigned char* sa = lds + stage * STAGE;
@@ -115,16 +117,18 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    const int sw = gemm_swz(lrow);  // tile rows start at multiples of 32, so the swizzle depends on lrow only
-    const int koff0 = ((0 + lhalf) ^ sw) << 4, koff1 = ((2 + lhalf) ^ sw) << 4;
+    const int sw = gemm_swz<BK>(lrow);  // tile rows start at multiples of 32, so the swizzle depends on lrow only
+    int koff[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) koff[ks] = ((2 * ks + lhalf) ^ sw) << 4;
     const int a_row_off = (wm * WTM * 32 + lrow) * ROWB;
     const int b_row_off = A_BYTES + (wn * WTN * 32 + lrow) * ROWB;
-    auto rd = [&](bf16x8* a, bf16x8* bb, int stage, int koff) {
+    auto rd = [&](bf16x8* a, bf16x8* bb, int stage, int koffv) {
         const unsigned char* st = lds + stage * STAGE;
 #pragma unroll
-        for (int i = 0; i < WTM; ++i) a[i] = *(const bf16x8*)(st + a_row_off + i * 32 * ROWB + koff);
+        for (int i = 0; i < WTM; ++i) a[i] = *(const bf16x8*)(st + a_row_off + i * 32 * ROWB + koffv);
 #pragma unroll
-        for (int j = 0; j < WTN; ++j) bb[j] = *(const bf16x8*)(st + b_row_off + j * 32 * ROWB + koff);
+        for (int j = 0; j < WTN; ++j) bb[j] = *(const bf16x8*)(st + b_row_off + j * 32 * ROWB + koffv);
     };
     auto mm = [&](const bf16x8* a, const bf16x8* bb) {
 #pragma unroll
@@ -148,21 +152,26 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
     if (nk >= STAGES - 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((STAGES - 2) * PER_TILE));
     else asm volatile("s_waitcnt vmcnt(0)");
     __builtin_amdgcn_s_barrier();
-    bf16x8 a0[WTM], b0[WTN], a1[WTM], b1[WTN];
-    rd(a0, b0, 0, koff0);
+    bf16x8 opa[2][WTM], opb[2][WTN];   // operands of the current and the next step
+    rd(opa[0], opb[0], 0, koff[0]);
     for (int kt = 0; kt < nk; ++kt) {
         const int cur = kt % STAGES;
-        rd(a1, b1, cur, koff1);
-        mm(a0, b0);
-        interleave();
-        // slice kt+1 must have landed before phase B reads its first operands
+        // steps 0 .. KS-2: this step's MFMAs, next step's operands from the same slice
+#pragma unroll
+        for (int ks = 0; ks + 1 < KS; ++ks) {
+            rd(opa[(ks + 1) & 1], opb[(ks + 1) & 1], cur, koff[ks + 1]);
+            mm(opa[ks & 1], opb[ks & 1]);
+            interleave();
+        }
+        // slice kt+1 must have landed before the last step reads its first operands
         if (kt + STAGES - 1 <= nk) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((STAGES - 3) * PER_TILE));
         else asm volatile("s_waitcnt vmcnt(0)");
         __builtin_amdgcn_s_barrier();
         // every wave has finished reading slice kt-1: refill its buffer
         if (kt + STAGES - 1 < nk) issue((kt + STAGES - 1) % STAGES, (kt + STAGES - 1) * BK);
-        rd(a0, b0, (kt + 1) % STAGES, koff0);  // past the last slice this reads stale LDS that is never used
-        mm(a1, b1);
+        // past the last slice this reads stale LDS that is never used
+        rd(opa[0], opb[0], (kt + 1) % STAGES, koff[0]);
+        mm(opa[(KS - 1) & 1], opb[(KS - 1) & 1]);
         interleave();
     }
 
@@ -194,10 +203,9 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
 }
 
 // Tile configurations.  Chosen per GEMM by gemm_pick() from how well the grid fills 256 CUs.
-struct GemmCfg { int bm, bn, lds_bytes; };
+struct GemmCfg { int bm, bn; };
 enum { GCFG_256x256 = 0, GCFG_256x128 = 1, GCFG_128x128 = 2, GCFG_COUNT = 3 };
-static const GemmCfg kGemmCfg[GCFG_COUNT] = {
-    {256, 256, (256 + 256) * 64 * 5}, {256, 128, (256 + 128) * 64 * 4}, {128, 128, (128 + 128) * 64 * 4}};
+static const GemmCfg kGemmCfg[GCFG_COUNT] = {{256, 256}, {256, 128}, {128, 128}};
 
 static int out_cols_per_tile(int cfg, int epi) { return epi == EPI_SWIGLU ? kGemmCfg[cfg].bn / 2 : kGemmCfg[cfg].bn; }
 
@@ -224,12 +232,12 @@ static int gemm_pick(int epi, int M, int N, int K) {
     return best;
 }
 
-template <int WTM, int WTN, int WAVES_M, int WAVES_N, int STAGES, int EPI>
+template <int WTM, int WTN, int WAVES_M, int WAVES_N, int BK, int STAGES, int EPI>
 static hipError_t gemm_launch_t(const bf16_t* A, const bf16_t* W, const bf16_t* W2, void* out, int M, int N, int K,
                                 hipStream_t st) {
     constexpr int BM = WAVES_M * WTM * 32, BN = WAVES_N * WTN * 32;
-    constexpr int LDS = (BM + BN) * 64 * STAGES;
-    auto kern = gemm_mfma_kernel<WTM, WTN, WAVES_M, WAVES_N, STAGES, EPI>;
+    constexpr int LDS = (BM + BN) * BK * 2 * STAGES;
+    auto kern = gemm_mfma_kernel<WTM, WTN, WAVES_M, WAVES_N, BK, STAGES, EPI>;
     static bool attr_set = false;   // one flag per instantiation
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
@@ -245,10 +253,15 @@ static hipError_t gemm_launch_t(const bf16_t* A, const bf16_t* W, const bf16_t* 
 template <int EPI>
 static hipError_t gemm_launch_cfg(int cfg, const bf16_t* A, const bf16_t* W, const bf16_t* W2, void* out, int M, int N,
                                   int K, hipStream_t st) {
+    const long tiles128 = long((M + 127) / 128) * (N / (EPI == EPI_SWIGLU ? 64 : 128));
     switch (cfg) {
-        case GCFG_256x256: return gemm_launch_t<4, 2, 2, 4, 5, EPI>(A, W, W2, out, M, N, K, st);
-        case GCFG_256x128: return gemm_launch_t<4, 2, 2, 2, 4, EPI>(A, W, W2, out, M, N, K, st);
-        default: return gemm_launch_t<2, 2, 2, 2, 4, EPI>(A, W, W2, out, M, N, K, st);
+        case GCFG_256x256: return gemm_launch_t<4, 2, 2, 4, 32, 5, EPI>(A, W, W2, out, M, N, K, st);
+        case GCFG_256x128: return gemm_launch_t<4, 2, 2, 2, 32, 4, EPI>(A, W, W2, out, M, N, K, st);
+        default:
+            // one workgroup per CU at most: spend the whole LDS on a deep ring of 64-deep slices
+            // (96 KB in flight per CU); more tiles than CUs: 64 KB rings so two workgroups share a CU
+            if (tiles128 <= 256 && (K % 64) == 0) return gemm_launch_t<2, 2, 2, 2, 64, 4, EPI>(A, W, W2, out, M, N, K, st);
+            return gemm_launch_t<2, 2, 2, 2, 32, 4, EPI>(A, W, W2, out, M, N, K, st);
     }
 }
 

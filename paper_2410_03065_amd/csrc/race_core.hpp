@@ -127,6 +127,9 @@ struct RaceCore {
         uint64_t started = 0, pred_end = 0;
         int inflight = -1;
     } w[2];
+    // progress of the load in flight, if the executor can observe it (bytes the tier has delivered
+    // so far and the time that took); 0 bytes = unknown
+    uint64_t load_prog_ns = 0, load_prog_bytes = 0;
     cake_decision_log* log = nullptr;
     int log_cap = 0, log_n = 0;
     bool log_overflow = false;
@@ -152,6 +155,12 @@ struct RaceCore {
         est.load_state(&p.LN, &p.LB);
         p.oc = (w[W_COMPUTE].busy && w[W_COMPUTE].pred_end > now) ? w[W_COMPUTE].pred_end - now : 0;
         p.ol = (w[W_LOAD].busy && w[W_LOAD].pred_end > now) ? w[W_LOAD].pred_end - now : 0;
+        if (w[W_LOAD].busy && load_prog_bytes > 0 && w[W_LOAD].inflight >= 0) {
+            // the chunk in flight tells the tier's current rate sooner than its completion would
+            p.LN = load_prog_ns; p.LB = load_prog_bytes;
+            const uint64_t total = bytes[w[W_LOAD].inflight];
+            p.ol = total > load_prog_bytes ? muldiv(total - load_prog_bytes, load_prog_ns, load_prog_bytes) : 0;
+        }
         const int lo = f_off > 0 ? f + 1 : f;   // first chunk the loader could still take
         if (f_off > 0) p.partial = est.est_compute(range_flops(*model, tok_begin[f] + f_off, tok_count[f] - f_off));
         if (mode == CAKE_COMPUTE_ONLY) p.m_star = n;
@@ -163,7 +172,7 @@ struct RaceCore {
             ce.resize(cnt > 0 ? cnt : 0); le.resize(cnt > 0 ? cnt : 0);
             for (int k = 0; k < cnt; ++k) {
                 ce[k] = est.est_compute(flops[lo + k]);
-                le[k] = est.est_load(bytes[lo + k]);
+                le[k] = muldiv(bytes[lo + k], p.LN, p.LB);
             }
             int m_rel = 0; uint64_t t = 0;
             if (cnt <= 0) m_rel = 0;
@@ -247,6 +256,7 @@ struct RaceCore {
     // back to the range and retires the loader; a failed compute retires the compute side.
     void complete(int who, uint64_t now, bool failed) {
         Worker& me = w[who];
+        if (who == W_LOAD) load_prog_ns = load_prog_bytes = 0;
         int i = me.inflight;
         me.busy = false; me.inflight = -1;
         if (i < 0) return;
