@@ -103,7 +103,7 @@ class KernelStats(C.Structure):
 
 class Tuning(C.Structure):
     _fields_ = [("prior_compute_ns", C.c_uint64), ("prior_compute_flops", C.c_uint64), ("piece_bytes", C.c_uint64),
-                ("kernel_path", C.c_int32), ("gemm_config", C.c_int32)]
+                ("kernel_path", C.c_int32), ("gemm_config", C.c_int32), ("attn_variant", C.c_int32), ("pad_", C.c_int32)]
 
 
 def load_library():
@@ -373,8 +373,9 @@ class Engine:
             raise CakeError(rc, "%s: %s" % (what, self.lib.cake_last_error(self.ctx).decode()))
         return rc
 
-    def set_tuning(self, prior_compute_ns=0, prior_compute_flops=0, piece_bytes=0, kernel_path=0, gemm_config=0):
-        t = Tuning(prior_compute_ns, prior_compute_flops, piece_bytes, kernel_path, gemm_config)
+    def set_tuning(self, prior_compute_ns=0, prior_compute_flops=0, piece_bytes=0, kernel_path=0, gemm_config=0,
+                   attn_variant=0):
+        t = Tuning(prior_compute_ns, prior_compute_flops, piece_bytes, kernel_path, gemm_config, attn_variant, 0)
         self._check(self.lib.cake_set_tuning(self.ctx, C.byref(t)), "cake_set_tuning")
 
     def _ids(self, tokens):

@@ -39,7 +39,7 @@ struct cake_ctx {
     std::atomic<double> gbps{0.0};
     int step_after = -1;
     double step_gbps = 0.0;
-    cake_tuning tun{1000000000ull, 500000000000000ull, 4ull << 20, 0, 0};  // gemm_config 0 = automatic
+    cake_tuning tun{1000000000ull, 500000000000000ull, 4ull << 20, 0, 0, 0, 0};  // gemm_config 0 = automatic
     std::mutex err_mu;
     std::string err;
     std::unique_ptr<std::atomic<int32_t>[]> status;
@@ -108,7 +108,7 @@ static hipError_t gemm(cake_ctx* c, int epi, const void* a, const void* w, const
 
 static hipError_t attention(cake_ctx* c, const void* q, void* out, int tok_begin, int rows, const KvView& kv) {
     if (c->m.dtype == CAKE_BF16 && c->tun.kernel_path == 0 && attention_mfma_supported(kv.head_dim, kv.page_tokens))
-        return launch_attention_mfma(q, out, c->m.n_q_heads, tok_begin, rows, kv, c->cs);
+        return launch_attention_mfma(q, out, c->m.n_q_heads, tok_begin, rows, kv, c->cs, c->tun.attn_variant);
     return launch_attention_generic(c->m.dtype, q, out, c->m.n_q_heads, tok_begin, rows, kv, c->cs);
 }
 
@@ -333,6 +333,8 @@ int32_t cake_set_tuning(cake_ctx* c, const cake_tuning* t) {
     c->tun.kernel_path = t->kernel_path;
     if (t->gemm_config < 0 || t->gemm_config > 3) return fail(c, CAKE_E_INVAL, "gemm_config must be 0..3");
     c->tun.gemm_config = t->gemm_config;
+    if (t->attn_variant < 0 || t->attn_variant > 1) return fail(c, CAKE_E_INVAL, "attn_variant must be 0 or 1");
+    c->tun.attn_variant = t->attn_variant;
     return CAKE_OK;
 }
 

@@ -338,26 +338,336 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, bf16_t* __restrict__ out, in
     }
 }
 
+// =====================================================================================
+// Eight-wave variant: two waves per SIMD, so that one wave's softmax (vector ALU) runs while the
+// other's MFMAs occupy the matrix pipe -- a single wave cannot overlap the two (an MFMA holds its
+// own wave's issue for most of its duration).  A chunk of 1024 queries x 32 heads only offers
+// 4 waves of 32 queries per CU, so the second wave group takes the other half of the KEYS: waves
+// 0-3 visit key tiles 0, 2, 4, ..., waves 4-7 tiles 1, 3, 5, ... with private softmax state, and
+// the two partial results are merged through LDS at the end (softmax over a union of key sets:
+// rescale both to the common reference and add).
+//
+// LDS: K ring of 2 x (two 16 KB tiles) and V^T ring of 2 x (two 16 KB tiles).  K of a tile pair
+// is consumed one iteration before its V^T, so per iteration the V^T of pair i+1 and the K of
+// pair i+2 are fetched, each into the buffer its group finished with in the previous iteration.
+// Masked scores are -inf, the initial reference is a large FINITE negative: a row whose keys in
+// one half are all above the diagonal then keeps exp2(-inf - finite) = 0 everywhere (no inf - inf),
+// ends with O = 0, l = 0 and the initial reference, and the merge weighs that half by exactly 0.
+// =====================================================================================
+constexpr float A8_NEG = -1.0e30f;
+constexpr int A8_RING = 2 * A_KBYTES;        // one ring slot: group A's tile then group B's tile
+constexpr int A8_VBASE = 2 * A8_RING;        // V^T ring after the K ring
+constexpr int A8_TABLE = 4 * A8_RING;        // page offsets after both rings
+
+__global__ void __launch_bounds__(512)
+attention_mfma8_kernel(const bf16_t* __restrict__ q, bf16_t* __restrict__ out, int n_q, int tok_begin, int rows,
+                       KvView kv, int q_tiles) {
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave8 = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave = wave8 & 3, grp = wave8 >> 2;
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    const int G = kv.n_kv, r = n_q / G;
+    int g, rest;
+    if ((G & 7) == 0) {
+        const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3, gpx = G >> 3;
+        g = xcd + 8 * (idx % gpx);
+        rest = idx / gpx;
+    } else {
+        g = blockIdx.x % G;
+        rest = blockIdx.x / G;
+    }
+    const int h = g * r + rest % r;
+    const int q0 = (rest / r) * AQ;
+    const int pt = kv.page_tokens;
+
+    const int my_row = min(q0 + wave * 32 + lrow, rows - 1);
+    const int my_pos = tok_begin + my_row;
+    const int wave_first_pos = tok_begin + min(q0 + wave * 32, rows - 1);
+    const int wg_last_pos = tok_begin + min(q0 + AQ, rows) - 1;
+    const int n_tiles = wg_last_pos / AK + 1;
+    const int n_pairs = (n_tiles + 1) >> 1;
+    const int first_masked = (wave_first_pos + 1) / AK;   // first tile with a key some query of this wave must not see
+
+    bf16x8 qreg[AHD / 16];
+    {
+        const bf16_t* qp = q + (size_t(h) * rows + my_row) * AHD + 8 * lhalf;
+#pragma unroll
+        for (int ks = 0; ks < AHD / 16; ++ks) qreg[ks] = *(const bf16x8*)(qp + 16 * ks);
+    }
+    unsigned koffg[4], voffg[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int j = wave + 4 * i;
+        int krow = 4 * j + (lane >> 4), kpos = lane & 15;
+        koffg[i] = unsigned(krow * AHD + ((kpos ^ (krow & 15)) << 3)) * 2u;
+        int vrow = 8 * j + (lane >> 3), vpos = lane & 7;
+        voffg[i] = unsigned(vrow * pt + ((vpos ^ ((vrow >> 1) & 7)) << 3)) * 2u;
+    }
+    const int last_page = wg_last_pos / pt;
+    unsigned long long* pg_lds = (unsigned long long*)(lds + A8_TABLE);
+    {
+        const size_t layer_base = size_t(kv.layer) * kv.n_physical_pages;
+        const size_t page_bytes = kv.page_elems() * 2, k_head = size_t(g) * pt * AHD * 2;
+        for (int i = tid; i <= last_page; i += 512) pg_lds[i] = (layer_base + kv.block_table[i]) * page_bytes + k_head;
+    }
+    __syncthreads();
+    const unsigned long long k_to_v = (size_t(G - g) * pt * AHD + size_t(g) * AHD * pt) * 2;
+    // this wave group's tile of a pair; a tile past the end re-reads the last real one (it is fully masked)
+    auto tile_of = [&](int pair) { return min(2 * pair + grp, n_tiles - 1); };
+    auto page_base = [&](int tile, unsigned* in_page0) {
+        const int key0 = tile * AK, lpage = key0 / pt;
+        *in_page0 = unsigned(key0 - lpage * pt);
+        const unsigned long long off = pg_lds[lpage];
+        const unsigned long long lo = (unsigned)__builtin_amdgcn_readfirstlane((int)unsigned(off));
+        const unsigned long long hi = (unsigned)__builtin_amdgcn_readfirstlane((int)unsigned(off >> 32));
+        return (const char*)kv.pool + ((hi << 32) | lo);
+    };
+    auto issue_k = [&](int pair) {
+        unsigned in_page0;
+        const char* kp = page_base(tile_of(pair), &in_page0) + size_t(in_page0) * (AHD * 2);
+        unsigned char* sa = lds + (pair & 1) * A8_RING + grp * A_KBYTES;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            __builtin_amdgcn_global_load_lds((const CAKE_GLOBAL_AS void*)(kp + size_t(koffg[i])),
+                                             (CAKE_LDS_AS void*)(sa + (wave + 4 * i) * 1024), 16, 0, 0);
+    };
+    auto issue_v = [&](int pair) {
+        unsigned in_page0;
+        const char* vp = page_base(tile_of(pair), &in_page0) + k_to_v + size_t(in_page0) * 2;
+        unsigned char* sa = lds + A8_VBASE + (pair & 1) * A8_RING + grp * A_KBYTES;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            __builtin_amdgcn_global_load_lds((const CAKE_GLOBAL_AS void*)(vp + size_t(voffg[i])),
+                                             (CAKE_LDS_AS void*)(sa + (wave + 4 * i) * 1024), 16, 0, 0);
+    };
+
+    const int sk = sigma16(lrow & 15);
+    const int krow_base = (16 * (lrow >> 4) + sk) * (AHD * 2);
+    int kaddr[AHD / 16];
+#pragma unroll
+    for (int ks = 0; ks < AHD / 16; ++ks) kaddr[ks] = grp * A_KBYTES + krow_base + (((2 * ks + lhalf) ^ sk) << 4);
+    const int sv = (lrow >> 1) & 7;
+    int vaddr[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) vaddr[j] = A8_VBASE + grp * A_KBYTES + lrow * (AK * 2) + (((2 * j + lhalf) ^ sv) << 4);
+
+    f32x16 o[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[t][v] = 0.f;
+    float m_run = A8_NEG, l_part = 0.f;
+    const float sl2 = 0.08838834764831845f * 1.4426950408889634f;
+    const f32x16 zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    float mx_cur = A8_NEG, corr_cur = 0.f;
+    bool moved_cur = false;
+    constexpr float RESCALE_LOG2 = 6.0f;
+    auto mask_tile = [&](f32x16* s, int tile) {
+        const int key0 = tile * AK;
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                int key = key0 + 32 * t + (v & 7) + 8 * lhalf + 16 * (v >> 3);
+                if (key > my_pos) s[t][v] = -INFINITY;
+            }
+    };
+    auto part_max = [&](const f32x16* s, int part, float acc) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc = fmaxf(acc, s[part >> 1][8 * (part & 1) + i]);
+        return acc;
+    };
+    auto finish_max = [&](float raw) {
+        float mx = raw * sl2;
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        moved_cur = mx > m_run + RESCALE_LOG2;
+        if (__builtin_amdgcn_ballot_w64(moved_cur) != 0) {
+            mx = fmaxf(mx, m_run);
+            corr_cur = __builtin_amdgcn_exp2f(m_run - mx);
+            m_run = mx;
+            moved_cur = true;
+        } else {
+            corr_cur = 1.0f;
+        }
+        mx_cur = m_run;
+    };
+
+    // iteration i: this group's tile 2i+grp is in K slot i&1 (scores already formed) and V slot i&1
+    auto step = [&](int i, f32x16* s_cur, f32x16* s_nxt) {
+        asm volatile("s_waitcnt vmcnt(0)");
+        __builtin_amdgcn_s_barrier();
+        if (i + 1 < n_pairs) issue_v(i + 1);
+        if (i + 2 < n_pairs) issue_k(i + 2);
+        const float mx = mx_cur;
+        const unsigned char* stk = lds + ((i + 1) & 1) * A8_RING;   // past the last pair: stale, result unused
+        const unsigned char* stv = lds + (i & 1) * A8_RING;
+        bf16x8 opa[4], opb[4], p[4];
+        auto read_k = [&](bf16x8* dst, int grpk) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                dst[e] = *(const bf16x8*)(stk + (e & 1) * 32 * (AHD * 2) + kaddr[2 * grpk + (e >> 1)]);
+        };
+        auto read_v = [&](bf16x8* dst, int j) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) dst[e] = *(const bf16x8*)(stv + e * 32 * (AK * 2) + vaddr[j]);
+        };
+        auto mma_k = [&](const bf16x8* src, int grpk) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int ks = 2 * grpk + (e >> 1), t = e & 1;
+                s_nxt[t] = mfma32(src[e], qreg[ks], ks == 0 ? zero16 : s_nxt[t]);
+            }
+        };
+        auto expo = [&](int grpe) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                float x = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[grpe >> 1][8 * (grpe & 1) + e], sl2, -mx));
+                l_part += x;
+                p[grpe][e] = bf16_t(x);
+            }
+        };
+        read_k(opa, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        read_k(opb, 1); mma_k(opa, 0); expo(0);
+        __builtin_amdgcn_sched_barrier(0);
+        read_k(opa, 2); mma_k(opb, 1); expo(1);
+        __builtin_amdgcn_sched_barrier(0);
+        read_k(opb, 3); mma_k(opa, 2); expo(2);
+        __builtin_amdgcn_sched_barrier(0);
+        read_v(opa, 0); mma_k(opb, 3); expo(3);
+        __builtin_amdgcn_sched_barrier(0);
+        const int next_tile = 2 * (i + 1) + grp;
+        if (next_tile >= first_masked) mask_tile(s_nxt, next_tile);   // also blanks tiles past the end
+        float raw;
+        read_v(opb, 1);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) o[t] = mfma32(opa[t], p[0], o[t]);
+        raw = part_max(s_nxt, 0, s_nxt[0][0]);
+        raw = part_max(s_nxt, 1, raw);
+        __builtin_amdgcn_sched_barrier(0);
+        read_v(opa, 2);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) o[t] = mfma32(opb[t], p[1], o[t]);
+        raw = part_max(s_nxt, 2, raw);
+        raw = part_max(s_nxt, 3, raw);
+        __builtin_amdgcn_sched_barrier(0);
+        read_v(opb, 3);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) o[t] = mfma32(opa[t], p[2], o[t]);
+        finish_max(raw);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) o[t] = mfma32(opb[t], p[3], o[t]);
+        __builtin_amdgcn_sched_barrier(0);
+        if (__builtin_amdgcn_ballot_w64(moved_cur) != 0) {
+            l_part *= corr_cur;
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) o[t][v] *= corr_cur;
+        }
+    };
+
+    // prologue: K(0), V(0), K(1) in flight; K(0) landed; scores and reference of the first tile
+    issue_k(0);
+    issue_v(0);
+    if (n_pairs > 1) {
+        issue_k(1);
+        asm volatile("s_waitcnt vmcnt(8)");
+    } else {
+        asm volatile("s_waitcnt vmcnt(4)");
+    }
+    __builtin_amdgcn_s_barrier();
+    f32x16 s_a[2], s_b[2];
+    {
+        const unsigned char* stk = lds;
+#pragma unroll
+        for (int ks = 0; ks < AHD / 16; ++ks)
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                bf16x8 a = *(const bf16x8*)(stk + t * 32 * (AHD * 2) + kaddr[ks]);
+                s_a[t] = mfma32(a, qreg[ks], ks == 0 ? zero16 : s_a[t]);
+            }
+    }
+    if (grp >= first_masked) mask_tile(s_a, grp);
+    {
+        float raw = s_a[0][0];
+#pragma unroll
+        for (int part = 0; part < 4; ++part) raw = part_max(s_a, part, raw);
+        finish_max(raw);
+    }
+    for (int i = 0; i < n_pairs; i += 2) {
+        step(i, s_a, s_b);
+        if (i + 1 < n_pairs) step(i + 1, s_b, s_a);
+    }
+
+    // merge the two key halves: group B parks (O, l, reference) in LDS, group A combines and stores
+    __syncthreads();
+    float* park = (float*)lds + size_t(wave) * 66 * 64 + lane;
+    if (grp == 1) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) park[(16 * t + v) * 64] = o[t][v];
+        park[64 * 64] = l_part;
+        park[65 * 64] = m_run;
+    }
+    __syncthreads();
+    if (grp == 0) {
+        const float m_b = park[65 * 64], l_b = park[64 * 64];
+        const float m = fmaxf(m_run, m_b);
+        const float ca = __builtin_amdgcn_exp2f(m_run - m), cb = __builtin_amdgcn_exp2f(m_b - m);
+        float l_mine = l_part * ca + l_b * cb;
+        const float l_tot = l_mine + __shfl_xor(l_mine, 32, 64);
+        const float inv = 1.0f / l_tot;
+        const int row = q0 + wave * 32 + lrow;
+        if (row < rows) {
+            bf16_t* op = out + size_t(row) * n_q * AHD + h * AHD;
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int v4 = 0; v4 < 4; ++v4) {
+                    bf16x4 w;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int v = 4 * v4 + e;
+                        w[e] = bf16_t((o[t][v] * ca + park[(16 * t + v) * 64] * cb) * inv);
+                    }
+                    *(bf16x4*)(op + t * 32 + 8 * v4 + 4 * lhalf) = w;
+                }
+        }
+    }
+}
+
 bool attention_mfma_supported(int head_dim, int page_tokens) {
     return head_dim == AHD && page_tokens % AK == 0;
 }
 
 hipError_t launch_attention_mfma(const void* q, void* out, int n_q, int tok_begin, int rows, const KvView& kv,
-                                 hipStream_t st) {
+                                 hipStream_t st, int variant) {
     if (rows <= 0) return hipSuccess;
     static bool attr_set = false;
     constexpr int LDS_MAX = 160 * 1024;
-    // ring of key/value tiles + one 8-byte page offset per logical page of this launch
-    const int LDS = A_STAGES * A_STAGE + 8 * ((tok_begin + rows - 1) / kv.page_tokens + 1);
-    if (LDS > LDS_MAX) return hipErrorInvalidValue;
+    const int table = 8 * ((tok_begin + rows - 1) / kv.page_tokens + 1);   // one 8-byte page offset per logical page
+    const int q_tiles = (rows + AQ - 1) / AQ;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)attention_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_MAX);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attention_mfma8_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_MAX);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const int q_tiles = (rows + AQ - 1) / AQ;
-    hipLaunchKernelGGL(attention_mfma_kernel, dim3(q_tiles * n_q), dim3(256), LDS, st, (const bf16_t*)q, (bf16_t*)out, n_q,
-                       tok_begin, rows, kv, q_tiles);
+    if (variant == 1) {
+        const int LDS = A_STAGES * A_STAGE + table;
+        if (LDS > LDS_MAX) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(attention_mfma_kernel, dim3(q_tiles * n_q), dim3(256), LDS, st, (const bf16_t*)q, (bf16_t*)out, n_q,
+                           tok_begin, rows, kv, q_tiles);
+    } else {
+        const int LDS = A8_TABLE + table;
+        if (LDS > LDS_MAX) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(attention_mfma8_kernel, dim3(q_tiles * n_q), dim3(512), LDS, st, (const bf16_t*)q, (bf16_t*)out, n_q,
+                           tok_begin, rows, kv, q_tiles);
+    }
     return hipGetLastError();
 }
 

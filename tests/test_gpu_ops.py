@@ -112,16 +112,16 @@ def _rounded(cache, kind):
     return out
 
 
-@pytest.mark.parametrize("kind,path", [("f32", 0), ("bf16", 1), ("bf16", 0)])
-@pytest.mark.parametrize("tok_begin,rows", [(0, 130), (256, 256), (448, 77), (1, 1)])
-def test_attention(kind, path, tok_begin, rows):
+@pytest.mark.parametrize("kind,path,variant", [("f32", 0, 0), ("bf16", 1, 0), ("bf16", 0, 0), ("bf16", 0, 1)])
+@pytest.mark.parametrize("tok_begin,rows", [(0, 130), (256, 256), (448, 77), (1, 1), (0, 64), (64, 1), (960, 200)])
+def test_attention(kind, path, variant, tok_begin, rows):
     import torch
     shape = SHAPE_F32 if kind == "f32" else SHAPE_BF
     pt, T = 128, tok_begin + rows
     n_log = (T + pt - 1) // pt
     bt = np.random.default_rng(3).permutation(n_log).astype(np.int32)
     eng = _engine(shape, n_log * pt, 256, pt, block_table=bt)
-    eng.set_tuning(kernel_path=path)
+    eng.set_tuning(kernel_path=path, attn_variant=variant)
     rng = np.random.default_rng(4 + rows)
     nq, nkv, hd = shape.n_q, shape.n_kv, shape.head_dim
     cache = otf.KVCache(1, T, nkv, hd)

@@ -32,7 +32,7 @@ def test_struct_sizes_match_the_header_layout():
     assert ctypes.sizeof(cake.Request) == 56
     assert ctypes.sizeof(cake.StepLog) == 40
     assert ctypes.sizeof(cake.ModelDesc) == 40
-    assert ctypes.sizeof(cake.Tuning) == 32
+    assert ctypes.sizeof(cake.Tuning) == 40
     assert ctypes.sizeof(cake.Kv) == 40
 
 
