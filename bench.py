@@ -28,8 +28,8 @@ PEAK_HBM_GBS = 8000.0
 
 
 def cpu_baseline(shape, chunk, n_tokens, total_flops):
-    """Times the oracle (as it stands) on a bounded sample: the first chunk of the prompt
-    through 2 layers of the same widths, then scales to the whole job by FLOP count."""
+    """Times the oracle (as it stands) on a bounded sample: the first 4 chunks of the prompt
+    through 4 layers of the same widths (10-20 s of host work), scaled to the whole job by FLOP count."""
     import numpy as np
     import synth_inputs as si
     from oracle import transformer as otf
@@ -38,19 +38,20 @@ def cpu_baseline(shape, chunk, n_tokens, total_flops):
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         threads = os.cpu_count()
-    small = shape.with_(n_layers=2, vocab=4096)
+    n_s = max(1, min(4, n_tokens // chunk))
+    small = shape.with_(n_layers=min(4, shape.n_layers), vocab=4096)
     w = si.make_weights(small, seed=0)
-    toks = si.make_tokens(chunk, small.vocab, seed=1)
+    toks = si.make_tokens(n_s * chunk, small.vocab, seed=1)
     t0 = time.perf_counter()
     otf.prefill_chunked(w, small, toks, chunk, kv_dtype="bf16")
     dt = time.perf_counter() - t0
-    fl = otf.chunk_flops(small, 0, chunk)
+    fl = sum(otf.chunk_flops(small, i, chunk) for i in range(n_s))
     return {
         "value": dt * total_flops / fl, "unit": "s (TTFT, compute-only, extrapolated by FLOPs)",
         "cores": int(threads), "kind": "oracle",
-        "sample": "oracle.prefill_chunked: first %d-token chunk through 2 of %d layers at full width, "
+        "sample": "oracle.prefill_chunked: first %d chunks of %d tokens through %d of %d layers at full width, "
                   "%.1f s measured, %.3f TFLOP; scaled x%.0f to the %d-token, %d-layer job"
-                  % (chunk, shape.n_layers, dt, fl / 1e12, total_flops / fl, n_tokens, shape.n_layers),
+                  % (n_s, chunk, small.n_layers, shape.n_layers, dt, fl / 1e12, total_flops / fl, n_tokens, shape.n_layers),
         "measured_s": dt, "measured_tflops": fl / dt / 1e12,
     }
 

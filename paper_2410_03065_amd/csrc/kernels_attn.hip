@@ -395,14 +395,14 @@ attention_mfma8_kernel(const bf16_t* __restrict__ q, bf16_t* __restrict__ out, i
 #pragma unroll
         for (int ks = 0; ks < AHD / 16; ++ks) qreg[ks] = *(const bf16x8*)(qp + 16 * ks);
     }
-    unsigned koffg[4], voffg[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        int j = wave + 4 * i;
-        int krow = 4 * j + (lane >> 4), kpos = lane & 15;
-        koffg[i] = unsigned(krow * AHD + ((kpos ^ (krow & 15)) << 3)) * 2u;
-        int vrow = 8 * j + (lane >> 3), vpos = lane & 7;
-        voffg[i] = unsigned(vrow * pt + ((vpos ^ ((vrow >> 1) & 7)) << 3)) * 2u;
+    // lane offsets of this wave's first K / V^T wave-load of a tile; the other three are a
+    // wave-uniform distance further (16 key rows / 32 head-dim rows), the swizzle term repeats
+    unsigned koff0, voff0;
+    {
+        int krow = 4 * wave + (lane >> 4), kpos = lane & 15;
+        koff0 = unsigned(krow * AHD + ((kpos ^ (krow & 15)) << 3)) * 2u;
+        int vrow = 8 * wave + (lane >> 3), vpos = lane & 7;
+        voff0 = unsigned(vrow * pt + ((vpos ^ ((vrow >> 1) & 7)) << 3)) * 2u;
     }
     const int last_page = wg_last_pos / pt;
     unsigned long long* pg_lds = (unsigned long long*)(lds + A8_TABLE);
@@ -429,7 +429,7 @@ attention_mfma8_kernel(const bf16_t* __restrict__ q, bf16_t* __restrict__ out, i
         unsigned char* sa = lds + (pair & 1) * A8_RING + grp * A_KBYTES;
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            __builtin_amdgcn_global_load_lds((const CAKE_GLOBAL_AS void*)(kp + size_t(koffg[i])),
+            __builtin_amdgcn_global_load_lds((const CAKE_GLOBAL_AS void*)(kp + size_t(i) * (16 * AHD * 2) + koff0),
                                              (CAKE_LDS_AS void*)(sa + (wave + 4 * i) * 1024), 16, 0, 0);
     };
     auto issue_v = [&](int pair) {
@@ -438,7 +438,7 @@ attention_mfma8_kernel(const bf16_t* __restrict__ q, bf16_t* __restrict__ out, i
         unsigned char* sa = lds + A8_VBASE + (pair & 1) * A8_RING + grp * A_KBYTES;
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            __builtin_amdgcn_global_load_lds((const CAKE_GLOBAL_AS void*)(vp + size_t(voffg[i])),
+            __builtin_amdgcn_global_load_lds((const CAKE_GLOBAL_AS void*)(vp + size_t(i) * 32 * pt * 2 + voff0),
                                              (CAKE_LDS_AS void*)(sa + (wave + 4 * i) * 1024), 16, 0, 0);
     };
 
@@ -536,6 +536,11 @@ attention_mfma8_kernel(const bf16_t* __restrict__ q, bf16_t* __restrict__ out, i
         read_k(opb, 3); mma_k(opa, 2); expo(2);
         __builtin_amdgcn_sched_barrier(0);
         read_v(opa, 0); mma_k(opb, 3); expo(3);
+        // the probabilities are only consumed after the branch below; pin them here, or the compiler
+        // sinks the exponentials out of the block whose MFMAs they are meant to overlap with
+#pragma unroll
+        for (int e = 0; e < 4; ++e) asm volatile("" ::"v"(p[e]));
+        asm volatile("" ::"v"(l_part));
         __builtin_amdgcn_sched_barrier(0);
         const int next_tile = 2 * (i + 1) + grp;
         if (next_tile >= first_masked) mask_tile(s_nxt, next_tile);   // also blanks tiles past the end

@@ -308,7 +308,7 @@ def test_adaptive_scheduling_mix():
     eng.set_store(images)
     r_c = eng.bidirectional_prefill(toks, C, 4.0, mode="compute_only")
     kv_bytes = T * otf.kv_bytes_per_token(shape.n_layers, shape.n_kv, shape.head_dim, 2)
-    rate = kv_bytes / r_c.ttft_ns * 0.6            # a tier somewhat slower than this GPU computes
+    rate = kv_bytes / r_c.ttft_ns * 0.8            # a tier somewhat slower than this GPU computes
     others = []
     for j, (n_tok, arr_ms) in enumerate(((2048, 0.0), (1500, 1.0), (2048, 6.0))):
         kv, pool = eng.new_kv(n_tok)
@@ -354,8 +354,9 @@ def test_adaptive_scheduling_mix():
     assert remaining == [0, 0, 0]
     assert any(0 < s["prefix_tokens"] < budget for s in steps)  # partial steps happened
     _check_decisions(res, shape, T, C, pt)
-    # bandwidth drop after the loader's 2nd chunk: more chunks end up computed
-    res2, _, _ = run(step_after=2)
+    # tenfold bandwidth drop after the loader's 1st chunk: a chunk then loads slower than the whole
+    # rest computes, so several more chunks end up computed (margin of more than two chunks)
+    res2, _, _ = run(step_after=1)
     assert _errs(eng.pool_images(T), want).max() < TOL["bf16"]
     _check_decisions(res2, shape, T, C, pt)
     assert res2.meet_point > res.meet_point
