@@ -66,9 +66,60 @@ __global__ void __launch_bounds__(256) rmsnorm_kernel(const float* __restrict__ 
     for (int c = threadIdx.x; c < d; c += 256) o[c] = from_f<T>(xr[c] * r * gain[c]);
 }
 
+// Rows whose length is a multiple of 1024: every thread keeps its NV float4 pieces of the row in
+// registers (one 16-byte load each, all in flight together), so the row is read once.
+template <typename T, int NV>
+__global__ void __launch_bounds__(256) rmsnorm_vec_kernel(const float* __restrict__ x, const float* __restrict__ gain,
+                                                          T* __restrict__ out, float eps) {
+    __shared__ float part[4];
+    constexpr int d = NV * 1024;
+    const float4* xr = (const float4*)(x + size_t(blockIdx.x) * d);
+    float4 v[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) v[i] = xr[threadIdx.x + 256 * i];
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) s += v[i].x * v[i].x + v[i].y * v[i].y + v[i].z * v[i].z + v[i].w * v[i].w;
+    s = wave_sum(s);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = s;
+    __syncthreads();
+    const float tot = part[0] + part[1] + part[2] + part[3];
+    const float r = 1.0f / sqrtf(tot / float(d) + eps);
+    T* o = out + size_t(blockIdx.x) * d;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int c4 = threadIdx.x + 256 * i;
+        const float4 g = ((const float4*)gain)[c4];
+        const float y0 = v[i].x * r * g.x, y1 = v[i].y * r * g.y, y2 = v[i].z * r * g.z, y3 = v[i].w * r * g.w;
+        if constexpr (sizeof(T) == 4) {
+            ((float4*)o)[c4] = make_float4(y0, y1, y2, y3);
+        } else {
+            typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4_t;
+            bf16x4_t w = {from_f<T>(y0), from_f<T>(y1), from_f<T>(y2), from_f<T>(y3)};
+            ((bf16x4_t*)o)[c4] = w;
+        }
+    }
+}
+
+template <typename T>
+static bool launch_rmsnorm_vec(const float* x, const float* gain, T* out, int rows, int d, float eps, hipStream_t st) {
+    if (d % 1024 != 0 || d > 8192 || ((uintptr_t(x) | uintptr_t(gain) | uintptr_t(out)) & 15)) return false;
+    switch (d / 1024) {
+#define CAKE_RMS_CASE(NV) \
+    case NV: hipLaunchKernelGGL((rmsnorm_vec_kernel<T, NV>), dim3(rows), dim3(256), 0, st, x, gain, out, eps); return true;
+        CAKE_RMS_CASE(1) CAKE_RMS_CASE(2) CAKE_RMS_CASE(3) CAKE_RMS_CASE(4) CAKE_RMS_CASE(5) CAKE_RMS_CASE(6) CAKE_RMS_CASE(7)
+        CAKE_RMS_CASE(8)
+#undef CAKE_RMS_CASE
+    }
+    return false;
+}
+
 hipError_t launch_rmsnorm(int dtype, const float* x, const float* gain, void* out, int rows, int d, float eps,
                           hipStream_t st) {
     if (rows <= 0) return hipSuccess;
+    if (dtype == 0 ? launch_rmsnorm_vec(x, gain, (float*)out, rows, d, eps, st)
+                   : launch_rmsnorm_vec(x, gain, (bf16_t*)out, rows, d, eps, st))
+        return hipGetLastError();
     if (dtype == 0) hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(rows), dim3(256), 0, st, x, gain, (float*)out, d, eps);
     else hipLaunchKernelGGL(rmsnorm_kernel<bf16_t>, dim3(rows), dim3(256), 0, st, x, gain, (bf16_t*)out, d, eps);
     return hipGetLastError();
@@ -156,12 +207,89 @@ rope_kv_write_kernel(const float* __restrict__ qkv, const float2* __restrict__ c
     }
 }
 
+// bf16, head_dim 128: same grid and semantics as above with 16-byte loads (4 consecutive elements =
+// 2 rotary pairs per thread, 32 threads per token row) and 8-byte stores; V^T leaves the LDS
+// transpose as 16-byte pieces of 8 consecutive tokens.
+__global__ void __launch_bounds__(256)
+rope_kv_write_bf16_hd128_kernel(const float* __restrict__ qkv, const float2* __restrict__ cs, bf16_t* __restrict__ q,
+                                int n_q, int tok_begin, int rows, KvView kv) {
+    constexpr int HD = 128, HALF = 64;
+    typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4_t;
+    typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+    __shared__ bf16_t vt[64][HD + 2];
+    const int n_kv = kv.n_kv;
+    const int ldq = (n_q + 2 * n_kv) * HD;
+    const int head = blockIdx.y;
+    const int tile_tok0 = (tok_begin / 64 + blockIdx.x) * 64;  // absolute
+    const int lo = max(tile_tok0, tok_begin), hi = min(tile_tok0 + 64, tok_begin + rows);
+    if (lo >= hi) return;
+    const int lpage = tile_tok0 / kv.page_tokens;
+    const int ppage = kv.block_table[lpage];
+    const int in_page0 = tile_tok0 - lpage * kv.page_tokens;
+    bf16_t* page = (bf16_t*)kv.pool + (size_t(kv.layer) * kv.n_physical_pages + ppage) * kv.page_elems();
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 4 elements of a row; 8 rows per pass
+
+    if (head < n_q + n_kv) {
+        const bool is_q = head < n_q;
+#pragma unroll
+        for (int pass = 0; pass < 8; ++pass) {
+            const int t = ty + 8 * pass, tok = tile_tok0 + t;
+            if (tok < lo) continue;
+            bf16_t* kdst = page + (size_t(head - n_q) * kv.page_tokens + in_page0 + t) * HD + 4 * tx;
+            if (tok >= hi) {  // slots of this tile past the range: keep them finite for masked reads
+                if (!is_q) *(bf16x4_t*)kdst = bf16x4_t{0, 0, 0, 0};
+                continue;
+            }
+            const int row = tok - tok_begin;
+            const float4 v = *(const float4*)(qkv + size_t(row) * ldq + head * HD + 4 * tx);
+            const float4 c = *(const float4*)(cs + row * HALF + 2 * tx);   // (cos, sin) of pairs 2tx, 2tx+1
+            bf16x4_t w = {bf16_t(v.x * c.x - v.y * c.y), bf16_t(v.x * c.y + v.y * c.x),
+                          bf16_t(v.z * c.z - v.w * c.w), bf16_t(v.z * c.w + v.w * c.z)};
+            bf16_t* dst = is_q ? q + (size_t(head) * rows + row) * HD + 4 * tx : kdst;
+            *(bf16x4_t*)dst = w;
+        }
+    } else {
+        const int g = head - n_q - n_kv;
+#pragma unroll
+        for (int pass = 0; pass < 8; ++pass) {
+            const int t = ty + 8 * pass, tok = tile_tok0 + t;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (tok >= lo && tok < hi) v = *(const float4*)(qkv + size_t(tok - tok_begin) * ldq + head * HD + 4 * tx);
+            vt[t][4 * tx + 0] = bf16_t(v.x); vt[t][4 * tx + 1] = bf16_t(v.y);
+            vt[t][4 * tx + 2] = bf16_t(v.z); vt[t][4 * tx + 3] = bf16_t(v.w);
+        }
+        __syncthreads();
+        bf16_t* vpage = page + size_t(n_kv) * kv.page_tokens * HD + size_t(g) * HD * kv.page_tokens;
+        // 128 rows (head-dim index) x 8 pieces of 8 tokens = 1024 pieces, 4 per thread
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int piece = threadIdx.x + 256 * i, e = piece >> 3, t0 = (piece & 7) * 8;
+            bf16x8_t w;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) w[k] = vt[t0 + k][e];
+            bf16_t* dst = vpage + size_t(e) * kv.page_tokens + in_page0 + t0;
+            if (tile_tok0 + t0 >= lo) {
+                *(bf16x8_t*)dst = w;   // zeros past the range
+            } else {                   // tokens before the range belong to an earlier call: leave them
+#pragma unroll
+                for (int k = 0; k < 8; ++k)
+                    if (tile_tok0 + t0 + k >= lo) dst[k] = w[k];
+            }
+        }
+    }
+}
+
 hipError_t launch_rope_kv_write(int dtype, const float* qkv, const float* cs, void* q, int n_q, int tok_begin,
                                 int rows, const KvView& kv, hipStream_t st) {
     if (rows <= 0) return hipSuccess;
     int tiles = (tok_begin + rows - 1) / 64 - tok_begin / 64 + 1;
     dim3 grid(tiles, n_q + 2 * kv.n_kv), block(256);
     const float2* c2 = (const float2*)cs;
+    const bool aligned = ((uintptr_t(qkv) | uintptr_t(cs) | uintptr_t(q) | uintptr_t(kv.pool)) & 15) == 0;
+    if (dtype == 1 && kv.head_dim == 128 && aligned) {
+        hipLaunchKernelGGL(rope_kv_write_bf16_hd128_kernel, grid, block, 0, st, qkv, c2, (bf16_t*)q, n_q, tok_begin, rows, kv);
+        return hipGetLastError();
+    }
     if (dtype == 0 && kv.head_dim == 64)
         hipLaunchKernelGGL((rope_kv_write_kernel<float, 64>), grid, block, 0, st, qkv, c2, (float*)q, n_q, tok_begin, rows, kv);
     else if (dtype == 0 && kv.head_dim == 128)

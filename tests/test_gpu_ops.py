@@ -30,13 +30,14 @@ SHAPE_F32 = si.ModelShape("op-f32", 1, 256, 4, 4, 64, 688, 64, "f32")
 
 
 @pytest.mark.parametrize("kind", ["f32", "bf16"])
-def test_rmsnorm(kind):
+@pytest.mark.parametrize("rows,d", [(37, 1000), (37, 4096), (5, 8192), (3, 1024), (2, 9216)])
+def test_rmsnorm(kind, rows, d):
     import torch
     shape = SHAPE_F32 if kind == "f32" else SHAPE_BF
     eng = _engine(shape, 256, 256, 64)
     rng = np.random.default_rng(0)
-    x = rng.standard_normal((37, 1000)).astype(np.float32) * 3
-    g = (1 + 0.3 * rng.standard_normal(1000)).astype(np.float32)
+    x = rng.standard_normal((rows, d)).astype(np.float32) * 3
+    g = (1 + 0.3 * rng.standard_normal(d)).astype(np.float32)
     got = eng.op_rmsnorm(torch.from_numpy(x).cuda(), torch.from_numpy(g).cuda()).float().cpu().numpy()
     want = otf.rmsnorm(x.astype(np.float64), g.astype(np.float64), shape.rms_eps)
     assert _rel(got, want) < (1e-6 if kind == "f32" else 2.0 ** -8)
