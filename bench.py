@@ -100,7 +100,7 @@ def main():
     shape = si.SHAPES[args.shape]
     T, C, pt = args.tokens, args.chunk, args.page_tokens
     n = (T + C - 1) // C
-    eng = cake.Engine(shape, None, max_tokens=T, max_chunk=C, page_tokens=pt, seed=0)
+    eng = cake.Engine(shape, None, max_tokens=T, max_chunk=C, page_tokens=pt, seed=0, with_head=True)
     toks = si.make_tokens(T, shape.vocab, seed=1)
     total_flops = sum(cake.range_flops(shape, i * C, min(C, T - i * C)) for i in range(n))
     kv_bytes = n * (C // pt) * cake.page_image_bytes(shape, pt)
@@ -127,6 +127,24 @@ def main():
     wall = time.perf_counter() - t0
     stats = eng.profile_read() if not args.no_profile else {}
     eng.profile_enable(False)
+
+    # first-token step on the complete cache (reported beside the headline value, not inside it)
+    eng.first_token(toks)
+    if not args.no_profile:
+        eng.profile_enable(True)
+    t1 = time.perf_counter()
+    ft = [eng.first_token(toks) for _ in range(3)]
+    ft_wall = (time.perf_counter() - t1) / 3
+    ft_stats = eng.profile_read() if not args.no_profile else {}
+    eng.profile_enable(False)
+    first_token = {"token": ft[-1][0], "wall_ms": round(ft_wall * 1e3, 3),
+                   "device_ms": round(float(np.mean([f[1] for f in ft])) / 1e6, 3), "bound": "hbm", "peak_gbs": PEAK_HBM_GBS}
+    for name in ("gemv", "decode_attention"):
+        st = ft_stats.get(name)
+        if st and st["launches"]:
+            first_token[name] = {"launches": st["launches"], "total_ms": round(st["total_ns"] / 3e6, 3),
+                                 "gbs": round(st["bytes"] / st["total_ns"], 1),
+                                 "frac_of_hbm_peak": round(st["bytes"] / st["total_ns"] / PEAK_HBM_GBS, 3)}
 
     r_c = eng.bidirectional_prefill(toks, C, args.gbps, mode="compute_only")
     r_l = eng.bidirectional_prefill(toks, C, args.gbps, mode="load_only")
@@ -182,6 +200,7 @@ def main():
         "load_gbps": {"configured": args.gbps, "achieved_bidirectional": round(load_bytes / load_ns, 4) if load_ns else None,
                       "achieved_load_only": round(r_l.achieved_gbps, 4), "kv_bytes": kv_bytes},
         "kernels": kernels,
+        "first_token": dict(first_token, ttft_to_first_token_s=round(ttft + ft_wall, 5)),
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:

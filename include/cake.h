@@ -100,6 +100,8 @@ typedef struct {
 typedef struct {
     const void* embed;                /* device, [vocab][d_model] */
     const cake_layer_weights* layers; /* host array of n_layers structs (copied by cake_create) */
+    const float* final_norm;          /* device, [d_model]; NULL if cake_first_token is not used */
+    const void* lm_head;              /* device, [vocab][d_model]; NULL likewise */
 } cake_weights;
 
 typedef struct {
@@ -278,6 +280,20 @@ int32_t cake_adaptive_serve(cake_ctx* ctx, cake_request* requests, int32_t n_req
                             cake_result* res, cake_step_log* steps, int32_t steps_cap,
                             int32_t* n_steps_out);
 
+/* First output token.  The paper measures the time to first token up to "the generation of the
+ * first token" (Sec. 5.1, Metrics); once every chunk's KV is resident -- whichever side produced
+ * it -- that token needs one more pass: the prompt's LAST token runs through the decoder against
+ * the complete cache (which is read, never written: a loaded last chunk keeps its stored bytes),
+ * then the final norm, the LM head and an argmax (lowest index among equal logits).
+ * Requires KV of [0, n_tokens) resident in `kv` and a context created with final_norm and
+ * lm_head.  token_ids: host, n_tokens ids (only the last is read).  token_out: host.
+ * logits_out: host, vocab float32, or NULL.  device_ns_out: HIP-event time of the step, or NULL.
+ * Blocking; runs on the compute stream.
+ * Errors: CAKE_E_INVAL, CAKE_E_STATE (no head weights), CAKE_E_HIP. */
+int32_t cake_first_token(cake_ctx* ctx, const int32_t* token_ids, int32_t n_tokens,
+                         const cake_kv* kv, int32_t* token_out, float* logits_out,
+                         uint64_t* device_ns_out);
+
 /* ---- small helpers ---------------------------------------------------- */
 
 /* Bandwidth of the simulated tier; thread-safe; takes effect at the next paced piece
@@ -322,7 +338,10 @@ int32_t cake_simulate_race(int32_t n_chunks, const uint64_t* chunk_flops,
  * once + results written once). */
 typedef enum {
     CAKE_K_EMBED = 0, CAKE_K_RMSNORM = 1, CAKE_K_GEMM_QKV = 2, CAKE_K_ROPE_KV = 3, CAKE_K_ATTENTION = 4,
-    CAKE_K_GEMM_O = 5, CAKE_K_GEMM_GATEUP = 6, CAKE_K_GEMM_DOWN = 7, CAKE_K_COUNT = 8
+    CAKE_K_GEMM_O = 5, CAKE_K_GEMM_GATEUP = 6, CAKE_K_GEMM_DOWN = 7,
+    CAKE_K_GEMV = 8,          /* first-token step: matrix-vector products (bytes = the weights streamed) */
+    CAKE_K_DECODE_ATTN = 9,   /* first-token step: one-token attention (bytes = the layer's K and V) */
+    CAKE_K_COUNT = 10
 } cake_kernel_class;
 typedef struct { uint64_t launches, total_ns, flops, bytes; } cake_kernel_stats;
 int32_t cake_profile_enable(cake_ctx* ctx, int32_t on);

@@ -247,6 +247,40 @@ def prefill_token_by_token(weights, shape, tokens: np.ndarray,
 
 
 # --------------------------------------------------------------------------- #
+# the first output token (Sec. 3: prefill ends with it; Sec. 5.1: TTFT is measured up to it)
+# --------------------------------------------------------------------------- #
+def lm_logits(weights, shape, hidden: np.ndarray) -> np.ndarray:
+    """Final RMSNorm and the vocabulary projection of hidden rows [..., d] -> [..., vocab]."""
+    h = rmsnorm(np.asarray(hidden, dtype=F64), np.asarray(weights["final_norm"], dtype=F64), shape.rms_eps)
+    return h @ np.asarray(weights["lm_head"], dtype=F64)
+
+
+def first_token_logits(weights, shape, tokens: np.ndarray, cache: KVCache) -> np.ndarray:
+    """Logits of the token that follows the prompt, from a COMPLETE cache that is only read:
+    the prompt's last token is embedded and taken through every block; in block l its rotated
+    query attends to cache.k[l, :T], cache.v[l, :T] exactly as they are (its own position
+    included -- after a bidirectional prefill that entry may be a loaded one)."""
+    tokens = np.asarray(tokens)
+    T = len(tokens)
+    n_q, hd = shape.n_q, shape.head_dim
+    pos = np.array([T - 1])
+    x = np.asarray(weights["embed"][tokens[T - 1]], dtype=F64)[None, :]
+    for l, lw in enumerate(weights["layers"]):
+        lw = _as64(lw)
+        h = rmsnorm(x, lw["attn_norm"], shape.rms_eps)
+        q = rope((h @ lw["wq"]).reshape(1, n_q, hd), pos, shape.rope_theta)
+        a = attention(q, cache.k[l, :T], cache.v[l, :T], pos, np.arange(T))
+        x = x + a.reshape(1, n_q * hd) @ lw["wo"]
+        x = x + swiglu_ffn(rmsnorm(x, lw["ffn_norm"], shape.rms_eps), lw["w_gate"], lw["w_up"], lw["w_down"])
+    return lm_logits(weights, shape, x[0])
+
+
+def greedy_token(logits: np.ndarray) -> int:
+    """Index of the largest logit; the lowest index among equal ones."""
+    return int(np.argmax(logits))
+
+
+# --------------------------------------------------------------------------- #
 # the bidirectional result (Sec. 4 Part 2; App. A steps 4-7)
 # --------------------------------------------------------------------------- #
 def bidirectional_kv(weights, shape, tokens, chunk: int, meet_chunk: int,

@@ -30,9 +30,10 @@ EXPORTS = [
     "cake_schedule_bandwidth_step", "cake_chunk_state", "cake_sync_compute", "cake_sync_load",
     "cake_range_flops", "cake_page_image_bytes", "cake_simulate_race", "cake_op_rmsnorm",
     "cake_op_gemm", "cake_op_gemm_residual", "cake_op_gemm_swiglu", "cake_op_rope_kv_write",
-    "cake_op_attention", "cake_profile_enable", "cake_profile_read", "cake_adaptive_serve",
+    "cake_op_attention", "cake_profile_enable", "cake_profile_read", "cake_adaptive_serve", "cake_first_token",
 ]
-KERNEL_CLASSES = ["embed", "rmsnorm", "gemm_qkv", "rope_kv", "attention", "gemm_o", "gemm_gateup", "gemm_down"]
+KERNEL_CLASSES = ["embed", "rmsnorm", "gemm_qkv", "rope_kv", "attention", "gemm_o", "gemm_gateup", "gemm_down",
+                  "gemv", "decode_attention"]
 
 
 class CakeError(RuntimeError):
@@ -51,7 +52,8 @@ class LayerWeights(C.Structure):
 
 
 class Weights(C.Structure):
-    _fields_ = [("embed", C.c_void_p), ("layers", C.POINTER(LayerWeights))]
+    _fields_ = [("embed", C.c_void_p), ("layers", C.POINTER(LayerWeights)), ("final_norm", C.c_void_p),
+                ("lm_head", C.c_void_p)]
 
 
 class Kv(C.Structure):
@@ -125,6 +127,7 @@ def load_library():
         "cake_load_chunk": (i32, [vp, P(KvStore), i32, i32, P(Kv), dbl]),
         "cake_plan_meet_point": (i32, [vp, vp, i32, u64, u64, P(i32), P(u64)]),
         "cake_bidirectional_prefill": (i32, [vp, vp, i32, P(KvStore), i32, dbl, i32, i32, P(Kv), P(Result)]),
+        "cake_first_token": (i32, [vp, vp, i32, P(Kv), P(i32), vp, P(u64)]),
         "cake_set_bandwidth": (i32, [vp, dbl]),
         "cake_schedule_bandwidth_step": (i32, [vp, i32, dbl]),
         "cake_chunk_state": (i32, [vp, i32]),
@@ -236,7 +239,7 @@ class Engine:
     store and the two streams, and forwards to the C ABI."""
 
     def __init__(self, shape, weights=None, *, max_tokens, max_chunk, page_tokens=256, block_table=None,
-                 n_physical_pages=None, device="cuda:0", seed=0):
+                 n_physical_pages=None, device="cuda:0", seed=0, with_head=False):
         import torch
         self.torch = torch
         self.lib = load_library()
@@ -251,6 +254,7 @@ class Engine:
         self.compute_stream = torch.cuda.Stream(device=self.dev)
         self.copy_stream = torch.cuda.Stream(device=self.dev)
         self._tensors = []
+        self.with_head = with_head or (weights is not None and "lm_head" in weights)
         self._build_weights(weights, seed)
         n_logical = (max_tokens + page_tokens - 1) // page_tokens
         n_phys = n_physical_pages or n_logical
@@ -312,7 +316,17 @@ class Engine:
             for k, v in t.items():
                 setattr(arr[l], k, v.data_ptr())
         self._layer_arr = arr
-        self._weights = Weights(self.embed.data_ptr(), arr)
+        self.final_norm = self.lm_head = None
+        if self.with_head:
+            if weights is not None:
+                self.final_norm = self._dev(weights["final_norm"], torch.float32)
+                self.lm_head = self._dev(weights["lm_head"].T)
+            else:
+                self.final_norm = torch.ones(s.d_model, dtype=torch.float32, device=self.dev)
+                self.lm_head = rnd(s.vocab, s.d_model)
+        self._weights = Weights(self.embed.data_ptr(), arr,
+                                self.final_norm.data_ptr() if self.with_head else None,
+                                self.lm_head.data_ptr() if self.with_head else None)
 
     # -- store -----------------------------------------------------------------------
     def set_store(self, images: np.ndarray):
@@ -415,6 +429,17 @@ class Engine:
             out.chunks = [{k: getattr(chunks[i], k) for k in ck} for i in range(min(n, res.n_chunks))]
             out.decisions = _decisions_to_list(dec, res.n_decisions)
         return out
+
+    def first_token(self, tokens, want_logits=False):
+        """The first output token from the complete KV of `tokens` (cake_first_token).
+        Returns (token id, device ns, logits as float32 numpy or None)."""
+        ids = self._ids(tokens)
+        tok, ns = C.c_int32(-1), C.c_uint64(0)
+        logits = np.empty(self.shape.vocab, dtype=np.float32) if want_logits else None
+        rc = self.lib.cake_first_token(self.ctx, ids.ctypes.data, len(ids), C.byref(self.kv), C.byref(tok),
+                                       logits.ctypes.data if want_logits else None, C.byref(ns))
+        self._check(rc, "cake_first_token")
+        return tok.value, ns.value, logits
 
     def new_kv(self, n_tokens):
         """A further KV pool + block table of this shape (one per concurrent request)."""

@@ -35,6 +35,12 @@ struct cake_ctx {
     void* act = nullptr;      // [max_chunk][ffn]          SwiGLU output, model dtype
     float* rope_cs = nullptr; // [max_chunk][hd/2][2]
     int32_t* d_ids = nullptr; // [max_tokens]
+    // first-token step (one row, float32 throughout); null unless the weights carry final_norm and lm_head
+    const float* final_norm = nullptr;
+    const void* lm_head = nullptr;
+    float *t_h = nullptr, *t_q = nullptr, *t_qr = nullptr, *t_ao = nullptr, *t_act = nullptr, *t_logits = nullptr,
+          *t_part = nullptr;
+    int32_t* t_tok = nullptr;
     hipEvent_t ev_a = nullptr, ev_b = nullptr;
     std::atomic<double> gbps{0.0};
     int step_after = -1;
@@ -163,6 +169,35 @@ static int enqueue_prefill(cake_ctx* c, int tok_begin, int rows, const cake_kv* 
         KLAUNCH(c, CAKE_K_GEMM_DOWN, 2 * R * d * ff, (R * ff + d * ff) * e + 2 * R * d * 4,
                 gemm(c, EPI_RESIDUAL_F32, c->act, w.w_down, nullptr, c->x, rows, d, m.ffn_dim));
     }
+    return CAKE_OK;
+}
+
+// Enqueues the first-token step for a prompt of n_tokens whose KV is complete; the last token's id
+// is already in c->d_ids[n_tokens-1].  The cache is read, never written.
+static int enqueue_first_token(cake_ctx* c, int n_tokens, const cake_kv* kv) {
+    const cake_model_desc& m = c->m;
+    const uint64_t d = m.d_model, hq = uint64_t(m.n_q_heads) * m.head_dim, hkv = uint64_t(m.n_kv_heads) * m.head_dim;
+    const uint64_t ff = m.ffn_dim, e = esize(c), T = n_tokens;
+    const int pos = n_tokens - 1;
+    HIP_TRY(c, launch_embed(m.dtype, c->embed, c->d_ids + pos, c->x, 1, d, m.vocab, c->cs));
+    for (int l = 0; l < m.n_layers; ++l) {
+        const cake_layer_weights& w = c->layers[l];
+        KvView view = make_view(c, kv, l);
+        HIP_TRY(c, launch_rmsnorm(CAKE_F32, c->x, w.attn_norm, c->t_h, 1, d, m.rms_eps, c->cs));
+        KLAUNCH(c, CAKE_K_GEMV, 2 * hq * d, hq * d * e,                 // the W_Q rows only: K and V of the token are cached
+                launch_gemv(m.dtype, 0, c->t_h, w.wqkv, nullptr, c->t_q, hq, d, c->cs));
+        HIP_TRY(c, launch_rope_token(c->t_q, c->t_qr, m.n_q_heads, m.head_dim, pos, m.rope_theta, c->cs));
+        KLAUNCH(c, CAKE_K_DECODE_ATTN, 4 * hq * T, 2 * hkv * T * e,
+                launch_decode_attention(m.dtype, c->t_qr, c->t_ao, c->t_part, m.n_q_heads, n_tokens, view, c->cs));
+        KLAUNCH(c, CAKE_K_GEMV, 2 * d * hq, d * hq * e, launch_gemv(m.dtype, 1, c->t_ao, w.wo, nullptr, c->x, d, hq, c->cs));
+        HIP_TRY(c, launch_rmsnorm(CAKE_F32, c->x, w.ffn_norm, c->t_h, 1, d, m.rms_eps, c->cs));
+        KLAUNCH(c, CAKE_K_GEMV, 4 * ff * d, 2 * ff * d * e, launch_gemv(m.dtype, 2, c->t_h, w.w_gate, w.w_up, c->t_act, ff, d, c->cs));
+        KLAUNCH(c, CAKE_K_GEMV, 2 * d * ff, d * ff * e, launch_gemv(m.dtype, 1, c->t_act, w.w_down, nullptr, c->x, d, ff, c->cs));
+    }
+    HIP_TRY(c, launch_rmsnorm(CAKE_F32, c->x, c->final_norm, c->t_h, 1, d, m.rms_eps, c->cs));
+    KLAUNCH(c, CAKE_K_GEMV, 2 * uint64_t(m.vocab) * d, uint64_t(m.vocab) * d * e,
+            launch_gemv(m.dtype, 0, c->t_h, c->lm_head, nullptr, c->t_logits, m.vocab, d, c->cs));
+    HIP_TRY(c, launch_argmax(c->t_logits, m.vocab, c->t_tok, c->cs));
     return CAKE_OK;
 }
 
@@ -296,6 +331,18 @@ int32_t cake_create(cake_ctx** out, const cake_model_desc* model, const cake_wei
     ok = ok && hipMalloc((void**)&c->rope_cs, R * m.head_dim * 4) == hipSuccess;
     ok = ok && hipMalloc((void**)&c->d_ids, size_t(max_tokens) * 4) == hipSuccess;
     ok = ok && hipEventCreate(&c->ev_a) == hipSuccess && hipEventCreate(&c->ev_b) == hipSuccess;
+    if (weights->final_norm && weights->lm_head) {
+        c->final_norm = weights->final_norm;
+        c->lm_head = weights->lm_head;
+        ok = ok && hipMalloc((void**)&c->t_h, size_t(m.d_model) * 4) == hipSuccess;
+        ok = ok && hipMalloc((void**)&c->t_q, hq * 4) == hipSuccess;
+        ok = ok && hipMalloc((void**)&c->t_qr, hq * 4) == hipSuccess;
+        ok = ok && hipMalloc((void**)&c->t_ao, hq * 4) == hipSuccess;
+        ok = ok && hipMalloc((void**)&c->t_act, size_t(m.ffn_dim) * 4) == hipSuccess;
+        ok = ok && hipMalloc((void**)&c->t_logits, size_t(m.vocab) * 4) == hipSuccess;
+        ok = ok && hipMalloc((void**)&c->t_part, decode_attention_workspace_bytes(m.n_q_heads, m.head_dim)) == hipSuccess;
+        ok = ok && hipMalloc((void**)&c->t_tok, 4) == hipSuccess;
+    }
     if (!ok) {
         (void)hipGetLastError();
         cake_destroy(c);
@@ -310,6 +357,8 @@ int32_t cake_destroy(cake_ctx* c) {
     if (c->cs || c->ls) (void)hipDeviceSynchronize();
     (void)hipFree(c->x); (void)hipFree(c->h); (void)hipFree(c->qkv); (void)hipFree(c->q);
     (void)hipFree(c->ao); (void)hipFree(c->act); (void)hipFree(c->rope_cs); (void)hipFree(c->d_ids);
+    (void)hipFree(c->t_h); (void)hipFree(c->t_q); (void)hipFree(c->t_qr); (void)hipFree(c->t_ao);
+    (void)hipFree(c->t_act); (void)hipFree(c->t_logits); (void)hipFree(c->t_part); (void)hipFree(c->t_tok);
     for (hipEvent_t e : c->prof_events) (void)hipEventDestroy(e);
     if (c->ev_a) (void)hipEventDestroy(c->ev_a);
     if (c->ev_b) (void)hipEventDestroy(c->ev_b);
@@ -448,6 +497,32 @@ int32_t cake_bidirectional_prefill(cake_ctx* c, const int32_t* token_ids, int32_
         return rc;
     }
     if ((res->chunks && res->chunks_cap < n) || ex.core.log_overflow) return CAKE_E_CAPACITY;
+    return CAKE_OK;
+}
+
+int32_t cake_first_token(cake_ctx* c, const int32_t* token_ids, int32_t n_tokens, const cake_kv* kv, int32_t* token_out,
+                         float* logits_out, uint64_t* device_ns_out) {
+    if (!c || !token_ids || !token_out) return CAKE_E_INVAL;
+    if (!c->final_norm || !c->lm_head) return fail(c, CAKE_E_STATE, "the context was created without final_norm / lm_head");
+    if (n_tokens <= 0 || n_tokens > c->max_tokens) return fail(c, CAKE_E_INVAL, "n_tokens %d outside (0, %d]", n_tokens, c->max_tokens);
+    int rc = check_kv(c, kv, n_tokens);
+    if (rc != CAKE_OK) return rc;
+    const int32_t last = token_ids[n_tokens - 1];
+    if (last < 0 || last >= c->m.vocab) return fail(c, CAKE_E_INVAL, "last token id outside the vocabulary");
+    HIP_TRY(c, hipMemcpyAsync(c->d_ids + (n_tokens - 1), &token_ids[n_tokens - 1], 4, hipMemcpyHostToDevice, c->cs));
+    HIP_TRY(c, hipEventRecord(c->ev_a, c->cs));
+    rc = enqueue_first_token(c, n_tokens, kv);
+    if (rc != CAKE_OK) return rc;
+    HIP_TRY(c, hipEventRecord(c->ev_b, c->cs));
+    HIP_TRY(c, hipMemcpyAsync(token_out, c->t_tok, 4, hipMemcpyDeviceToHost, c->cs));
+    if (logits_out)
+        HIP_TRY(c, hipMemcpyAsync(logits_out, c->t_logits, size_t(c->m.vocab) * 4, hipMemcpyDeviceToHost, c->cs));
+    HIP_TRY(c, hipStreamSynchronize(c->cs));
+    if (device_ns_out) {
+        float ms = 0.f;
+        HIP_TRY(c, hipEventElapsedTime(&ms, c->ev_a, c->ev_b));
+        *device_ns_out = uint64_t(double(ms) * 1e6);
+    }
     return CAKE_OK;
 }
 

@@ -362,3 +362,59 @@ def test_adaptive_scheduling_mix():
     assert _errs(eng.pool_images(T), want).max() < TOL["bf16"]
     _check_decisions(res2, shape, T, C, pt)
     assert res2.meet_point > res.meet_point
+
+
+# --------------------------------------------------------------------------- first token
+def _first_token_check(shape, T, C, pt, m, kind, seed):
+    """Bidirectional prefill with a forced split, then the first-token step: logits against the
+    oracle's (its own cache for the same split), the token against the oracle's argmax."""
+    import paper_2410_03065_amd as cake
+    w = si.make_weights(shape, seed=seed, with_head=True)
+    toks = si.make_tokens(T, shape.vocab, seed=seed + 1)
+    eng = cake.Engine(shape, w, max_tokens=((T + pt - 1) // pt) * pt, max_chunk=C, page_tokens=pt)
+    stored = otf.prefill_chunked(w, shape, toks, C, kv_dtype=kind)
+    eng.set_store(ostore.pack_store(stored, pt, kind))
+    pool_before = None
+    res = eng.bidirectional_prefill(toks, C, 4.0, mode="forced", forced_m=m)
+    assert res.meet_point == m
+    pool_before = eng.pool_raw(T).copy()
+    tok, ns, logits = eng.first_token(toks, want_logits=True)
+    np.testing.assert_array_equal(eng.pool_raw(T), pool_before)            # the cache is only read
+    ref_cache = otf.bidirectional_kv(w, shape, toks, C, m, stored, kv_dtype=kind)
+    want = otf.first_token_logits(w, shape, toks, ref_cache)
+    err = np.abs(logits - want).max() / np.abs(want).max()
+    assert err < TOL[kind], err
+    # the argmax is decided in float32 on the GPU: it must be a logit the oracle cannot tell from its maximum
+    assert 0 <= tok < shape.vocab and ns > 0
+    assert want[tok] >= want.max() - 2 * TOL[kind] * np.abs(want).max()
+    if np.sort(want)[-1] - np.sort(want)[-2] > 2 * TOL[kind] * np.abs(want).max():
+        assert tok == otf.greedy_token(want)
+    assert tok == int(np.argmax(logits))                                   # and exactly the argmax of its own logits
+    return eng
+
+
+@pytest.mark.parametrize("m", [0, 3, 8])
+def test_first_token_tiny_fp32(m):
+    """Config-1 shape with a head: loaded-only, mid split and computed-only caches; ragged key count."""
+    _first_token_check(si.TINY.with_(vocab=1000), 2000, 256, 128, m, "f32", seed=40)
+
+
+@pytest.mark.parametrize("shape,T,C,pt,m", [
+    (BF_NARROW_GQA4, 4096, 1024, 256, 2),      # GQA 4:1, 64 key tiles over several splits
+    (BF_NARROW_GQA8, 3000, 1024, 256, 1),      # GQA 8:1, ragged last tile
+    (BF_NARROW_MHA, 1111, 512, 128, 3),        # MHA, odd key count
+])
+def test_first_token_bf16(shape, T, C, pt, m):
+    _first_token_check(shape, T, C, pt, m, "bf16", seed=44)
+
+
+def test_first_token_needs_head_weights():
+    import paper_2410_03065_amd as cake
+    shape = si.TINY.with_(vocab=100)
+    w = si.make_weights(shape, seed=1)
+    eng = cake.Engine(shape, w, max_tokens=256, max_chunk=256, page_tokens=64)
+    toks = si.make_tokens(200, shape.vocab, seed=2)
+    eng.bidirectional_prefill(toks, 256, 4.0, mode="compute_only")
+    with pytest.raises(cake.CakeError) as e:
+        eng.first_token(toks)
+    assert e.value.code == cake.E_STATE

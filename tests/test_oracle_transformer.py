@@ -329,3 +329,45 @@ def test_chunk_flops_grows_linearly():
     params = t.n_layers * (8 * 8 + 2 * 8 * 4 + 8 * 8 + 3 * 8 * 12)
     pairs = sum(q + 1 for q in range(i * C, (i + 1) * C))
     assert otf.chunk_flops(t, i, C) == 2 * params * C + t.n_layers * t.n_q * 4 * t.head_dim * pairs
+
+
+# --------------------------------------------------------------------------- first token
+def test_first_token_equals_last_row_of_full_forward():
+    """Decode-step identity: re-running the last token against the finished cache gives the
+    hidden state the full forward had at that position, hence the same logits."""
+    shape = si.TINY.with_(vocab=97, n_layers=3)
+    w = si.make_weights(shape, seed=4, with_head=True)
+    toks = si.make_tokens(50, shape.vocab, seed=5)
+    cache, hidden = otf.prefill_chunked(w, shape, toks, 16, return_hidden=True)
+    want = otf.lm_logits(w, shape, hidden[-1])
+    got = otf.first_token_logits(w, shape, toks, cache)
+    assert np.abs(got - want).max() < 1e-10 * np.abs(want).max()
+    # and against the textbook definition written out: softmax-free check of the head itself
+    h = hidden[-1] / np.sqrt(np.mean(hidden[-1] ** 2) + shape.rms_eps) * np.asarray(w["final_norm"], dtype=np.float64)
+    np.testing.assert_allclose(want, h @ np.asarray(w["lm_head"], dtype=np.float64), rtol=1e-12)
+
+
+def test_first_token_reads_the_cache_as_it_is():
+    """The cache is authoritative, the last position included (it may hold loaded bytes)."""
+    shape = si.TINY.with_(vocab=97)
+    w = si.make_weights(shape, seed=6, with_head=True)
+    toks = si.make_tokens(40, shape.vocab, seed=7)
+    cache = otf.prefill_chunked(w, shape, toks, 16)
+    base = otf.first_token_logits(w, shape, toks, cache)
+    k0, v0 = cache.k.copy(), cache.v.copy()
+    for t in (0, 39):                                   # an early entry and the token's own
+        cache.v[1, t] += 0.5
+        bumped = cache.v.copy()
+        assert np.abs(otf.first_token_logits(w, shape, toks, cache) - base).max() > 1e-6
+        np.testing.assert_array_equal(cache.v, bumped)  # read-only
+        np.testing.assert_array_equal(cache.k, k0)
+        cache.v[:] = v0
+    # earlier prompt tokens enter only through the cache
+    toks2 = toks.copy()
+    toks2[:39] = (toks2[:39] + 1) % shape.vocab
+    np.testing.assert_array_equal(otf.first_token_logits(w, shape, toks2, cache), base)
+
+
+def test_greedy_token_lowest_index_on_ties():
+    assert otf.greedy_token(np.array([1.0, 3.0, 3.0, 2.0])) == 1
+    assert otf.greedy_token(np.array([-np.inf, -5.0])) == 1
