@@ -368,6 +368,11 @@ int32_t cake_op_rope_kv_write(cake_ctx* ctx, const float* qkv, void* q, int32_t 
  * against layer `layer` of kv's pages, keys 0 .. tok_begin+rows-1. */
 int32_t cake_op_attention(cake_ctx* ctx, const void* q, void* out, int32_t layer,
                           int32_t tok_begin, int32_t rows, const cake_kv* kv);
+/* out[n_q][hd] (float32) = attention of ONE query per head, q[n_q][hd] (float32, already rotated),
+ * against keys 0 .. n_keys-1 of layer `layer` (the first-token step's attention).  Needs a
+ * context created with head weights (it owns the split workspace). */
+int32_t cake_op_decode_attention(cake_ctx* ctx, const float* q, float* out, int32_t layer,
+                                 int32_t n_keys, const cake_kv* kv);
 
 #ifdef __cplusplus
 }

@@ -31,6 +31,7 @@ EXPORTS = [
     "cake_range_flops", "cake_page_image_bytes", "cake_simulate_race", "cake_op_rmsnorm",
     "cake_op_gemm", "cake_op_gemm_residual", "cake_op_gemm_swiglu", "cake_op_rope_kv_write",
     "cake_op_attention", "cake_profile_enable", "cake_profile_read", "cake_adaptive_serve", "cake_first_token",
+    "cake_op_decode_attention",
 ]
 KERNEL_CLASSES = ["embed", "rmsnorm", "gemm_qkv", "rope_kv", "attention", "gemm_o", "gemm_gateup", "gemm_down",
                   "gemv", "decode_attention"]
@@ -128,6 +129,7 @@ def load_library():
         "cake_plan_meet_point": (i32, [vp, vp, i32, u64, u64, P(i32), P(u64)]),
         "cake_bidirectional_prefill": (i32, [vp, vp, i32, P(KvStore), i32, dbl, i32, i32, P(Kv), P(Result)]),
         "cake_first_token": (i32, [vp, vp, i32, P(Kv), P(i32), vp, P(u64)]),
+        "cake_op_decode_attention": (i32, [vp, vp, vp, i32, i32, P(Kv)]),
         "cake_set_bandwidth": (i32, [vp, dbl]),
         "cake_schedule_bandwidth_step": (i32, [vp, i32, dbl]),
         "cake_chunk_state": (i32, [vp, i32]),
@@ -428,6 +430,14 @@ class Engine:
             ck = [f[0] for f in ChunkLog._fields_]
             out.chunks = [{k: getattr(chunks[i], k) for k in ck} for i in range(min(n, res.n_chunks))]
             out.decisions = _decisions_to_list(dec, res.n_decisions)
+        return out
+
+    def op_decode_attention(self, q, layer, n_keys):
+        """q: float32 device tensor [n_q][hd] -> float32 [n_q][hd]."""
+        out = self.torch.empty_like(q)
+        self._check(self.lib.cake_op_decode_attention(self.ctx, q.data_ptr(), out.data_ptr(), layer, n_keys,
+                                                      C.byref(self.kv)), "cake_op_decode_attention")
+        self.sync()
         return out
 
     def first_token(self, tokens, want_logits=False):

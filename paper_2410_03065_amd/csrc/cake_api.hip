@@ -188,7 +188,8 @@ static int enqueue_first_token(cake_ctx* c, int n_tokens, const cake_kv* kv) {
                 launch_gemv(m.dtype, 0, c->t_h, w.wqkv, nullptr, c->t_q, hq, d, c->cs));
         HIP_TRY(c, launch_rope_token(c->t_q, c->t_qr, m.n_q_heads, m.head_dim, pos, m.rope_theta, c->cs));
         KLAUNCH(c, CAKE_K_DECODE_ATTN, 4 * hq * T, 2 * hkv * T * e,
-                launch_decode_attention(m.dtype, c->t_qr, c->t_ao, c->t_part, m.n_q_heads, n_tokens, view, c->cs));
+                launch_decode_attention(m.dtype, c->t_qr, c->t_ao, c->t_part, m.n_q_heads, n_tokens, view, c->cs,
+                                        c->tun.kernel_path == 1));
         KLAUNCH(c, CAKE_K_GEMV, 2 * d * hq, d * hq * e, launch_gemv(m.dtype, 1, c->t_ao, w.wo, nullptr, c->x, d, hq, c->cs));
         HIP_TRY(c, launch_rmsnorm(CAKE_F32, c->x, w.ffn_norm, c->t_h, 1, d, m.rms_eps, c->cs));
         KLAUNCH(c, CAKE_K_GEMV, 4 * ff * d, 2 * ff * d * e, launch_gemv(m.dtype, 2, c->t_h, w.w_gate, w.w_up, c->t_act, ff, d, c->cs));
@@ -834,6 +835,17 @@ int32_t cake_op_attention(cake_ctx* c, const void* q, void* out, int32_t layer, 
     int rc = check_kv(c, kv, tok_begin + rows);
     if (rc != CAKE_OK) return rc;
     HIP_TRY(c, attention(c, q, out, tok_begin, rows, make_view(c, kv, layer)));
+    return CAKE_OK;
+}
+
+int32_t cake_op_decode_attention(cake_ctx* c, const float* q, float* out, int32_t layer, int32_t n_keys, const cake_kv* kv) {
+    if (!c || !q || !out || layer < 0 || layer >= c->m.n_layers || n_keys <= 0 || n_keys > c->max_tokens)
+        return fail(c, CAKE_E_INVAL, "op_decode_attention: bad argument");
+    if (!c->t_part) return fail(c, CAKE_E_STATE, "the context was created without final_norm / lm_head");
+    int rc = check_kv(c, kv, n_keys);
+    if (rc != CAKE_OK) return rc;
+    HIP_TRY(c, launch_decode_attention(c->m.dtype, q, out, c->t_part, c->m.n_q_heads, n_keys, make_view(c, kv, layer), c->cs,
+                                       c->tun.kernel_path == 1));
     return CAKE_OK;
 }
 

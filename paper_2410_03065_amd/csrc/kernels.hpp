@@ -47,6 +47,10 @@ bool attention_mfma_supported(int head_dim, int page_tokens);
 hipError_t launch_attention_mfma(const void* q, void* out, int n_q, int tok_begin, int rows,
                                  const KvView& kv, hipStream_t st, int variant = 0);
 
+bool decode_attention_mfma_supported(int dtype, int head_dim, int page_tokens, int r);
+hipError_t launch_decode_attention_mfma(const float* q, float* part, int n_q, int n_keys, int tiles_per_split,
+                                        int n_splits, const KvView& kv, hipStream_t st);
+
 // ---- first-token step (one row of activations: matrix-vector products, one-token attention) ----
 // out[n] (mode 0: =, 1: +=) sum_k x[k] w[n][k]; mode 2: out[n] = silu(x.w[n]) * (x.w2[n]).  x, out float32.
 hipError_t launch_gemv(int dtype, int mode, const float* x, const void* w, const void* w2, float* out,
@@ -54,8 +58,9 @@ hipError_t launch_gemv(int dtype, int mode, const float* x, const void* w, const
 hipError_t launch_rope_token(const float* qin, float* qout, int n_heads, int head_dim, int pos,
                              float theta, hipStream_t st);
 size_t decode_attention_workspace_bytes(int n_q, int head_dim);
+// generic_only: keep to the vector-ALU kernel (testing)
 hipError_t launch_decode_attention(int dtype, const float* q, float* out, float* part, int n_q,
-                                   int n_keys, const KvView& kv, hipStream_t st);
+                                   int n_keys, const KvView& kv, hipStream_t st, bool generic_only = false);
 hipError_t launch_argmax(const float* v, int n, int32_t* result, hipStream_t st);
 
 }  // namespace cake

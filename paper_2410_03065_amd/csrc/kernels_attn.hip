@@ -645,6 +645,165 @@ attention_mfma8_kernel(const bf16_t* __restrict__ q, bf16_t* __restrict__ out, i
     }
 }
 
+// =====================================================================================
+// One-token attention on the matrix cores (first-token step; bf16 pages, head_dim 128).
+//
+// The "queries" of a workgroup are the r query heads that share KV head g, all at the same
+// position; they fill r of the 32 columns of the same transposed products as above
+// (S^T = K Q^T, O^T = V^T P^T), the other columns stay zero.  That wastes most of the MFMA
+// columns, which is free here: the kernel is bound by streaming the layer's K and V once, and
+// one 32-wide MFMA step consumes 1 KB of them.  There is no reuse between waves, so nothing is
+// staged in LDS: every lane loads its MFMA operand slices straight from the pages (K row
+// sigma16-permuted as above, V^T row = head-dim index), a wave has the V^T tile of this step
+// and the K tile of the next in flight while it works, and the four waves of a workgroup take
+// the key tiles of the workgroup's range in turn.  Partial (max, sum, O) per wave are merged
+// through LDS and written per key range for the combine kernel.
+// =====================================================================================
+__global__ void __launch_bounds__(256)
+decode_attention_mfma_kernel(const float* __restrict__ q, float* __restrict__ part, int n_q, int n_keys,
+                             int tiles_per_split, KvView kv) {
+    extern __shared__ float dlds[];   // [4][r][AHD + 2]: O, then max (natural-log units), then sum
+    const int g = blockIdx.x, split = blockIdx.y, n_splits = gridDim.y;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    const int r = n_q / kv.n_kv;
+    const int pt = kv.page_tokens;
+    const int n_tiles = (n_keys + AK - 1) / AK;
+    const int tile_lo = split * tiles_per_split, tile_hi = min(tile_lo + tiles_per_split, n_tiles);
+    const float sl2 = 0.08838834764831845f * 1.4426950408889634f;
+
+    bf16x8 qB[AHD / 16];
+#pragma unroll
+    for (int ks = 0; ks < AHD / 16; ++ks)
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            qB[ks][e] = lrow < r ? bf16_t(q[size_t(g * r + lrow) * AHD + 16 * ks + 8 * lhalf + e] * sl2) : bf16_t(0.f);
+
+    const int krow = 16 * (lrow >> 4) + sigma16(lrow & 15);
+    const size_t layer_base = size_t(kv.layer) * kv.n_physical_pages;
+    bf16x8 kA[2][AHD / 16], vA[4][4];
+    auto tile_page = [&](int tile, int* in_page0) {
+        const int key0 = tile * AK, lpage = key0 / pt;
+        *in_page0 = key0 - lpage * pt;
+        return (const bf16_t*)kv.pool + (layer_base + kv.block_table[lpage]) * kv.page_elems();
+    };
+    auto load_k = [&](int tile) {
+        int in_page0;
+        const bf16_t* kp = tile_page(tile, &in_page0) + (size_t(g) * pt + in_page0) * AHD + 8 * lhalf;
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int ks = 0; ks < AHD / 16; ++ks) kA[t][ks] = *(const bf16x8*)(kp + size_t(32 * t + krow) * AHD + 16 * ks);
+    };
+    auto load_v = [&](int tile) {
+        int in_page0;
+        const bf16_t* vp = tile_page(tile, &in_page0) + size_t(kv.n_kv) * pt * AHD + size_t(g) * AHD * pt + in_page0 + 8 * lhalf;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) vA[dt][c] = *(const bf16x8*)(vp + size_t(32 * dt + lrow) * pt + 16 * c);
+    };
+
+    f32x16 o[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[t][v] = 0.f;
+    float m_run = -1.0e30f, l_part = 0.f;   // finite start: exp2(-inf - m) of a masked key is 0, never NaN
+    const f32x16 zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+
+    int tile = tile_lo + wave;
+    if (tile < tile_hi) load_k(tile);
+    for (; tile < tile_hi; tile += 4) {
+        load_v(tile);
+        f32x16 s[2];
+#pragma unroll
+        for (int ks = 0; ks < AHD / 16; ++ks)
+#pragma unroll
+            for (int t = 0; t < 2; ++t) s[t] = mfma32(kA[t][ks], qB[ks], ks == 0 ? zero16 : s[t]);
+        if (tile + 4 < tile_hi) load_k(tile + 4);
+        if ((tile + 1) * AK > n_keys) {   // ragged last tile: keys past the prompt
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    if (tile * AK + 32 * t + 16 * (v >> 3) + 8 * lhalf + (v & 7) >= n_keys) s[t][v] = -INFINITY;
+        }
+        float mx = s[0][0];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[t][v]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m_run, mx);
+        const float corr = __builtin_amdgcn_exp2f(m_run - m_new);
+        m_run = m_new;
+        if (__builtin_amdgcn_ballot_w64(corr != 1.0f) != 0) {   // what was summed so far moves to the new reference
+            l_part *= corr;
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) o[t][v] *= corr;
+        }
+        bf16x8 pB[4];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const float x = __builtin_amdgcn_exp2f(s[t][v] - m_new);
+                l_part += x;
+                pB[2 * t + (v >> 3)][v & 7] = bf16_t(x);
+            }
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt) o[dt] = mfma32(vA[dt][c], pB[c], o[dt]);
+    }
+
+    // merge the four waves; column n of a wave belongs to query head g*r + n
+    const float l_tot = l_part + __shfl_xor(l_part, 32, 64);
+    if (lrow < r) {
+        float* w = dlds + size_t(wave * r + lrow) * (AHD + 2);
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) w[32 * dt + 8 * (v >> 2) + 4 * lhalf + (v & 3)] = o[dt][v];
+        if (lhalf == 0) { w[AHD] = m_run * 0.6931471805599453f; w[AHD + 1] = l_tot; }
+    }
+    __syncthreads();
+    for (int idx = tid; idx < r * AHD; idx += 256) {
+        const int j = idx / AHD, d = idx % AHD;
+        float m = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) m = fmaxf(m, dlds[size_t(w * r + j) * (AHD + 2) + AHD]);
+        float num = 0.f, den = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float* src = dlds + size_t(w * r + j) * (AHD + 2);
+            const float c = __expf(src[AHD] - m);
+            num += src[d] * c;
+            den += src[AHD + 1] * c;
+        }
+        float* dst = part + (size_t(g * r + j) * n_splits + split) * (AHD + 2);
+        dst[d] = num;
+        if (d == 0) { dst[AHD] = m; dst[AHD + 1] = den; }
+    }
+}
+
+bool decode_attention_mfma_supported(int dtype, int head_dim, int page_tokens, int r) {
+    return dtype == 1 && head_dim == AHD && page_tokens % AK == 0 && r >= 1 && r <= 32;
+}
+
+// Writes n_splits partial results per query head into `part` ([n_q][n_splits][head_dim + 2]).
+hipError_t launch_decode_attention_mfma(const float* q, float* part, int n_q, int n_keys, int tiles_per_split,
+                                        int n_splits, const KvView& kv, hipStream_t st) {
+    const int r = n_q / kv.n_kv;
+    const size_t lds = size_t(4) * r * (AHD + 2) * sizeof(float);
+    hipLaunchKernelGGL(decode_attention_mfma_kernel, dim3(kv.n_kv, n_splits), dim3(256), lds, st, q, part, n_q, n_keys,
+                       tiles_per_split, kv);
+    return hipGetLastError();
+}
+
 bool attention_mfma_supported(int head_dim, int page_tokens) {
     return head_dim == AHD && page_tokens % AK == 0;
 }

@@ -25,19 +25,34 @@ __device__ __forceinline__ float wmax(float v) {
     return v;
 }
 
+// Sum over aligned groups of W lanes (W = 8, 16 or 32), result in every lane of the group.  The
+// steps inside a row of 16 lanes are DPP moves fused into the add (no LDS traffic): swap
+// neighbours, swap pairs, mirror the half row, mirror the row.
+template <int W>
+__device__ __forceinline__ float group_sum(float v) {
+    static_assert(W == 8 || W == 16 || W == 32, "group width");
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true));  // row_half_mirror
+    if (W >= 16) v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, true));  // row_mirror
+    if (W >= 32) v += __shfl_xor(v, 16, 64);
+    return v;
+}
+
 // 16 bytes of T -> floats
 template <typename T> struct Ld16;
 template <> struct Ld16<float> {
     static constexpr int N = 4;
-    static __device__ __forceinline__ void load(const float* p, float* o) {
-        const float4 v = *(const float4*)p;
-        o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
+    static __device__ __forceinline__ uint4 raw(const float* p) { return *(const uint4*)p; }
+    static __device__ __forceinline__ void unpack(const uint4& v, float* o) {
+        o[0] = __uint_as_float(v.x); o[1] = __uint_as_float(v.y); o[2] = __uint_as_float(v.z); o[3] = __uint_as_float(v.w);
     }
+    static __device__ __forceinline__ void load(const float* p, float* o) { unpack(raw(p), o); }
 };
 template <> struct Ld16<bf16_t> {
     static constexpr int N = 8;
-    static __device__ __forceinline__ void load(const bf16_t* p, float* o) {
-        const uint4 v = *(const uint4*)p;
+    static __device__ __forceinline__ uint4 raw(const bf16_t* p) { return *(const uint4*)p; }
+    static __device__ __forceinline__ void unpack(const uint4& v, float* o) {
         const unsigned w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -45,6 +60,7 @@ template <> struct Ld16<bf16_t> {
             o[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
         }
     }
+    static __device__ __forceinline__ void load(const bf16_t* p, float* o) { unpack(raw(p), o); }
 };
 
 }  // namespace
@@ -136,7 +152,7 @@ hipError_t launch_rope_token(const float* qin, float* qout, int n_heads, int hea
 constexpr int DEC_MAX_SPLITS = 128;
 
 template <typename T, int HD, int R>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256, 2)
 decode_attention_kernel(const float* __restrict__ q, float* __restrict__ part, int n_keys, int tiles_per_split,
                         KvView kv) {
     constexpr int E = Ld16<T>::N;
@@ -155,11 +171,6 @@ decode_attention_kernel(const float* __restrict__ q, float* __restrict__ part, i
 
     const int ksub = lane % KL, kq = lane / KL;
     const int vsub = lane % VL, vq = lane / VL;
-    float qreg[R][E];
-#pragma unroll
-    for (int j = 0; j < R; ++j)
-#pragma unroll
-        for (int e = 0; e < E; ++e) qreg[j][e] = q[size_t(g * R + j) * HD + ksub * E + e] * scale;
     float o_acc[R][NVI];
     float m_run[R], l_run[R];
 #pragma unroll
@@ -182,23 +193,36 @@ decode_attention_kernel(const float* __restrict__ q, float* __restrict__ part, i
             in_page0 = key0 - lpage * pt;
             page = (const T*)kv.pool + (layer_base + kv.block_table[lpage]) * kv.page_elems();
         }
+        // every K load of the tile is issued before the first is used (16 KB in flight together, not
+        // one 1 KB round trip after another); the V^T loads go out as soon as the scores are formed,
+        // so they fly during the softmax.  Registers are kept under 256 so two waves share a SIMD.
+        uint4 kraw[NQI], vraw[NVI];
         if (have) {
             const T* kp = page + (size_t(g) * pt + in_page0) * HD;
-#pragma unroll 4
+            const T* vp = page + size_t(kv.n_kv) * pt * HD + size_t(g) * HD * pt + in_page0;
+#pragma unroll
+            for (int it = 0; it < NQI; ++it) kraw[it] = Ld16<T>::raw(kp + size_t(it * KPI + kq) * HD + ksub * E);
+            float qreg[R][E];   // this lane's slice of the group's queries (L1-resident after the first tile)
+#pragma unroll
+            for (int j = 0; j < R; ++j)
+#pragma unroll
+                for (int e = 0; e < E; ++e) qreg[j][e] = q[size_t(g * R + j) * HD + ksub * E + e] * scale;
+#pragma unroll
             for (int it = 0; it < NQI; ++it) {
                 const int kt = it * KPI + kq;
                 float kf[E];
-                Ld16<T>::load(kp + size_t(kt) * HD + ksub * E, kf);
+                Ld16<T>::unpack(kraw[it], kf);
 #pragma unroll
                 for (int j = 0; j < R; ++j) {
                     float d = 0.f;
 #pragma unroll
                     for (int e = 0; e < E; ++e) d = __builtin_fmaf(kf[e], qreg[j][e], d);
-#pragma unroll
-                    for (int o = KL / 2; o > 0; o >>= 1) d += __shfl_xor(d, o, 64);
+                    d = group_sum<KL>(d);
                     if (ksub == 0) sc[wave][j][kt] = d;
                 }
             }
+#pragma unroll
+            for (int it = 0; it < NVI; ++it) vraw[it] = Ld16<T>::raw(vp + size_t(it * RPI + vq) * pt + vsub * E);
         }
         __syncthreads();
         float corr[R], pl[R][E];
@@ -221,19 +245,16 @@ decode_attention_kernel(const float* __restrict__ q, float* __restrict__ part, i
             for (int j = 0; j < R; ++j)
 #pragma unroll
                 for (int e = 0; e < E; ++e) pl[j][e] = sc[wave][j][vsub * E + e];
-            const T* vp = page + size_t(kv.n_kv) * pt * HD + size_t(g) * HD * pt + in_page0;
 #pragma unroll
             for (int it = 0; it < NVI; ++it) {
-                const int drow = it * RPI + vq;
                 float vf[E];
-                Ld16<T>::load(vp + size_t(drow) * pt + vsub * E, vf);
+                Ld16<T>::unpack(vraw[it], vf);
 #pragma unroll
                 for (int j = 0; j < R; ++j) {
                     float d = 0.f;
 #pragma unroll
                     for (int e = 0; e < E; ++e) d = __builtin_fmaf(vf[e], pl[j][e], d);
-#pragma unroll
-                    for (int o = VL / 2; o > 0; o >>= 1) d += __shfl_xor(d, o, 64);
+                    d = group_sum<VL>(d);
                     o_acc[j][it] = o_acc[j][it] * corr[j] + d;
                 }
             }
@@ -309,18 +330,23 @@ static hipError_t decode_launch_r(int r, dim3 grid, hipStream_t st, const float*
 }
 
 // q[n_q][hd] (float32, rotated) against keys [0, n_keys) of the layer; out[n_q][hd] float32.
-// `part` must hold decode_attention_workspace_bytes().
+// `part` must hold decode_attention_workspace_bytes().  bf16 pages with head_dim 128 go to the
+// MFMA kernel (one workgroup per CU, each wave streaming its own tiles); everything else to the
+// vector-ALU kernel above.
 hipError_t launch_decode_attention(int dtype, const float* q, float* out, float* part, int n_q, int n_keys,
-                                   const KvView& kv, hipStream_t st) {
+                                   const KvView& kv, hipStream_t st, bool generic_only) {
     if (n_keys <= 0 || n_q % kv.n_kv) return hipErrorInvalidValue;
     const int r = n_q / kv.n_kv;
-    const int splits = decode_attention_splits(n_keys, kv.n_kv);
     const int n_tiles = (n_keys + 63) / 64;
+    const bool mfma = !generic_only && decode_attention_mfma_supported(dtype, kv.head_dim, kv.page_tokens, r);
+    int splits = mfma ? std::max(1, std::min({256 / std::max(1, kv.n_kv), (n_tiles + 3) / 4, DEC_MAX_SPLITS}))
+                      : decode_attention_splits(n_keys, kv.n_kv);
     const int tps = (n_tiles + splits - 1) / splits;
     const int used = (n_tiles + tps - 1) / tps;   // every launched split owns at least one tile
     dim3 grid(kv.n_kv, used);
     hipError_t e;
-    if (dtype == 0 && kv.head_dim == 64) e = decode_launch_r<float, 64>(r, grid, st, q, part, n_keys, tps, kv);
+    if (mfma) e = launch_decode_attention_mfma(q, part, n_q, n_keys, tps, used, kv, st);
+    else if (dtype == 0 && kv.head_dim == 64) e = decode_launch_r<float, 64>(r, grid, st, q, part, n_keys, tps, kv);
     else if (dtype == 0 && kv.head_dim == 128) e = decode_launch_r<float, 128>(r, grid, st, q, part, n_keys, tps, kv);
     else if (dtype == 1 && kv.head_dim == 64) e = decode_launch_r<bf16_t, 64>(r, grid, st, q, part, n_keys, tps, kv);
     else if (dtype == 1 && kv.head_dim == 128) e = decode_launch_r<bf16_t, 128>(r, grid, st, q, part, n_keys, tps, kv);

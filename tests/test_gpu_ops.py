@@ -172,3 +172,38 @@ def test_attention_and_page_write_above_2_and_4_gib():
     held = ostore.unpack_store(eng.pool_raw(T).view(np.uint16), T, nkv, hd, pt, "bf16")
     want = otf.attention(q64, held.k[0], held.v[0], pos, pos)
     assert _rel(got, want) < 1.2e-2
+
+
+@pytest.mark.parametrize("kind,path,shape_kw,T,pt", [
+    ("bf16", 0, dict(n_q=8, n_kv=2), 40000, 256),     # GQA 4:1, 625 key tiles: several tiles per wave, ragged tail
+    ("bf16", 0, dict(n_q=8, n_kv=1), 9001, 64),       # GQA 8:1, small pages
+    ("bf16", 0, dict(n_q=4, n_kv=4), 70, 128),        # MHA, two tiles
+    ("bf16", 1, dict(n_q=8, n_kv=2), 5000, 256),      # vector-ALU kernel on the same layout
+    ("f32", 0, dict(n_q=4, n_kv=4), 3000, 128),       # float32 pages, head_dim 64
+    ("f32", 0, dict(n_q=4, n_kv=2), 130, 64),
+])
+def test_decode_attention(kind, path, shape_kw, T, pt):
+    """One query per head against T cached keys (first-token step), both kernels."""
+    import torch
+    import paper_2410_03065_amd as cake
+    base = SHAPE_F32 if kind == "f32" else SHAPE_BF
+    shape = base.with_(vocab=64, n_layers=1, **shape_kw)
+    w = si.make_weights(shape, seed=0, with_head=True)
+    n_log = (T + pt - 1) // pt
+    bt = np.random.default_rng(5).permutation(n_log).astype(np.int32)
+    eng = cake.Engine(shape, w, max_tokens=n_log * pt, max_chunk=min(256, n_log * pt), page_tokens=pt, block_table=bt)
+    eng.set_tuning(kernel_path=path)
+    rng = np.random.default_rng(T)
+    nq, nkv, hd = shape.n_q, shape.n_kv, shape.head_dim
+    cache = otf.KVCache(1, T, nkv, hd)
+    cache.k[0] = rng.standard_normal((T, nkv, hd)) * 1.5
+    cache.v[0] = rng.standard_normal((T, nkv, hd))
+    cache = _rounded(cache, kind)
+    eng.set_store(ostore.pack_store(cache, pt, kind))
+    eng.load_chunk(0, T)
+    q = rng.standard_normal((nq, hd)).astype(np.float32) * 2
+    got = eng.op_decode_attention(torch.from_numpy(q).cuda(), 0, T).cpu().numpy()
+    want = otf.attention(q.astype(np.float64)[None], cache.k[0], cache.v[0], np.array([T - 1]), np.arange(T))[0]
+    # MFMA path: q and the probabilities are rounded to bf16 (2^-9 each); others are float32 throughout
+    tol = 1.2e-2 if (kind == "bf16" and path == 0) else 2e-5
+    assert _rel(got, want) < tol, _rel(got, want)
