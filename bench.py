@@ -146,6 +146,17 @@ def main():
                                  "gbs": round(st["bytes"] / st["total_ns"], 1),
                                  "frac_of_hbm_peak": round(st["bytes"] / st["total_ns"] / PEAK_HBM_GBS, 3)}
 
+    # fetch unit of one page (finer than the compute chunk): the adaptive engine with this request alone
+    fine = None
+    if pt < C:
+        reqs = [dict(tokens=toks, arrival_ns=0, prefix=True)]
+        eng.adaptive_serve(reqs, C, pt, args.gbps)
+        fr = [eng.adaptive_serve(reqs, C, pt, args.gbps) for _ in range(2)]
+        fine = {"fetch_unit_tokens": pt, "compute_step_tokens": C,
+                "ttft_s": round(float(np.mean([f[0].ttft_ns for f in fr])) / 1e9, 5),
+                "tokens_computed": [f[1][0]["tokens_computed"] for f in fr],
+                "tokens_loaded": [f[1][0]["tokens_loaded"] for f in fr]}
+
     r_c = eng.bidirectional_prefill(toks, C, args.gbps, mode="compute_only")
     r_l = eng.bidirectional_prefill(toks, C, args.gbps, mode="load_only")
 
@@ -201,6 +212,7 @@ def main():
                       "achieved_load_only": round(r_l.achieved_gbps, 4), "kv_bytes": kv_bytes},
         "kernels": kernels,
         "first_token": dict(first_token, ttft_to_first_token_s=round(ttft + ft_wall, 5)),
+        "fine_fetch_unit": fine,
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:

@@ -143,6 +143,10 @@ typedef struct {
     int32_t f_off;   /* tokens of chunk f already claimed by compute before this look (0 unless steps are
                         smaller than a chunk); when > 0 chunk f is compute's and the plan covers [f+1, b]
                         with partial_ns added to the compute offset */
+    int32_t claimed_tokens; /* tokens this claim covers (0 on a wait; 0 from cake_simulate_race, which has no
+                               token ranges): a compute step may span several chunks when the chunks are
+                               fetch units smaller than the step, starting at token f_off of chunk `claimed` */
+    int32_t pad_;
     uint64_t now_ns;
     uint64_t o_c, o_l;                            /* predicted remaining ns of the work in flight on each side */
     uint64_t est_compute_ns, est_compute_flops;   /* throughput sample: last <= 4 computed chunks, or the prior */

@@ -290,6 +290,23 @@ def fill_token_budget(budget: int, n_decoding: int, nonprefix_remaining: Sequenc
     return dec, grants, min(left, prefix_offer)
 
 
+def front_claim(f: int, f_off: int, b: int, m_star: int, max_tokens: int, tok_count: Sequence[int]):
+    """Token-granular claim of the compute side (adaptive mode, Sec. 4 Part 3, with fetch units
+    smaller than a compute step, Sec. 5.1 "Implementation"): take consecutive tokens from token
+    ``f_off`` of chunk ``f`` on, whole chunks and at last a part of one, until ``max_tokens`` are
+    taken, the unclaimed range [f, b] ends, or the next chunk is at or past the meet point.
+    Returns (tokens, f after, f_off after)."""
+    got = 0
+    while f <= b and f < m_star and got < max_tokens:
+        take = min(tok_count[f] - f_off, max_tokens - got)
+        got += take
+        f_off += take
+        if f_off < tok_count[f]:
+            break
+        f, f_off = f + 1, 0
+    return got, f, f_off
+
+
 def expected_meet_point(f: int, b: int, f_off: int, o_c: int, o_l: int, partial_ns: int,
                         est: Estimator, chunk_flops: Sequence[int], chunk_bytes: Sequence[int]) -> int:
     """The split a planned look at the range [f, b] must log.  When the compute side has

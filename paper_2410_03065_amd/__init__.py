@@ -74,7 +74,8 @@ class ChunkLog(C.Structure):
 
 class DecisionLog(C.Structure):
     _fields_ = [("who", C.c_int32), ("f", C.c_int32), ("b", C.c_int32), ("m_star", C.c_int32),
-                ("claimed", C.c_int32), ("f_off", C.c_int32), ("now_ns", C.c_uint64), ("o_c", C.c_uint64),
+                ("claimed", C.c_int32), ("f_off", C.c_int32), ("claimed_tokens", C.c_int32), ("pad_", C.c_int32),
+                ("now_ns", C.c_uint64), ("o_c", C.c_uint64),
                 ("o_l", C.c_uint64), ("est_compute_ns", C.c_uint64), ("est_compute_flops", C.c_uint64),
                 ("est_load_ns", C.c_uint64), ("est_load_bytes", C.c_uint64), ("partial_ns", C.c_uint64)]
 

@@ -458,6 +458,7 @@ int32_t cake_bidirectional_prefill(cake_ctx* c, const int32_t* token_ids, int32_
     ex.core.est.prior_l_bytes = gbps > 0 ? uint64_t(gbps * 1e9) : 4000000000ull;
     if (ex.core.est.prior_l_bytes == 0) ex.core.est.prior_l_bytes = 1;
     ex.core.init(n, flops.data(), bytes.data(), mode, forced_m);
+    ex.core.tok_begin = tb.data(); ex.core.tok_count = tc.data(); ex.core.model = &c->m;
     ex.core.log = res->decisions;
     ex.core.log_cap = res->decisions ? res->decisions_cap : 0;
     ex.status = c->status.get();

@@ -10,6 +10,7 @@
 // Everything here is integer arithmetic on logged inputs, so every decision can
 // be replayed exactly by an independent implementation.
 #pragma once
+#include <algorithm>
 #include <cstddef>
 #include <cstdint>
 #include <vector>
@@ -185,11 +186,12 @@ struct RaceCore {
         return p;
     }
 
-    void record(int who, uint64_t now, const Plan& p, int f0, int b0, int off0, int claim) {
+    void record(int who, uint64_t now, const Plan& p, int f0, int b0, int off0, int claim, int claim_tokens) {
         if (!log) return;
         if (log_n < log_cap) {
             cake_decision_log& d = log[log_n++];
             d.who = who; d.f = f0; d.b = b0; d.m_star = p.m_star; d.claimed = claim; d.f_off = off0;
+            d.claimed_tokens = claim_tokens; d.pad_ = 0;
             d.now_ns = now; d.o_c = p.oc; d.o_l = p.ol;
             d.est_compute_ns = p.D; d.est_compute_flops = p.F; d.est_load_ns = p.LN; d.est_load_bytes = p.LB;
             d.partial_ns = p.partial;
@@ -201,17 +203,19 @@ struct RaceCore {
     int decide(int who, uint64_t now) {
         if (f > b || w[who].retired || w[who].busy) return -1;
         const Plan p = plan(who, now);
-        int f0 = f, b0 = b, off0 = f_off, claim = -1;
+        int f0 = f, b0 = b, off0 = f_off, claim = -1, claim_tokens = 0;
         uint64_t cost = 0;
         if (who == W_COMPUTE && f < p.m_star) {
             cost = f_off > 0 ? p.partial : est.est_compute(flops[f]);
+            if (tok_count) claim_tokens = tok_count[f] - f_off;
             claim = f++;
             f_off = 0;
         } else if (who == W_LOAD && b >= p.m_star && !(b == f && f_off > 0)) {
             cost = est.est_load(bytes[b]);
+            if (tok_count) claim_tokens = tok_count[b];
             claim = b--;
         }
-        record(who, now, p, f0, b0, off0, claim);
+        record(who, now, p, f0, b0, off0, claim, claim_tokens);
         if (claim >= 0) {
             Worker& me = w[who];
             me.busy = true; me.inflight = claim; me.started = now;
@@ -220,9 +224,10 @@ struct RaceCore {
         return claim;
     }
 
-    // Compute side, token granular: claims up to max_tokens tokens from the front of the range,
-    // never past the planned meet point and never past the end of chunk f.  Returns the number of
-    // tokens claimed (0 = wait) and their first token.  The compute worker is marked busy until
+    // Compute side, token granular: claims up to max_tokens consecutive tokens from the front of the
+    // range, over as many chunks as that takes (the chunks here may be fetch units much smaller than
+    // a compute step) but never into a chunk at or past the planned meet point.  Returns the number
+    // of tokens claimed (0 = wait) and their first token.  The compute worker is marked busy until
     // complete_front().
     int claim_front(uint64_t now, int max_tokens, int* first_token) {
         if (f > b || w[W_COMPUTE].retired || w[W_COMPUTE].busy || max_tokens <= 0) return 0;
@@ -230,16 +235,19 @@ struct RaceCore {
         const int f0 = f, b0 = b, off0 = f_off;
         int got = 0;
         if (f < p.m_star) {
-            got = tok_count[f] - f_off;
-            if (got > max_tokens) got = max_tokens;
             *first_token = tok_begin[f] + f_off;
+            while (f <= b && f < p.m_star && got < max_tokens) {
+                const int take = std::min(tok_count[f] - f_off, max_tokens - got);
+                got += take;
+                f_off += take;
+                if (f_off < tok_count[f]) break;
+                ++f; f_off = 0;
+            }
             Worker& me = w[W_COMPUTE];
-            me.busy = true; me.inflight = f; me.started = now;
+            me.busy = true; me.inflight = f0; me.started = now;
             me.pred_end = sat_add(now, est.est_compute(range_flops(*model, *first_token, got)));
-            f_off += got;
-            if (f_off == tok_count[f]) { ++f; f_off = 0; }
         }
-        record(W_COMPUTE, now, p, f0, b0, off0, got > 0 ? f0 : -1);
+        record(W_COMPUTE, now, p, f0, b0, off0, got > 0 ? f0 : -1, got);
         return got;
     }
 

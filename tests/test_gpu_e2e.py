@@ -34,15 +34,19 @@ def _setup(shape, T, C, pt, seed=0, scramble=False, std=0.02):
     return w, toks, eng
 
 
-def _check_decisions(res, shape, T, C, pt):
-    """Every logged look at the range is the brute-force optimum of its own logged inputs."""
+def _check_decisions(res, shape, T, C, pt, step_tokens=None):
+    """Every logged look at the range is the brute-force optimum of its own logged inputs, and every
+    claim is what the oracle's rules give for that look.  C is the chunk of the plan (the fetch unit
+    when that is smaller than a compute step); step_tokens, if given, is the compute step every
+    claim had available (a request alone on the GPU), else claims are only bounded from above."""
     n = (T + C - 1) // C
     flops = [mp.range_flops(shape.n_layers, shape.d_model, shape.n_q, shape.n_kv, shape.head_dim, shape.ffn,
                             i * C, min((i + 1) * C, T)) for i in range(n)]
     per_page = pt * otf.kv_bytes_per_token(shape.n_layers, shape.n_kv, shape.head_dim, shape.elem_bytes)
     byts = [((min((i + 1) * C, T) - i * C + pt - 1) // pt) * per_page for i in range(n)]
+    tok_count = [min((i + 1) * C, T) - i * C for i in range(n)]
     assert len(res.decisions) > 0
-    claimed = {0: [], 1: []}
+    computed, loaded = [], []
     for d in res.decisions:
         e = mp.Estimator(d["est_compute_ns"], d["est_compute_flops"], d["est_load_ns"], d["est_load_bytes"])
         assert d["m_star"] == mp.expected_meet_point(d["f"], d["b"], d["f_off"], d["o_c"], d["o_l"], d["partial_ns"],
@@ -52,13 +56,25 @@ def _check_decisions(res, shape, T, C, pt):
             rest = mp.range_flops(shape.n_layers, shape.d_model, shape.n_q, shape.n_kv, shape.head_dim, shape.ffn,
                                   t0, min((d["f"] + 1) * C, T))
             assert d["partial_ns"] == e.est_compute(rest), d
-        loader_may = d["b"] >= d["m_star"] and not (d["b"] == d["f"] and d["f_off"] > 0)
-        want_claim = d["f"] if (d["who"] == 0 and d["f"] < d["m_star"]) else d["b"] if (d["who"] == 1 and loader_may) else -1
-        assert d["claimed"] == want_claim, d
-        if d["claimed"] >= 0:
-            claimed[d["who"]].append(d["claimed"])
+        if d["who"] == 0:
+            avail, _, _ = mp.front_claim(d["f"], d["f_off"], d["b"], d["m_star"], 10 ** 9, tok_count)
+            if avail == 0:
+                assert d["claimed"] == -1 and d["claimed_tokens"] == 0, d
+                continue
+            assert d["claimed"] == d["f"], d
+            if step_tokens is not None:
+                assert d["claimed_tokens"] == mp.front_claim(d["f"], d["f_off"], d["b"], d["m_star"], step_tokens, tok_count)[0], d
+            assert 0 < d["claimed_tokens"] <= avail, d
+            _, f2, off2 = mp.front_claim(d["f"], d["f_off"], d["b"], d["m_star"], d["claimed_tokens"], tok_count)
+            computed += list(range(d["f"], f2 + (1 if off2 > 0 else 0)))
+        else:
+            loader_may = d["b"] >= d["m_star"] and not (d["b"] == d["f"] and d["f_off"] > 0)
+            assert d["claimed"] == (d["b"] if loader_may else -1), d
+            assert d["claimed_tokens"] == (tok_count[d["b"]] if loader_may else 0), d
+            if loader_may:
+                loaded.append(d["claimed"])
     m = res.meet_point
-    assert sorted(set(claimed[0])) == list(range(m)) and claimed[1] == list(range(n - 1, m - 1, -1))
+    assert sorted(set(computed)) == list(range(m)) and loaded == list(range(n - 1, m - 1, -1))
     assert [c["source"] for c in res.chunks] == [0] * m + [1] * (n - m)
     for c, fl, by in zip(res.chunks, flops, byts):
         assert c["work"] == (fl if c["source"] == 0 else by)
@@ -418,3 +434,42 @@ def test_first_token_needs_head_weights():
     with pytest.raises(cake.CakeError) as e:
         eng.first_token(toks)
     assert e.value.code == cake.E_STATE
+
+
+# --------------------------------------------------------------------------- fetch unit finer than the compute step
+@pytest.mark.parametrize("shape,T,step,unit", [
+    (BF_NARROW_GQA4, 4096 + 300, 1024, 128),      # ragged prompt, 35 fetch units, 8 units per compute step
+    (BF_NARROW_MHA, 3072, 512, 256),
+])
+def test_fetch_unit_smaller_than_compute_step(shape, T, step, unit):
+    """Sec. 5.1 "Implementation": the fetch granularity is decoupled from the compute chunk.  The
+    request runs alone through the adaptive engine: compute steps of `step` tokens span several
+    fetch units, the loader claims single units, and the two sides meet on a unit boundary."""
+    import paper_2410_03065_amd as cake
+    pt = unit
+    w = si.make_weights(shape, seed=50)
+    toks = si.make_tokens(T, shape.vocab, seed=51)
+    eng = cake.Engine(shape, w, max_tokens=((T + pt - 1) // pt) * pt, max_chunk=step, page_tokens=pt)
+    ref = otf.prefill_chunked(w, shape, toks, step, kv_dtype="bf16")
+    images = ostore.pack_store(ref, pt, "bf16")
+    want = ostore.decode_words(images, "bf16")
+    eng.set_store(images)
+    eng.bidirectional_prefill(toks, step, 4.0, mode="compute_only")
+    r_c = eng.bidirectional_prefill(toks, step, 4.0, mode="compute_only")
+    kv_bytes = T * otf.kv_bytes_per_token(shape.n_layers, shape.n_kv, shape.head_dim, 2)
+    rate = kv_bytes / r_c.ttft_ns            # the tier delivers as fast as this GPU computes: meet near the middle
+    reqs = [dict(tokens=toks, arrival_ns=0, prefix=True)]
+    eng.clear_pool()
+    res, per_req, steps = eng.adaptive_serve(reqs, step, unit, rate)
+    n_units = (T + unit - 1) // unit
+    m = res.meet_point
+    assert res.n_chunks == n_units and 0 < m < n_units
+    assert per_req[0]["tokens_computed"] == m * unit and per_req[0]["tokens_loaded"] == T - m * unit
+    assert _errs(eng.pool_images(T), want).max() < TOL["bf16"]
+    np.testing.assert_array_equal(eng.pool_raw(T)[m:].view(np.uint16), images[m:])          # loaded units = stored bytes
+    _check_decisions(res, shape, T, unit, pt, step_tokens=step)
+    # compute steps really spanned several units, and the last one stopped at the loader's boundary
+    comp = [d for d in res.decisions if d["who"] == 0 and d["claimed_tokens"] > 0]
+    assert max(d["claimed_tokens"] for d in comp) == step
+    assert sum(d["claimed_tokens"] for d in comp) == m * unit
+    assert all(s["prefix_tokens"] <= step for s in steps)

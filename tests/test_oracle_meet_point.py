@@ -200,3 +200,31 @@ def test_expected_meet_point_with_a_partial_chunk():
     # 4 tokens-worth of chunk 0 already taken: chunk 0 is compute's, 6 ns of it left
     assert mp.expected_meet_point(0, 3, 4, 0, 0, 6, est, c, l) == 1 + mp.brute_force_meet_point(c[1:], l[1:], 6, 0)[0]
     assert mp.expected_meet_point(3, 3, 1, 0, 0, 5, est, c, l) == 4          # nothing left for the loader
+
+
+def test_front_claim_rule():
+    """Hand-worked claims over fetch units of 128 tokens (the last one ragged)."""
+    tc = [128, 128, 128, 128, 100]
+    assert mp.front_claim(0, 0, 4, 5, 300, tc) == (300, 2, 44)        # two whole units and 44 tokens of the third
+    assert mp.front_claim(2, 44, 4, 5, 300, tc) == (300, 4, 88)       # 84 + 128 + 88 of the ragged last unit
+    assert mp.front_claim(2, 44, 4, 5, 84, tc) == (84, 3, 0)          # exactly the rest of a unit
+    assert mp.front_claim(0, 0, 4, 2, 1000, tc) == (256, 2, 0)        # stops at the meet point
+    assert mp.front_claim(0, 0, 1, 5, 1000, tc) == (256, 2, 0)        # stops where the unclaimed range ends
+    assert mp.front_claim(3, 0, 4, 5, 1000, tc) == (228, 5, 0)        # ragged tail
+    assert mp.front_claim(2, 0, 4, 2, 1000, tc) == (0, 2, 0)          # nothing before the meet point: wait
+    assert mp.front_claim(1, 5, 4, 1, 10, tc) == (0, 1, 5)            # meet point at f: the rest of f waits for the plan
+    # a claim never exceeds the step, and consecutive claims tile the computed prefix exactly
+    rng = np.random.default_rng(0)
+    for _ in range(200):
+        n = int(rng.integers(1, 12))
+        tcs = [int(rng.integers(1, 9)) * 64 for _ in range(n)]
+        m = int(rng.integers(0, n + 1))
+        step = int(rng.integers(1, 20)) * 32
+        f = off = total = 0
+        while True:
+            got, f, off = mp.front_claim(f, off, n - 1, m, step, tcs)
+            assert got <= step
+            if got == 0:
+                break
+            total += got
+        assert total == sum(tcs[:m]) and (f, off) == (m, 0)
