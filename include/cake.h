@@ -267,8 +267,32 @@ typedef struct {
     int32_t prefix_tokens;      /* priority 3: what was left for the prefix-cached request */
     int32_t prefix_tok_begin;   /* first token of the prefix request's part, or -1 */
     int32_t first_nonprefix_req; /* index of the first non-prefix request served, or -1 */
-    int32_t pad_;
+    int32_t other_tokens;       /* taken off the top by the other-users trace (cake_set_traces), else 0 */
 } cake_step_log;
+
+/* Resource traces for the NEXT cake_adaptive_serve (copied; cleared when that call returns).
+ * other_tokens: the paper's measure of GPU utilisation (Sec. 5.1 "GPU Resource Utilization"): at
+ *   engine step k, other_tokens[k % n_other_tokens] tokens of the budget belong to other users
+ *   and the requests of the call share the rest (budget 512, other 256 = 50 % utilisation).  The
+ *   other users' share is really computed, as a prefill of that many of scratch_token_ids into
+ *   scratch_kv (pages of the same layout holding >= n_scratch_tokens tokens), so it costs the
+ *   GPU time it stands for.  Each entry <= n_scratch_tokens and <= the context's max_chunk.
+ * gbps: the tier's bandwidth over time (Sec. 5.6): sample gbps[(t / gbps_interval_ns) % n_gbps],
+ *   t since the call started, overrides the call's rate; samples below 0.01 GB/s count as 0.01.
+ * A NULL pointer / zero length leaves that resource constant.  traces == NULL clears both.
+ * Errors: CAKE_E_INVAL. */
+typedef struct {
+    const int32_t* other_tokens;
+    int32_t n_other_tokens;
+    int32_t n_scratch_tokens;
+    const cake_kv* scratch_kv;
+    const int32_t* scratch_token_ids; /* host */
+    const double* gbps;
+    int32_t n_gbps;
+    int32_t pad_;
+    uint64_t gbps_interval_ns;
+} cake_traces;
+int32_t cake_set_traces(cake_ctx* ctx, const cake_traces* traces);
 
 /* Serves a mix of requests on one GPU with the paper's adaptive mode: every engine step fills a
  * budget of `token_budget` tokens in the order decoding requests, chunked prefill of requests

@@ -31,7 +31,7 @@ EXPORTS = [
     "cake_range_flops", "cake_page_image_bytes", "cake_simulate_race", "cake_op_rmsnorm",
     "cake_op_gemm", "cake_op_gemm_residual", "cake_op_gemm_swiglu", "cake_op_rope_kv_write",
     "cake_op_attention", "cake_profile_enable", "cake_profile_read", "cake_adaptive_serve", "cake_first_token",
-    "cake_op_decode_attention",
+    "cake_op_decode_attention", "cake_set_traces",
 ]
 KERNEL_CLASSES = ["embed", "rmsnorm", "gemm_qkv", "rope_kv", "attention", "gemm_o", "gemm_gateup", "gemm_down",
                   "gemv", "decode_attention"]
@@ -89,7 +89,13 @@ class Request(C.Structure):
 class StepLog(C.Structure):
     _fields_ = [("start_ns", C.c_uint64), ("end_ns", C.c_uint64), ("decode_tokens", C.c_int32),
                 ("nonprefix_tokens", C.c_int32), ("prefix_tokens", C.c_int32), ("prefix_tok_begin", C.c_int32),
-                ("first_nonprefix_req", C.c_int32), ("pad_", C.c_int32)]
+                ("first_nonprefix_req", C.c_int32), ("other_tokens", C.c_int32)]
+
+
+class Traces(C.Structure):
+    _fields_ = [("other_tokens", C.c_void_p), ("n_other_tokens", C.c_int32), ("n_scratch_tokens", C.c_int32),
+                ("scratch_kv", C.c_void_p), ("scratch_token_ids", C.c_void_p), ("gbps", C.c_void_p),
+                ("n_gbps", C.c_int32), ("pad_", C.c_int32), ("gbps_interval_ns", C.c_uint64)]
 
 
 class Result(C.Structure):
@@ -130,6 +136,7 @@ def load_library():
         "cake_plan_meet_point": (i32, [vp, vp, i32, u64, u64, P(i32), P(u64)]),
         "cake_bidirectional_prefill": (i32, [vp, vp, i32, P(KvStore), i32, dbl, i32, i32, P(Kv), P(Result)]),
         "cake_first_token": (i32, [vp, vp, i32, P(Kv), P(i32), vp, P(u64)]),
+        "cake_set_traces": (i32, [vp, P(Traces)]),
         "cake_op_decode_attention": (i32, [vp, vp, vp, i32, i32, P(Kv)]),
         "cake_set_bandwidth": (i32, [vp, dbl]),
         "cake_schedule_bandwidth_step": (i32, [vp, i32, dbl]),
@@ -463,6 +470,27 @@ class Engine:
         self._tensors.append((bt_host, bt_dev, pool))
         return kv, pool
 
+    def set_traces(self, other_tokens=None, gbps_trace=None, gbps_interval_ns=0, scratch_seed=99):
+        """Resource traces of the next adaptive_serve (cake_set_traces): per-step tokens of other users,
+        bandwidth samples over time.  The scratch pages and ids for the other users' prefill are made here."""
+        t = Traces()
+        keep = []
+        if other_tokens is not None and len(other_tokens):
+            ot = np.ascontiguousarray(other_tokens, dtype=np.int32)
+            n_scr = max(int(ot.max()), 1)
+            if getattr(self, "_scratch", None) is None or self._scratch[2] < n_scr:
+                kv, pool = self.new_kv(n_scr)
+                self._scratch = (kv, pool, n_scr)
+            ids = np.random.default_rng(scratch_seed).integers(0, self.shape.vocab, n_scr).astype(np.int32)
+            t.other_tokens, t.n_other_tokens, t.n_scratch_tokens = ot.ctypes.data, len(ot), n_scr
+            t.scratch_kv, t.scratch_token_ids = C.addressof(self._scratch[0]), ids.ctypes.data
+            keep += [ot, ids]
+        if gbps_trace is not None and len(gbps_trace):
+            g = np.ascontiguousarray(gbps_trace, dtype=np.float64)
+            t.gbps, t.n_gbps, t.gbps_interval_ns = g.ctypes.data, len(g), int(gbps_interval_ns)
+            keep.append(g)
+        self._check(self.lib.cake_set_traces(self.ctx, C.byref(t)), "cake_set_traces")
+
     def adaptive_serve(self, requests, token_budget, fetch_chunk, gbps):
         """requests: list of dicts {tokens, arrival_ns, prefix (bool), kv (Kv or None = the engine's own)}.
         Returns (PrefillResult for the prefix request, per-request dicts, step list)."""
@@ -500,7 +528,7 @@ class Engine:
         out.decisions = _decisions_to_list(dec, res.n_decisions)
         per_req = [dict(ttft_ns=arr[i].ttft_ns, tokens_computed=arr[i].tokens_computed, tokens_loaded=arr[i].tokens_loaded)
                    for i in range(n)]
-        sk = [f[0] for f in StepLog._fields_ if f[0] != "pad_"]
+        sk = [f[0] for f in StepLog._fields_]
         step_list = [{k: getattr(steps[i], k) for k in sk} for i in range(ns.value)]
         return out, per_req, step_list
 

@@ -45,6 +45,12 @@ struct cake_ctx {
     std::atomic<double> gbps{0.0};
     int step_after = -1;
     double step_gbps = 0.0;
+    // traces for the next cake_adaptive_serve (copied by cake_set_traces)
+    std::vector<int32_t> tr_other, tr_ids;
+    std::vector<double> tr_gbps;
+    uint64_t tr_interval_ns = 0;
+    std::atomic<uint64_t> tr_t0{0};   // 0: no bandwidth trace running
+    cake_kv tr_kv{};
     cake_tuning tun{1000000000ull, 500000000000000ull, 4ull << 20, 0, 0, 0, 0};  // gemm_config 0 = automatic
     std::mutex err_mu;
     std::string err;
@@ -213,6 +219,18 @@ static void wait_until_ns(uint64_t deadline) {
     }
 }
 
+// The tier's rate right now: the bandwidth trace if one is running (never below 0.01 GB/s, so a
+// sample of zero slows the load down without stalling it for good), else the configured rate.
+static double live_rate(cake_ctx* c) {
+    const uint64_t t0 = c->tr_t0.load(std::memory_order_relaxed);
+    if (t0 && !c->tr_gbps.empty() && c->tr_interval_ns) {
+        const uint64_t now = mono_ns();
+        const size_t k = size_t(((now > t0 ? now - t0 : 0) / c->tr_interval_ns) % c->tr_gbps.size());
+        return std::max(c->tr_gbps[k], 0.01);
+    }
+    return c->gbps.load(std::memory_order_relaxed);
+}
+
 // fixed_gbps > 0: that rate; == 0: unthrottled; < 0: the context's live rate.
 static int enqueue_load(cake_ctx* c, const cake_kv_store* st, int tok_begin, int tok_count, const cake_kv* kv,
                         double fixed_gbps) {
@@ -240,7 +258,7 @@ static int enqueue_load(cake_ctx* c, const cake_kv_store* st, int tok_begin, int
             const char* src = img + uint64_t(l) * layer_bytes;
             for (uint64_t off = 0; off < layer_bytes; off += piece_max) {
                 uint64_t n = std::min(piece_max, layer_bytes - off);
-                double rate = fixed_gbps < 0 ? c->gbps.load(std::memory_order_relaxed) : fixed_gbps;
+                double rate = fixed_gbps < 0 ? live_rate(c) : fixed_gbps;
                 if (rate > 0) {
                     release += double(n) / rate;  // GB/s = bytes per ns
                     wait_until_ns(start + uint64_t(release));
@@ -528,6 +546,36 @@ int32_t cake_first_token(cake_ctx* c, const int32_t* token_ids, int32_t n_tokens
     return CAKE_OK;
 }
 
+int32_t cake_set_traces(cake_ctx* c, const cake_traces* t) {
+    if (!c) return CAKE_E_INVAL;
+    c->tr_other.clear(); c->tr_ids.clear(); c->tr_gbps.clear(); c->tr_interval_ns = 0;
+    if (!t) return CAKE_OK;
+    if (t->n_other_tokens < 0 || t->n_gbps < 0) return fail(c, CAKE_E_INVAL, "traces: negative length");
+    if (t->n_other_tokens > 0) {
+        if (!t->other_tokens || !t->scratch_kv || !t->scratch_token_ids || t->n_scratch_tokens <= 0)
+            return fail(c, CAKE_E_INVAL, "traces: other_tokens needs scratch pages and token ids");
+        int rc = check_kv(c, t->scratch_kv, t->n_scratch_tokens);
+        if (rc != CAKE_OK) return rc;
+        for (int i = 0; i < t->n_other_tokens; ++i)
+            if (t->other_tokens[i] < 0 || t->other_tokens[i] > t->n_scratch_tokens || t->other_tokens[i] > c->max_chunk)
+                return fail(c, CAKE_E_INVAL, "traces: other_tokens[%d] outside [0, min(scratch, max_chunk)]", i);
+        for (int i = 0; i < t->n_scratch_tokens; ++i)
+            if (t->scratch_token_ids[i] < 0 || t->scratch_token_ids[i] >= c->m.vocab)
+                return fail(c, CAKE_E_INVAL, "traces: scratch token id outside the vocabulary");
+        c->tr_other.assign(t->other_tokens, t->other_tokens + t->n_other_tokens);
+        c->tr_ids.assign(t->scratch_token_ids, t->scratch_token_ids + t->n_scratch_tokens);
+        c->tr_kv = *t->scratch_kv;
+    }
+    if (t->n_gbps > 0) {
+        if (!t->gbps || t->gbps_interval_ns == 0) return fail(c, CAKE_E_INVAL, "traces: gbps needs samples and an interval");
+        for (int i = 0; i < t->n_gbps; ++i)
+            if (!(t->gbps[i] >= 0)) return fail(c, CAKE_E_INVAL, "traces: gbps[%d] negative", i);
+        c->tr_gbps.assign(t->gbps, t->gbps + t->n_gbps);
+        c->tr_interval_ns = t->gbps_interval_ns;
+    }
+    return CAKE_OK;
+}
+
 // Adaptive mode (Sec. 4 Part 3): the engine loop that deals a token budget out per step.
 int32_t cake_adaptive_serve(cake_ctx* c, cake_request* reqs, int32_t n_reqs, int32_t token_budget, int32_t fetch_chunk,
                             double gbps, cake_result* res, cake_step_log* steps, int32_t steps_cap,
@@ -598,8 +646,9 @@ int32_t cake_adaptive_serve(cake_ctx* c, cake_request* reqs, int32_t n_reqs, int
     uint64_t prefix_compute_end = 0, starved_ns = 0;
     ex.t0 = mono_ns();
 
-    struct Part { int req, first, count; };
+    struct Part { int req, first, count; };   // req == -1: the other users' share of the step (trace)
     std::vector<Part> parts;
+    if (!c->tr_gbps.empty()) c->tr_t0.store(mono_ns());
     while (n_done < n_reqs && hard == CAKE_OK) {
         uint64_t now = ex.now();
         if (P >= 0 && !loader_started && reqs[P].arrival_ns <= now) {
@@ -610,7 +659,12 @@ int32_t cake_adaptive_serve(cake_ctx* c, cake_request* reqs, int32_t n_reqs, int
         // complete; (2) prefill of requests without a stored prefix, oldest first; (3) the rest to
         // the prefix-cached request, as far as the plan gives it to the compute side
         parts.clear();
-        int left = token_budget, np_tokens = 0, first_np = -1;
+        int left = token_budget, np_tokens = 0, first_np = -1, bg_tokens = 0;
+        if (!c->tr_other.empty()) {
+            bg_tokens = std::min(left, c->tr_other[size_t(n_steps) % c->tr_other.size()]);
+            if (bg_tokens > 0) parts.push_back({-1, 0, bg_tokens});
+            left -= bg_tokens;
+        }
         for (int k = 0; k < n_reqs && left > 0; ++k) {
             int i = order[k];
             if (i == P || done[i] || reqs[i].arrival_ns > now) continue;
@@ -629,7 +683,13 @@ int32_t cake_adaptive_serve(cake_ctx* c, cake_request* reqs, int32_t n_reqs, int
         }
         if (got > 0) parts.push_back({P, first, got});
 
-        if (parts.empty()) {
+        const bool only_background = parts.size() == 1 && parts[0].req == -1;
+        bool prefix_finished_by_loader = false;
+        if (parts.empty() || only_background) {
+            std::unique_lock<std::mutex> lk(ex.mu);
+            prefix_finished_by_loader = prefix_live && ex.core.range_empty() && !ex.core.w[W_LOAD].busy;
+        }
+        if (parts.empty() || (only_background && prefix_finished_by_loader)) {
             // idle: the prefix request may be finished by the loader, or nothing has arrived yet
             std::unique_lock<std::mutex> lk(ex.mu);
             if (prefix_live && ex.core.range_empty() && !ex.core.w[W_LOAD].busy) {
@@ -651,16 +711,17 @@ int32_t cake_adaptive_serve(cake_ctx* c, cake_request* reqs, int32_t n_reqs, int
         // ---- run the step
         const uint64_t t_start = ex.now();
         for (const Part& p : parts) {
-            const cake_request& r = reqs[p.req];
-            if (hipMemcpyAsync(c->d_ids + p.first, r.token_ids + p.first, size_t(p.count) * 4, hipMemcpyHostToDevice, c->cs) != hipSuccess) { hard = CAKE_E_HIP; break; }
-            int rc = enqueue_prefill(c, p.first, p.count, r.kv);
+            const int32_t* ids = p.req < 0 ? c->tr_ids.data() : reqs[p.req].token_ids + p.first;
+            const cake_kv* pkv = p.req < 0 ? &c->tr_kv : reqs[p.req].kv;
+            if (hipMemcpyAsync(c->d_ids + p.first, ids, size_t(p.count) * 4, hipMemcpyHostToDevice, c->cs) != hipSuccess) { hard = CAKE_E_HIP; break; }
+            int rc = enqueue_prefill(c, p.first, p.count, pkv);
             if (rc != CAKE_OK) { hard = rc; break; }
         }
         if (hard == CAKE_OK && hipStreamSynchronize(c->cs) != hipSuccess) hard = fail(c, CAKE_E_HIP, "compute stream failed in an adaptive step");
         const uint64_t t_end = ex.now();
         if (hard != CAKE_OK) break;
         for (const Part& p : parts) {
-            if (p.req == P) continue;
+            if (p.req == P || p.req < 0) continue;
             next_tok[p.req] += p.count;
             reqs[p.req].tokens_computed += p.count;
             if (next_tok[p.req] == reqs[p.req].n_tokens) {
@@ -696,7 +757,7 @@ int32_t cake_adaptive_serve(cake_ctx* c, cake_request* reqs, int32_t n_reqs, int
             if (n_steps < steps_cap) {
                 cake_step_log& sl = steps[n_steps];
                 sl.start_ns = now; sl.end_ns = t_end; sl.decode_tokens = 0; sl.nonprefix_tokens = np_tokens;
-                sl.prefix_tokens = got; sl.prefix_tok_begin = got > 0 ? first : -1; sl.first_nonprefix_req = first_np; sl.pad_ = 0;
+                sl.prefix_tokens = got; sl.prefix_tok_begin = got > 0 ? first : -1; sl.first_nonprefix_req = first_np; sl.other_tokens = bg_tokens;
             } else steps_overflow = true;
         }
         ++n_steps;
@@ -727,6 +788,8 @@ int32_t cake_adaptive_serve(cake_ctx* c, cake_request* reqs, int32_t n_reqs, int
         }
         if (res->chunks && i < res->chunks_cap) res->chunks[i] = cl;
     }
+    c->tr_t0.store(0);   // traces apply to one run
+    c->tr_other.clear(); c->tr_ids.clear(); c->tr_gbps.clear(); c->tr_interval_ns = 0;
     if (n_steps_out) *n_steps_out = std::min(n_steps, steps ? steps_cap : n_steps);
     if (hard != CAKE_OK) {
         if (c->err.empty()) fail(c, hard, "adaptive run ended with status %d", hard);

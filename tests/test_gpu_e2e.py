@@ -473,3 +473,95 @@ def test_fetch_unit_smaller_than_compute_step(shape, T, step, unit):
     assert max(d["claimed_tokens"] for d in comp) == step
     assert sum(d["claimed_tokens"] for d in comp) == m * unit
     assert all(s["prefix_tokens"] <= step for s in steps)
+
+
+# --------------------------------------------------------------------------- utilisation levels and fluctuating resources
+def _trace_setup(T=8192, step=1024, unit=256):
+    import paper_2410_03065_amd as cake
+    shape, pt = BF_NARROW_GQA4, unit
+    w = si.make_weights(shape, seed=60)
+    toks = si.make_tokens(T, shape.vocab, seed=61)
+    eng = cake.Engine(shape, w, max_tokens=T, max_chunk=step, page_tokens=pt)
+    ref = otf.prefill_chunked(w, shape, toks, step, kv_dtype="bf16")
+    images = ostore.pack_store(ref, pt, "bf16")
+    eng.set_store(images)
+    eng.bidirectional_prefill(toks, step, 4.0, mode="compute_only")
+    r_c = eng.bidirectional_prefill(toks, step, 4.0, mode="compute_only")
+    rate = T * otf.kv_bytes_per_token(shape.n_layers, shape.n_kv, shape.head_dim, 2) / r_c.ttft_ns
+    return shape, toks, eng, images, ostore.decode_words(images, "bf16"), rate
+
+
+def _check_trace_run(eng, shape, toks, images, want, res, per_req, steps, step, unit, other_of_step, step_tokens):
+    T = len(toks)
+    m = res.meet_point
+    assert per_req[0]["tokens_computed"] == min(m * unit, T) and per_req[0]["tokens_computed"] + per_req[0]["tokens_loaded"] == T
+    assert _errs(eng.pool_images(T), want).max() < TOL["bf16"]
+    np.testing.assert_array_equal(eng.pool_raw(T)[m:].view(np.uint16), images[m:])
+    _check_decisions(res, shape, T, unit, unit, step_tokens=step_tokens)
+    for k, s in enumerate(steps):                       # the budget of every step, dealt by the oracle's rule
+        other = other_of_step(k)
+        dec, grants, pref = mp.fill_token_budget(step, 0, [other] if other else [], 10 ** 9)
+        assert s["other_tokens"] == sum(grants) == other and s["decode_tokens"] == dec == 0
+        assert s["nonprefix_tokens"] == 0 and 0 <= s["prefix_tokens"] <= pref
+
+
+def test_gpu_utilisation_levels():
+    """Sec. 5.1 "GPU Resource Utilization": other users hold a fixed part of every step's token
+    budget (and really run), the prefix request gets 100 / 50 / 12.5 % of it.  The less compute it
+    gets, the more of the prompt the planner leaves to the loader."""
+    step, unit = 1024, 256
+    shape, toks, eng, images, want, rate = _trace_setup(step=step, unit=unit)
+    reqs = [dict(tokens=toks, arrival_ns=0, prefix=True)]
+    computed = {}
+    for share in (1.0, 0.5, 0.125):
+        other = int(step * (1 - share))
+        eng.clear_pool()
+        if other:
+            eng.set_traces(other_tokens=[other])
+        res, per_req, steps = eng.adaptive_serve(reqs, step, unit, rate)
+        _check_trace_run(eng, shape, toks, images, want, res, per_req, steps, step, unit, lambda k: other, step - other)
+        computed[share] = per_req[0]["tokens_computed"]
+    # tier as fast as the whole GPU: about 1/2, 1/3 and 1/9 of the prompt computed
+    assert computed[1.0] > computed[0.5] > computed[0.125] > 0
+    # the trace applied to one run only
+    eng.clear_pool()
+    _, _, steps = eng.adaptive_serve(reqs, step, unit, rate)
+    assert all(s["other_tokens"] == 0 for s in steps)
+
+
+def test_fluctuating_budget_and_bandwidth():
+    """Sec. 5.6: a random per-step compute budget and a random bandwidth trace at once; the result
+    is still the oracle's KV, every plan the optimum of what was known at that instant, every
+    claim within the step's share."""
+    step, unit = 1024, 256
+    shape, toks, eng, images, want, rate = _trace_setup(step=step, unit=unit)
+    rng = np.random.default_rng(7)
+    other = (rng.integers(0, step // 64 + 1, 37) * 64).astype(np.int32)        # 0 .. 1024 tokens, cycled
+    gbps = rng.uniform(0.0, 2.0, 53) * rate                                    # 0 .. twice the GPU's own pace
+    reqs = [dict(tokens=toks, arrival_ns=0, prefix=True)]
+    eng.clear_pool()
+    eng.set_traces(other_tokens=other, gbps_trace=gbps, gbps_interval_ns=1_000_000)
+    res, per_req, steps = eng.adaptive_serve(reqs, step, unit, rate)
+    _check_trace_run(eng, shape, toks, images, want, res, per_req, steps, step, unit, lambda k: int(other[k % len(other)]), None)
+    assert 0 < res.meet_point < len(toks) // unit
+    # the loader's measured rates moved with the trace: not all loaded units took the same time
+    durs = [c["end_ns"] - c["start_ns"] for c in res.chunks if c["source"] == 1]
+    assert len(durs) >= 2 and max(durs) > 1.2 * min(durs)
+
+
+def test_traces_argument_errors():
+    import paper_2410_03065_amd as cake
+    import ctypes as C
+    shape = si.TINY.with_(vocab=100)
+    eng = cake.Engine(shape, si.make_weights(shape, seed=1), max_tokens=256, max_chunk=128, page_tokens=64)
+    other = np.array([64], dtype=np.int32)
+    t = cake.Traces()
+    t.other_tokens, t.n_other_tokens = other.ctypes.data, 1            # no scratch pages
+    assert eng.lib.cake_set_traces(eng.ctx, C.byref(t)) == cake.E_INVAL
+    with pytest.raises(cake.CakeError):
+        eng.set_traces(other_tokens=[129])                             # more than the largest compute step
+    with pytest.raises(cake.CakeError):
+        eng.set_traces(gbps_trace=[1.0, -2.0], gbps_interval_ns=1000)
+    with pytest.raises(cake.CakeError):
+        eng.set_traces(gbps_trace=[1.0], gbps_interval_ns=0)
+    assert eng.lib.cake_set_traces(eng.ctx, None) == cake.OK
