@@ -1,0 +1,96 @@
+#!/usr/bin/env python3
+"""Utilisation x bandwidth grid and fluctuation trace of the paper's evaluation, on synthetic input.
+
+    python -m paper_2410_03065_amd.sweeps --grid          # Sec. 5.2 / Table 3 layout
+    python -m paper_2410_03065_amd.sweeps --fluctuation   # Sec. 5.6 / Fig. 5 layout
+
+Grid: one prefix-cached prompt (default: Llama3-8B shape, 32768 random tokens) is produced by the
+adaptive engine while other users hold 0 / 12.5 / 50 / 87.5 % of every step's token budget, at the
+tier bandwidths the paper lists (7, 25, 32, 56, 100 Gbps).  Each cell prints TTFT and the speed-up
+over load-only (KV bytes / bandwidth, measured) and over compute-only at the same utilisation
+(measured with the tier made useless).  Prints a Markdown table; inputs are seeded and synthetic.
+"""
+from __future__ import annotations
+
+import argparse
+import os
+import sys
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--grid", action="store_true")
+    ap.add_argument("--fluctuation", action="store_true")
+    ap.add_argument("--shape", default="llama3-8b-shape")
+    ap.add_argument("--tokens", type=int, default=32768)
+    ap.add_argument("--budget", type=int, default=1024, help="token budget of an engine step")
+    ap.add_argument("--fetch-unit", type=int, default=256)
+    ap.add_argument("--gbit", type=float, nargs="*", default=[7, 25, 32, 56, 100], help="tier bandwidths in Gbit/s")
+    ap.add_argument("--shares", type=float, nargs="*", default=[0.125, 0.5, 0.875, 1.0])
+    args = ap.parse_args()
+
+    import numpy as np
+    import synth_inputs as si
+    import paper_2410_03065_amd as cake
+
+    shape = si.SHAPES[args.shape]
+    T, B, U = args.tokens, args.budget, args.fetch_unit
+    eng = cake.Engine(shape, None, max_tokens=T, max_chunk=B, page_tokens=U, seed=0)
+    toks = si.make_tokens(T, shape.vocab, seed=1)
+    eng.bidirectional_prefill(toks, B, 4.0, mode="compute_only", log=False)     # stored KV = our own compute-only pass
+    eng.store_from_pool(T)
+    reqs = [dict(tokens=toks, arrival_ns=0, prefix=True)]
+
+    def run(gbps, other=None, gbps_trace=None, interval_ns=0):
+        if other is not None or gbps_trace is not None:
+            eng.set_traces(other_tokens=other, gbps_trace=gbps_trace, gbps_interval_ns=interval_ns)
+        return eng.adaptive_serve(reqs, B, U, gbps)
+
+    run(4.0)   # warm-up
+    print("workload: %s, %d random tokens, step budget %d, fetch unit %d, one MI355X" % (shape.name, T, B, U))
+    if args.grid:
+        load_only = {}
+        for gb in args.gbit:
+            r = eng.bidirectional_prefill(toks, B, gb / 8.0, mode="load_only", log=False)
+            load_only[gb] = r.ttft_ns / 1e9
+        print("\n| utilisation | compute-only s | " + " | ".join("%g Gbps: TTFT s (x load-only \\\\ x compute-only)" % g for g in args.gbit) + " |")
+        print("|---|---|" + "---|" * len(args.gbit))
+        for share in args.shares:
+            other = int(round(B * (1 - share)))
+            tr = [other] if other else None
+            res_c, _, _ = run(1e-4, tr)                                      # tier too slow to be given anything
+            t_c = res_c.ttft_ns / 1e9
+            assert res_c.meet_point == res_c.n_chunks
+            cells = []
+            for gb in args.gbit:
+                res, per_req, _ = run(gb / 8.0, tr)
+                t = res.ttft_ns / 1e9
+                cells.append("%.3f (%.2f \\\\ %.2f) m=%d" % (t, load_only[gb] / t, t_c / t, per_req[0]["tokens_computed"]))
+            print("| %.1f %% | %.3f | %s |" % (share * 100, t_c, " | ".join(cells)))
+        print("\nload-only s: " + ", ".join("%g Gbps %.3f" % (g, load_only[g]) for g in args.gbit))
+    if args.fluctuation:
+        rng = np.random.default_rng(3)
+        other = (B - rng.integers(0, B // 2 // 64 + 1, 64) * 64).astype(np.int32)      # the request gets 0 .. B/2 tokens a step
+        gbps = rng.uniform(0.0, 25.0 / 8.0, 64)                                        # 0 .. 25 Gbit/s
+        res, per_req, steps = run(25.0 / 16.0, other, gbps, 20_000_000)
+        t = res.ttft_ns / 1e9
+        print("\nfluctuation: budget for the request uniform in [0, %d] tokens per step, bandwidth uniform in [0, 25] Gbps "
+              "re-drawn every 20 ms: TTFT %.3f s, %d tokens computed, %d loaded, %d engine steps, %d planner looks"
+              % (B // 2, t, per_req[0]["tokens_computed"], per_req[0]["tokens_loaded"], len(steps), len(res.decisions)))
+        print("| t ms | planned meet point (fetch unit) | load estimate GB/s | compute estimate TFLOP/s |")
+        print("|---|---|---|---|")
+        last = -1
+        for d in res.decisions:
+            ms = int(d["now_ns"] / 1e6)
+            if ms // 100 != last:
+                last = ms // 100
+                print("| %d | %d | %.2f | %.0f |" % (ms, d["m_star"], d["est_load_bytes"] / max(1, d["est_load_ns"]),
+                                                    d["est_compute_flops"] / max(1, d["est_compute_ns"]) / 1e3))
+
+
+if __name__ == "__main__":
+    main()
