@@ -76,3 +76,78 @@ def unpack_store(images: np.ndarray, n_tokens: int, n_kv: int, hd: int,
             cache.v[l, t0:t1] = np.transpose(vblk[:, :, :n], (2, 0, 1))
     cache.filled = n_tokens
     return cache
+
+
+# --------------------------------------------------------------------------- #
+# 8-bit stored KV (Sec. 5.5: KV compression combined with the method, "the most common
+# 8-bit quantization"; the paper names no scheme)
+# --------------------------------------------------------------------------- #
+# Reading taken here: symmetric absmax quantisation of every (token, KV head) row of head_dim
+# values, for K (as cached, rotated) and V alike:
+#     scale = max|x| / 127            code = round_half_even(x / scale), clipped to [-127, 127]
+#     x'    = storage_round(code * scale)
+# with scale and both products / quotients in float32 (the GPU's precision; these steps decide
+# integers and stored bit patterns, so the oracle takes them in that precision too).  A row of
+# zeros has scale 0 and codes 0.  An image of one page, per layer and per K|V:
+#     int8   codes [kv_head][token_in_page][hd]      (V is NOT transposed in this format)
+#     float32 scales [kv_head][token_in_page]
+# i.e. n_kv * page_tokens * (hd + 4) bytes against 2 * n_kv * page_tokens * hd for bf16.
+
+def quantize_rows_int8(x: np.ndarray):
+    """x [..., hd] (values exactly representable in float32) -> (int8 codes, float32 scales [...])."""
+    x32 = np.ascontiguousarray(x, dtype=np.float32)
+    scale = (np.abs(x32).max(axis=-1) / np.float32(127.0)).astype(np.float32)
+    safe = np.where(scale > 0, scale, np.float32(1.0)).astype(np.float32)
+    q = np.rint((x32 / safe[..., None]).astype(np.float32))
+    q = np.clip(q, -127, 127).astype(np.int8)
+    q[scale == 0] = 0
+    return q, scale
+
+
+def dequantize_rows_int8(codes: np.ndarray, scale: np.ndarray, dtype: str) -> np.ndarray:
+    """code * scale in float32, then the storage rounding of ``dtype``; returned as float64."""
+    from .transformer import round_storage
+    x32 = (codes.astype(np.float32) * scale[..., None].astype(np.float32)).astype(np.float32)
+    return round_storage(x32.astype(np.float64), dtype)
+
+
+def int8_image_bytes(n_layers: int, n_kv: int, hd: int, page_tokens: int) -> int:
+    return n_layers * 2 * n_kv * page_tokens * (hd + 4)
+
+
+def pack_store_int8(cache: KVCache, page_tokens: int) -> np.ndarray:
+    """[n_logical_pages, L, 2, n_kv * page_tokens * (hd + 4)] bytes (uint8)."""
+    L, T, n_kv, hd = cache.k.shape
+    n_pages = (T + page_tokens - 1) // page_tokens
+    nc = n_kv * page_tokens * hd
+    out = np.zeros((n_pages, L, 2, n_kv * page_tokens * (hd + 4)), dtype=np.uint8)
+    for p in range(n_pages):
+        t0, t1 = p * page_tokens, min((p + 1) * page_tokens, T)
+        n = t1 - t0
+        for l in range(L):
+            for which, src in ((0, cache.k), (1, cache.v)):
+                blk = np.zeros((n_kv, page_tokens, hd), dtype=np.float64)
+                blk[:, :n, :] = np.transpose(src[l, t0:t1], (1, 0, 2))        # [kv, tok, hd]
+                q, sc = quantize_rows_int8(blk)
+                out[p, l, which, :nc] = q.reshape(-1).view(np.uint8)
+                out[p, l, which, nc:] = sc.reshape(-1).view(np.uint8)
+    return out
+
+
+def unpack_store_int8(images: np.ndarray, n_tokens: int, n_kv: int, hd: int,
+                      page_tokens: int, dtype: str) -> KVCache:
+    """The cache a loader must produce from int8 images: dequantised and storage-rounded."""
+    n_pages, L = images.shape[0], images.shape[1]
+    nc = n_kv * page_tokens * hd
+    cache = KVCache(L, n_tokens, n_kv, hd)
+    for p in range(n_pages):
+        t0, t1 = p * page_tokens, min((p + 1) * page_tokens, n_tokens)
+        n = t1 - t0
+        for l in range(L):
+            for which, dst in ((0, cache.k), (1, cache.v)):
+                q = images[p, l, which, :nc].view(np.int8).reshape(n_kv, page_tokens, hd)
+                sc = np.ascontiguousarray(images[p, l, which, nc:]).view(np.float32).reshape(n_kv, page_tokens)
+                x = dequantize_rows_int8(q, sc, dtype)
+                dst[l, t0:t1] = np.transpose(x[:, :n, :], (1, 0, 2))
+    cache.filled = n_tokens
+    return cache

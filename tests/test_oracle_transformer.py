@@ -371,3 +371,46 @@ def test_first_token_reads_the_cache_as_it_is():
 def test_greedy_token_lowest_index_on_ties():
     assert otf.greedy_token(np.array([1.0, 3.0, 3.0, 2.0])) == 1
     assert otf.greedy_token(np.array([-np.inf, -5.0])) == 1
+
+
+# --------------------------------------------------------------------------- 8-bit stored KV
+def test_int8_rows_hand_worked():
+    from oracle import store as ostore
+    x = np.array([[127.0, -63.5, 1.0, 0.49, -0.51, 0.0, 2.5, -127.0],      # scale 1: ties to even, clipping at the ends
+                  [0.0] * 8,                                              # zero row: scale 0, codes 0
+                  [0.5, -0.25, 0.125, 0.0, 0.0, 0.0, 0.0, 0.0]])          # scale 0.5/127
+    q, sc = ostore.quantize_rows_int8(x)
+    assert sc[0] == 1.0 and q[0].tolist() == [127, -64, 1, 0, -1, 0, 2, -127]     # -63.5 -> -64 (even), 2.5 -> 2 (even)
+    assert sc[1] == 0.0 and not q[1].any()
+    assert sc[2] == np.float32(0.5) / np.float32(127) and q[2].tolist()[:3] == [127, -64, 32]   # 63.5 -> 64, 31.75 -> 32
+    d = ostore.dequantize_rows_int8(q, sc, "f32")
+    assert d[0].tolist() == [127.0, -64.0, 1.0, 0.0, -1.0, 0.0, 2.0, -127.0] and not d[1].any()
+    assert abs(d[2][0] - 0.5) < 1e-7
+
+
+def test_int8_store_properties():
+    from oracle import store as ostore
+    rng = np.random.default_rng(3)
+    L, T, n_kv, hd, pt = 2, 150, 2, 64, 64
+    cache = otf.KVCache(L, T, n_kv, hd)
+    cache.k[:] = otf.round_storage(rng.standard_normal(cache.k.shape) * 3, "bf16")
+    cache.v[:] = otf.round_storage(rng.standard_normal(cache.v.shape), "bf16")
+    img = ostore.pack_store_int8(cache, pt)
+    assert img.shape == (3, L, 2, n_kv * pt * (hd + 4)) and img[0].size == ostore.int8_image_bytes(L, n_kv, hd, pt)
+    assert ostore.int8_image_bytes(32, 8, 128, 256) * 2 * 128 == 32 * 2 * 8 * 256 * 128 * 2 * 132    # (hd+4)/(2 hd) of the bf16 image
+    back = ostore.unpack_store_int8(img, T, n_kv, hd, pt, "bf16")
+    for a, b in ((cache.k, back.k), (cache.v, back.v)):
+        amax = np.abs(a).max(axis=-1, keepdims=True)
+        # half a quantisation step plus the bf16 rounding of the result
+        assert np.all(np.abs(a - b) <= amax / 254 * (1 + 1e-6) + np.abs(b) * 2.0 ** -8)
+        hit = np.abs(a) == amax                                           # the row's largest element is code +-127: exact up to rounding
+        assert np.all(np.abs(a[hit] - b[hit]) <= np.abs(a[hit]) * 2.0 ** -7)
+    codes = img[..., :n_kv * pt * hd].view(np.int8)
+    assert codes.min() >= -127 and codes.max() <= 127 and np.abs(codes).max() == 127
+    # slots past the prompt are zeros with scale 0
+    tail = img[2, :, :, :n_kv * pt * hd].view(np.int8).reshape(L, 2, n_kv, pt, hd)[:, :, :, T - 2 * pt:, :]
+    assert not tail.any()
+    # quantising what was dequantised (before storage rounding) reproduces the codes
+    q, sc = ostore.quantize_rows_int8(cache.k[0])
+    q2, _ = ostore.quantize_rows_int8(q.astype(np.float32) * sc[..., None])
+    np.testing.assert_array_equal(q, q2)
