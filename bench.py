@@ -160,6 +160,16 @@ def main():
     r_c = eng.bidirectional_prefill(toks, C, args.gbps, mode="compute_only")
     r_l = eng.bidirectional_prefill(toks, C, args.gbps, mode="load_only")
 
+    # the same tier with an 8-bit store written from the pool (which the compute-only pass just filled)
+    eng.bidirectional_prefill(toks, C, args.gbps, mode="compute_only", log=False)
+    eng.write_store(T, cake.STORE_INT8)
+    eng.bidirectional_prefill(toks, C, args.gbps, mode="bidir", log=False)
+    r8 = [eng.bidirectional_prefill(toks, C, args.gbps, mode="bidir") for _ in range(2)]
+    r8_l = eng.bidirectional_prefill(toks, C, args.gbps, mode="load_only")
+    int8_store = {"ttft_s": round(float(np.mean([r.ttft_ns for r in r8])) / 1e9, 5), "meet_point": [r.meet_point for r in r8],
+                  "load_only_s": round(r8_l.ttft_ns / 1e9, 5), "store_bytes": int(r8_l.load_bytes),
+                  "achieved_gbps_load_only": round(r8_l.achieved_gbps, 4)}
+
     ttft = float(np.mean([r.ttft_ns for r in runs])) / 1e9
     comp_flops = sum(r.compute_flops for r in runs)
     comp_dev_ns = sum(r.compute_device_ns for r in runs)
@@ -213,6 +223,7 @@ def main():
         "kernels": kernels,
         "first_token": dict(first_token, ttft_to_first_token_s=round(ttft + ft_wall, 5)),
         "fine_fetch_unit": fine,
+        "int8_store": int8_store,
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:

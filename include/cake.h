@@ -113,11 +113,21 @@ typedef struct {
     int32_t n_logical_pages;
 } cake_kv;
 
+/* How a store holds a page.  CAKE_STORE_RAW: the page's bytes as they are in HBM (layout above).
+ * CAKE_STORE_INT8 (Sec. 5.5: compressed KV combined with the method): per layer and per K|V,
+ *   int8 codes [kv_head][token][head_dim] then float32 scales [kv_head][token];
+ *   value = code * scale, one scale per token and KV head (absmax / 127), V not transposed.
+ *   n_layers*2*n_kv*page_tokens*(head_dim+4) bytes per page.  Loaded pages are dequantised on
+ *   arrival (float32 product, rounded once to the KV element type). */
+typedef enum { CAKE_STORE_RAW = 0, CAKE_STORE_INT8 = 1 } cake_store_format;
+
 typedef struct {
     const void* base;           /* pinned host */
-    uint64_t page_stride_bytes; /* >= n_layers*2*n_kv*page_tokens*head_dim*elem */
+    uint64_t page_stride_bytes; /* >= the page image size of `format` */
     int32_t page_tokens;        /* must equal cake_kv.page_tokens */
     int32_t n_pages;            /* logical pages held */
+    int32_t format;             /* cake_store_format */
+    int32_t pad_;
 } cake_kv_store;
 
 /* One record per chunk, indexed by chunk number. */
@@ -321,6 +331,14 @@ int32_t cake_adaptive_serve(cake_ctx* ctx, cake_request* requests, int32_t n_req
 int32_t cake_first_token(cake_ctx* ctx, const int32_t* token_ids, int32_t n_tokens,
                          const cake_kv* kv, int32_t* token_out, float* logits_out,
                          uint64_t* device_ns_out);
+
+/* Bytes of one page image in a store of `format`. */
+uint64_t cake_store_image_bytes(const cake_model_desc* model, int32_t page_tokens, int32_t format);
+/* Writes the pages that hold tokens [0, n_tokens) of `kv` into `dst` (pinned host, writable
+ * despite the const base) in dst->format: CAKE_STORE_RAW copies, CAKE_STORE_INT8 quantises on the
+ * GPU (scale = absmax / 127 per token and KV head, codes rounded half to even).  Blocking.
+ * Errors: CAKE_E_INVAL, CAKE_E_NOMEM (staging), CAKE_E_HIP. */
+int32_t cake_write_store(cake_ctx* ctx, const cake_kv* kv, int32_t n_tokens, const cake_kv_store* dst);
 
 /* ---- small helpers ---------------------------------------------------- */
 

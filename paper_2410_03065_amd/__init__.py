@@ -31,8 +31,9 @@ EXPORTS = [
     "cake_range_flops", "cake_page_image_bytes", "cake_simulate_race", "cake_op_rmsnorm",
     "cake_op_gemm", "cake_op_gemm_residual", "cake_op_gemm_swiglu", "cake_op_rope_kv_write",
     "cake_op_attention", "cake_profile_enable", "cake_profile_read", "cake_adaptive_serve", "cake_first_token",
-    "cake_op_decode_attention", "cake_set_traces",
+    "cake_op_decode_attention", "cake_set_traces", "cake_store_image_bytes", "cake_write_store",
 ]
+STORE_RAW, STORE_INT8 = 0, 1
 KERNEL_CLASSES = ["embed", "rmsnorm", "gemm_qkv", "rope_kv", "attention", "gemm_o", "gemm_gateup", "gemm_down",
                   "gemv", "decode_attention"]
 
@@ -64,7 +65,7 @@ class Kv(C.Structure):
 
 class KvStore(C.Structure):
     _fields_ = [("base", C.c_void_p), ("page_stride_bytes", C.c_uint64), ("page_tokens", C.c_int32),
-                ("n_pages", C.c_int32)]
+                ("n_pages", C.c_int32), ("format", C.c_int32), ("pad_", C.c_int32)]
 
 
 class ChunkLog(C.Structure):
@@ -137,6 +138,8 @@ def load_library():
         "cake_bidirectional_prefill": (i32, [vp, vp, i32, P(KvStore), i32, dbl, i32, i32, P(Kv), P(Result)]),
         "cake_first_token": (i32, [vp, vp, i32, P(Kv), P(i32), vp, P(u64)]),
         "cake_set_traces": (i32, [vp, P(Traces)]),
+        "cake_store_image_bytes": (u64, [P(ModelDesc), i32, i32]),
+        "cake_write_store": (i32, [vp, P(Kv), i32, P(KvStore)]),
         "cake_op_decode_attention": (i32, [vp, vp, vp, i32, i32, P(Kv)]),
         "cake_set_bandwidth": (i32, [vp, dbl]),
         "cake_schedule_bandwidth_step": (i32, [vp, i32, dbl]),
@@ -347,10 +350,28 @@ class Engine:
         t.numpy()[:] = flat.view(np.int32 if flat.dtype == np.uint32 else np.int16)
         self._set_store_tensor(t)
 
-    def _set_store_tensor(self, t):
+    def _set_store_tensor(self, t, fmt=STORE_RAW):
         self.store_tensor = t
         stride = t.shape[1] * t.element_size()
-        self.store = KvStore(t.data_ptr(), stride, self.page_tokens, t.shape[0])
+        self.store = KvStore(t.data_ptr(), stride, self.page_tokens, t.shape[0], fmt, 0)
+
+    def set_store_int8(self, images: np.ndarray):
+        """images: [n_pages, L, 2, bytes] uint8 in the int8 store format (codes then scales per layer and K|V)."""
+        torch = self.torch
+        flat = np.ascontiguousarray(images).reshape(images.shape[0], -1)
+        t = torch.empty(flat.shape, dtype=torch.uint8, pin_memory=True)
+        t.numpy()[:] = flat
+        self._set_store_tensor(t, STORE_INT8)
+
+    def write_store(self, n_tokens, fmt=STORE_INT8):
+        """The pool's KV of [0, n_tokens) written into a new pinned store of the given format (cake_write_store)."""
+        torch = self.torch
+        n_pages = (n_tokens + self.page_tokens - 1) // self.page_tokens
+        image = int(self.lib.cake_store_image_bytes(C.byref(model_desc(self.shape)), self.page_tokens, fmt))
+        t = torch.empty((n_pages, image), dtype=torch.uint8, pin_memory=True)
+        self._set_store_tensor(t, fmt)
+        self._check(self.lib.cake_write_store(self.ctx, C.byref(self.kv), n_tokens, C.byref(self.store)), "cake_write_store")
+        return t
 
     def store_from_pool(self, n_tokens):
         """Copies the pool's current KV of [0, n_tokens) into a new pinned store (page images)."""

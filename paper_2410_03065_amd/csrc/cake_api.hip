@@ -41,6 +41,8 @@ struct cake_ctx {
     float *t_h = nullptr, *t_q = nullptr, *t_qr = nullptr, *t_ao = nullptr, *t_act = nullptr, *t_logits = nullptr,
           *t_part = nullptr;
     int32_t* t_tok = nullptr;
+    void* q_stage = nullptr;   // device staging for int8 page images (allocated at the first use)
+    size_t q_stage_bytes = 0;
     hipEvent_t ev_a = nullptr, ev_b = nullptr;
     std::atomic<double> gbps{0.0};
     int step_after = -1;
@@ -231,6 +233,17 @@ static double live_rate(cake_ctx* c) {
     return c->gbps.load(std::memory_order_relaxed);
 }
 
+static int ensure_stage(cake_ctx* c, uint64_t bytes) {
+    if (c->q_stage_bytes >= bytes) return CAKE_OK;
+    // the copy stream may still read the old buffer
+    if (hipStreamSynchronize(c->ls) != hipSuccess) return fail(c, CAKE_E_HIP, "stream sync before staging growth");
+    (void)hipFree(c->q_stage);
+    c->q_stage = nullptr; c->q_stage_bytes = 0;
+    if (hipMalloc(&c->q_stage, bytes) != hipSuccess) { (void)hipGetLastError(); return fail(c, CAKE_E_NOMEM, "staging buffer of %llu bytes", (unsigned long long)bytes); }
+    c->q_stage_bytes = bytes;
+    return CAKE_OK;
+}
+
 // fixed_gbps > 0: that rate; == 0: unthrottled; < 0: the context's live rate.
 static int enqueue_load(cake_ctx* c, const cake_kv_store* st, int tok_begin, int tok_count, const cake_kv* kv,
                         double fixed_gbps) {
@@ -241,31 +254,49 @@ static int enqueue_load(cake_ctx* c, const cake_kv_store* st, int tok_begin, int
     const int pt = kv->page_tokens;
     if (tok_begin % pt) return fail(c, CAKE_E_INVAL, "load range must start on a page boundary");
     const int p0 = tok_begin / pt, p1 = (tok_begin + tok_count + pt - 1) / pt;
+    if (st->format != CAKE_STORE_RAW && st->format != CAKE_STORE_INT8) return fail(c, CAKE_E_INVAL, "store: unknown format %d", st->format);
     const uint64_t layer_bytes = uint64_t(2) * m.n_kv_heads * pt * m.head_dim * esize(c);
-    const uint64_t image_bytes = layer_bytes * m.n_layers;
+    const uint64_t image_bytes = cake::store_image_bytes(m, pt, st->format);
     if (st->page_stride_bytes < image_bytes) return fail(c, CAKE_E_INVAL, "store: page stride smaller than a page image");
     if (p1 > st->n_pages) return fail(c, CAKE_E_STORE_MISS, "store holds %d pages, page %d requested", st->n_pages, p1 - 1);
     const uint64_t piece_max = c->tun.piece_bytes ? c->tun.piece_bytes : (4ull << 20);
+    if (st->format == CAKE_STORE_INT8) {
+        int rc = ensure_stage(c, uint64_t(p1 - p0) * image_bytes);
+        if (rc != CAKE_OK) return rc;
+    }
     const uint64_t start = mono_ns();
     c->load_bytes_done.store(0);
     c->load_start_ns.store(start);
     double release = 0.0;  // ns after start at which the tier has delivered everything issued so far
+    auto paced_copy = [&](char* dst, const char* src, uint64_t bytes) -> int {
+        for (uint64_t off = 0; off < bytes; off += piece_max) {
+            uint64_t n = std::min(piece_max, bytes - off);
+            double rate = fixed_gbps < 0 ? live_rate(c) : fixed_gbps;
+            if (rate > 0) {
+                release += double(n) / rate;  // GB/s = bytes per ns
+                wait_until_ns(start + uint64_t(release));
+            }
+            HIP_TRY(c, hipMemcpyAsync(dst + off, src + off, n, hipMemcpyHostToDevice, c->ls));
+            c->load_bytes_done.fetch_add(n, std::memory_order_relaxed);
+        }
+        return CAKE_OK;
+    };
     for (int p = p0; p < p1; ++p) {
         const char* img = (const char*)st->base + uint64_t(p) * st->page_stride_bytes;
         const int pp = kv->block_table_host[p];
+        if (st->format == CAKE_STORE_INT8) {
+            // the whole image lands in the staging buffer, then one kernel on the copy stream
+            // dequantises it into the page of every layer; stream order keeps the two apart
+            char* stage = (char*)c->q_stage + uint64_t(p - p0) * image_bytes;
+            int rc = paced_copy(stage, img, image_bytes);
+            if (rc != CAKE_OK) return rc;
+            HIP_TRY(c, launch_dequant_page(m.dtype, stage, make_view(c, kv, 0), pp, m.n_layers, c->ls));
+            continue;
+        }
         for (int l = 0; l < m.n_layers; ++l) {
             char* dst = (char*)kv->pool + (uint64_t(l) * kv->n_physical_pages + pp) * layer_bytes;
-            const char* src = img + uint64_t(l) * layer_bytes;
-            for (uint64_t off = 0; off < layer_bytes; off += piece_max) {
-                uint64_t n = std::min(piece_max, layer_bytes - off);
-                double rate = fixed_gbps < 0 ? live_rate(c) : fixed_gbps;
-                if (rate > 0) {
-                    release += double(n) / rate;  // GB/s = bytes per ns
-                    wait_until_ns(start + uint64_t(release));
-                }
-                HIP_TRY(c, hipMemcpyAsync(dst + off, src + off, n, hipMemcpyHostToDevice, c->ls));
-                c->load_bytes_done.fetch_add(n, std::memory_order_relaxed);
-            }
+            int rc = paced_copy(dst, img + uint64_t(l) * layer_bytes, layer_bytes);
+            if (rc != CAKE_OK) return rc;
         }
     }
     return CAKE_OK;
@@ -378,6 +409,7 @@ int32_t cake_destroy(cake_ctx* c) {
     (void)hipFree(c->ao); (void)hipFree(c->act); (void)hipFree(c->rope_cs); (void)hipFree(c->d_ids);
     (void)hipFree(c->t_h); (void)hipFree(c->t_q); (void)hipFree(c->t_qr); (void)hipFree(c->t_ao);
     (void)hipFree(c->t_act); (void)hipFree(c->t_logits); (void)hipFree(c->t_part); (void)hipFree(c->t_tok);
+    (void)hipFree(c->q_stage);
     for (hipEvent_t e : c->prof_events) (void)hipEventDestroy(e);
     if (c->ev_a) (void)hipEventDestroy(c->ev_a);
     if (c->ev_b) (void)hipEventDestroy(c->ev_b);
@@ -447,7 +479,8 @@ int32_t cake_bidirectional_prefill(cake_ctx* c, const int32_t* token_ids, int32_
     if (mode != CAKE_COMPUTE_ONLY) {
         if (!store || !store->base) return fail(c, CAKE_E_INVAL, "store: null");
         if (store->page_tokens != kv->page_tokens) return fail(c, CAKE_E_INVAL, "store/page size mismatch");
-        if (store->page_stride_bytes < cake::page_image_bytes(c->m, kv->page_tokens))
+        if (store->format != CAKE_STORE_RAW && store->format != CAKE_STORE_INT8) return fail(c, CAKE_E_INVAL, "store: unknown format %d", store->format);
+        if (store->page_stride_bytes < cake::store_image_bytes(c->m, kv->page_tokens, store->format))
             return fail(c, CAKE_E_INVAL, "store: page stride smaller than a page image");
         if (!(gbps > 0)) return fail(c, CAKE_E_INVAL, "gbps must be positive");
     }
@@ -457,7 +490,7 @@ int32_t cake_bidirectional_prefill(cake_ctx* c, const int32_t* token_ids, int32_
 
     std::vector<int32_t> tb(n), tc(n);
     std::vector<uint64_t> flops(n), bytes(n);
-    const uint64_t image = cake::page_image_bytes(c->m, kv->page_tokens);
+    const uint64_t image = cake::store_image_bytes(c->m, kv->page_tokens, store ? store->format : CAKE_STORE_RAW);
     for (int i = 0; i < n; ++i) {
         tb[i] = i * chunk;
         tc[i] = std::min(chunk, n_tokens - tb[i]);
@@ -546,6 +579,39 @@ int32_t cake_first_token(cake_ctx* c, const int32_t* token_ids, int32_t n_tokens
     return CAKE_OK;
 }
 
+int32_t cake_write_store(cake_ctx* c, const cake_kv* kv, int32_t n_tokens, const cake_kv_store* dst) {
+    if (!c || !dst || !dst->base) return CAKE_E_INVAL;
+    if (n_tokens <= 0 || n_tokens > c->max_tokens) return fail(c, CAKE_E_INVAL, "n_tokens %d outside (0, %d]", n_tokens, c->max_tokens);
+    int rc = check_kv(c, kv, n_tokens);
+    if (rc != CAKE_OK) return rc;
+    if (dst->format != CAKE_STORE_RAW && dst->format != CAKE_STORE_INT8) return fail(c, CAKE_E_INVAL, "store: unknown format %d", dst->format);
+    const int pt = kv->page_tokens, n_pages = (n_tokens + pt - 1) / pt;
+    const uint64_t image = cake::store_image_bytes(c->m, pt, dst->format);
+    if (dst->page_tokens != pt || dst->page_stride_bytes < image || dst->n_pages < n_pages)
+        return fail(c, CAKE_E_INVAL, "store does not fit %d pages of %llu bytes", n_pages, (unsigned long long)image);
+    const uint64_t layer_bytes = uint64_t(2) * c->m.n_kv_heads * pt * c->m.head_dim * esize(c);
+    if (dst->format == CAKE_STORE_INT8) {
+        rc = ensure_stage(c, image);
+        if (rc != CAKE_OK) return rc;
+    }
+    for (int p = 0; p < n_pages; ++p) {
+        char* out = (char*)dst->base + uint64_t(p) * dst->page_stride_bytes;
+        const int pp = kv->block_table_host[p];
+        if (dst->format == CAKE_STORE_INT8) {
+            char* stage = (char*)c->q_stage;   // quantise, copy out, next page: one stream keeps them in order
+            HIP_TRY(c, launch_quant_page(c->m.dtype, stage, make_view(c, kv, 0), pp, c->m.n_layers, c->cs));
+            HIP_TRY(c, hipMemcpyAsync(out, stage, image, hipMemcpyDeviceToHost, c->cs));
+        } else {
+            for (int l = 0; l < c->m.n_layers; ++l) {
+                const char* src = (const char*)kv->pool + (uint64_t(l) * kv->n_physical_pages + pp) * layer_bytes;
+                HIP_TRY(c, hipMemcpyAsync(out + uint64_t(l) * layer_bytes, src, layer_bytes, hipMemcpyDeviceToHost, c->cs));
+            }
+        }
+    }
+    HIP_TRY(c, hipStreamSynchronize(c->cs));
+    return CAKE_OK;
+}
+
 int32_t cake_set_traces(cake_ctx* c, const cake_traces* t) {
     if (!c) return CAKE_E_INVAL;
     c->tr_other.clear(); c->tr_ids.clear(); c->tr_gbps.clear(); c->tr_interval_ns = 0;
@@ -604,12 +670,14 @@ int32_t cake_adaptive_serve(cake_ctx* c, cake_request* reqs, int32_t n_reqs, int
         const cake_request& r = reqs[P];
         if (!r.store || !r.store->base) return fail(c, CAKE_E_INVAL, "prefix request without a store");
         if (fetch_chunk <= 0 || fetch_chunk % r.kv->page_tokens) return fail(c, CAKE_E_INVAL, "fetch_chunk must be a multiple of page_tokens");
-        if (r.store->page_tokens != r.kv->page_tokens || r.store->page_stride_bytes < cake::page_image_bytes(c->m, r.kv->page_tokens))
+        if (r.store->format != CAKE_STORE_RAW && r.store->format != CAKE_STORE_INT8) return fail(c, CAKE_E_INVAL, "store: unknown format %d", r.store->format);
+        if (r.store->page_tokens != r.kv->page_tokens ||
+            r.store->page_stride_bytes < cake::store_image_bytes(c->m, r.kv->page_tokens, r.store->format))
             return fail(c, CAKE_E_INVAL, "store does not match the page layout");
         if (!(gbps > 0)) return fail(c, CAKE_E_INVAL, "gbps must be positive");
         nc = (r.n_tokens + fetch_chunk - 1) / fetch_chunk;
         tb.resize(nc); tc.resize(nc); flops.resize(nc); bytes.resize(nc);
-        const uint64_t image = cake::page_image_bytes(c->m, r.kv->page_tokens);
+        const uint64_t image = cake::store_image_bytes(c->m, r.kv->page_tokens, r.store->format);
         for (int i = 0; i < nc; ++i) {
             tb[i] = i * fetch_chunk;
             tc[i] = std::min(fetch_chunk, r.n_tokens - tb[i]);

@@ -52,6 +52,11 @@ uint64_t cake_range_flops(const cake_model_desc* model, int32_t tok_begin, int32
     return cake::range_flops(*model, tok_begin, tok_count);
 }
 
+uint64_t cake_store_image_bytes(const cake_model_desc* model, int32_t page_tokens, int32_t format) {
+    if (!model || page_tokens <= 0 || (format != CAKE_STORE_RAW && format != CAKE_STORE_INT8)) return 0;
+    return cake::store_image_bytes(*model, page_tokens, format);
+}
+
 uint64_t cake_page_image_bytes(const cake_model_desc* model, int32_t page_tokens) {
     if (!model || page_tokens <= 0) return 0;
     return cake::page_image_bytes(*model, page_tokens);

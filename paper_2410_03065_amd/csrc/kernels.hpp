@@ -51,6 +51,12 @@ bool decode_attention_mfma_supported(int dtype, int head_dim, int page_tokens, i
 hipError_t launch_decode_attention_mfma(const float* q, float* part, int n_q, int n_keys, int tiles_per_split,
                                         int n_splits, const KvView& kv, hipStream_t st);
 
+// ---- 8-bit stored KV: one page image (all layers) <-> the layer pages of physical page phys_page ----
+hipError_t launch_dequant_page(int dtype, const void* image, const KvView& kv, int phys_page, int n_layers,
+                               hipStream_t st);
+hipError_t launch_quant_page(int dtype, void* image, const KvView& kv, int phys_page, int n_layers,
+                             hipStream_t st);
+
 // ---- first-token step (one row of activations: matrix-vector products, one-token attention) ----
 // out[n] (mode 0: =, 1: +=) sum_k x[k] w[n][k]; mode 2: out[n] = silu(x.w[n]) * (x.w2[n]).  x, out float32.
 hipError_t launch_gemv(int dtype, int mode, const float* x, const void* w, const void* w2, float* out,

@@ -74,6 +74,12 @@ inline uint64_t page_image_bytes(const cake_model_desc& m, int page_tokens) {
     return uint64_t(m.n_layers) * 2 * m.n_kv_heads * page_tokens * m.head_dim * e;
 }
 
+// Bytes of one page image in a store of the given format (cake_store_format).
+inline uint64_t store_image_bytes(const cake_model_desc& m, int page_tokens, int format) {
+    if (format == CAKE_STORE_INT8) return uint64_t(m.n_layers) * 2 * m.n_kv_heads * page_tokens * (uint64_t(m.head_dim) + 4);
+    return page_image_bytes(m, page_tokens);
+}
+
 // Running integer estimates (rules stated at cake_decision_log in cake.h).
 struct Estimator {
     uint64_t prior_c_ns = 1000000000ull, prior_c_flops = 500000000000000ull;

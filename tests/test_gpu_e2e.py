@@ -34,7 +34,7 @@ def _setup(shape, T, C, pt, seed=0, scramble=False, std=0.02):
     return w, toks, eng
 
 
-def _check_decisions(res, shape, T, C, pt, step_tokens=None):
+def _check_decisions(res, shape, T, C, pt, step_tokens=None, page_bytes=None):
     """Every logged look at the range is the brute-force optimum of its own logged inputs, and every
     claim is what the oracle's rules give for that look.  C is the chunk of the plan (the fetch unit
     when that is smaller than a compute step); step_tokens, if given, is the compute step every
@@ -42,7 +42,7 @@ def _check_decisions(res, shape, T, C, pt, step_tokens=None):
     n = (T + C - 1) // C
     flops = [mp.range_flops(shape.n_layers, shape.d_model, shape.n_q, shape.n_kv, shape.head_dim, shape.ffn,
                             i * C, min((i + 1) * C, T)) for i in range(n)]
-    per_page = pt * otf.kv_bytes_per_token(shape.n_layers, shape.n_kv, shape.head_dim, shape.elem_bytes)
+    per_page = page_bytes or pt * otf.kv_bytes_per_token(shape.n_layers, shape.n_kv, shape.head_dim, shape.elem_bytes)
     byts = [((min((i + 1) * C, T) - i * C + pt - 1) // pt) * per_page for i in range(n)]
     tok_count = [min((i + 1) * C, T) - i * C for i in range(n)]
     assert len(res.decisions) > 0
@@ -565,3 +565,65 @@ def test_traces_argument_errors():
     with pytest.raises(cake.CakeError):
         eng.set_traces(gbps_trace=[1.0], gbps_interval_ns=0)
     assert eng.lib.cake_set_traces(eng.ctx, None) == cake.OK
+
+
+# --------------------------------------------------------------------------- 8-bit stored KV on the load path
+def test_int8_store_load_is_bit_exact_and_quantiser_matches():
+    """Pages loaded from an int8 store equal the oracle's dequantised values bit for bit (the code x
+    scale product and the storage rounding are fixed by the format); the GPU's store writer
+    produces the oracle's codes and scales from the same pages."""
+    import paper_2410_03065_amd as cake
+    for kind, shape, T, pt in (("bf16", BF_NARROW_GQA4, 1000, 256), ("f32", si.TINY, 500, 128)):
+        rng = np.random.default_rng(9)
+        eng = cake.Engine(shape, si.make_weights(shape, seed=1), max_tokens=((T + pt - 1) // pt) * pt, max_chunk=pt,
+                          page_tokens=pt, block_table=np.random.default_rng(2).permutation((T + pt - 1) // pt).astype(np.int32))
+        cache = otf.KVCache(shape.n_layers, T, shape.n_kv, shape.head_dim)
+        cache.k[:] = otf.round_storage(rng.standard_normal(cache.k.shape) * 4, kind)
+        cache.v[:] = otf.round_storage(rng.standard_normal(cache.v.shape), kind)
+        cache.v[0, 5] = 0.0                                                  # a row of zeros: scale 0
+        img8 = ostore.pack_store_int8(cache, pt)
+        eng.set_store_int8(img8)
+        res = eng.bidirectional_prefill(si.make_tokens(T, shape.vocab, seed=3), pt, 2.0, mode="load_only")
+        assert res.meet_point == 0 and res.load_bytes == img8.size
+        want = ostore.pack_store(ostore.unpack_store_int8(img8, T, shape.n_kv, shape.head_dim, pt, kind), pt, kind)
+        np.testing.assert_array_equal(eng.pool_raw(T).view(want.dtype), want)
+        # the store writer on what the pages now hold: quantising dequantised values gives the codes back
+        t = eng.write_store(T, cake.STORE_INT8).numpy().reshape(img8.shape)
+        held = ostore.unpack_store(eng.pool_raw(T).view(want.dtype), T, shape.n_kv, shape.head_dim, pt, kind)
+        np.testing.assert_array_equal(t, ostore.pack_store_int8(held, pt))
+        # and a raw store written the same way is the pages themselves
+        t = eng.write_store(T, cake.STORE_RAW).numpy()
+        np.testing.assert_array_equal(t.view(want.dtype).reshape(want.shape), want)
+
+
+def test_bidirectional_with_int8_store_moves_the_meet_point_left():
+    """Sec. 5.5: the same tier bandwidth with an 8-bit store.  Computed chunks match the oracle's
+    bf16 KV as before, loaded chunks are the dequantised store (within half a quantisation step of
+    it), the plan counts the bytes the store really holds, and more of the prompt is loaded."""
+    import paper_2410_03065_amd as cake
+    shape, T, C, pt = BF_NARROW_GQA4, 8192, 512, 256
+    w, toks, eng = _setup(shape, T, C, pt, seed=70)
+    ref = otf.prefill_chunked(w, shape, toks, C, kv_dtype="bf16")
+    raw = ostore.pack_store(ref, pt, "bf16")
+    want = ostore.decode_words(raw, "bf16")
+    img8 = ostore.pack_store_int8(ref, pt)
+    deq = ostore.pack_store(ostore.unpack_store_int8(img8, T, shape.n_kv, shape.head_dim, pt, "bf16"), pt, "bf16")
+    eng.set_store(raw)
+    eng.bidirectional_prefill(toks, C, 4.0, mode="compute_only")
+    r_c = eng.bidirectional_prefill(toks, C, 4.0, mode="compute_only")
+    rate = T * otf.kv_bytes_per_token(shape.n_layers, shape.n_kv, shape.head_dim, 2) / r_c.ttft_ns
+    eng.clear_pool()
+    r16 = eng.bidirectional_prefill(toks, C, rate, mode="bidir")
+    eng.set_store_int8(img8)
+    eng.clear_pool()
+    r8 = eng.bidirectional_prefill(toks, C, rate, mode="bidir")
+    m, ppc = r8.meet_point, C // pt
+    got = eng.pool_images(T)
+    assert _errs(got, want).max() < TOL["bf16"]                              # against the unquantised oracle KV
+    np.testing.assert_array_equal(eng.pool_raw(T)[m * ppc:].view(np.uint16), deq[m * ppc:])
+    per_page8 = ostore.int8_image_bytes(shape.n_layers, shape.n_kv, shape.head_dim, pt)
+    assert all(c["work"] == ppc * per_page8 for c in r8.chunks if c["source"] == 1)
+    assert r8.load_bytes == (T // C - m) * ppc * per_page8
+    _check_decisions(r8, shape, T, C, pt, page_bytes=per_page8)
+    # tier as fast as the GPU on 16-bit KV: about 8 of 16 chunks loaded there, about 11 with 8-bit KV
+    assert 0 < r8.meet_point < r16.meet_point

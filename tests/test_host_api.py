@@ -34,6 +34,7 @@ def test_struct_sizes_match_the_header_layout():
     assert ctypes.sizeof(cake.ModelDesc) == 40
     assert ctypes.sizeof(cake.Tuning) == 40
     assert ctypes.sizeof(cake.Kv) == 40
+    assert ctypes.sizeof(cake.KvStore) == 32 and ctypes.sizeof(cake.Traces) == 56
 
 
 def test_planner_equals_brute_force_bit_exactly():
