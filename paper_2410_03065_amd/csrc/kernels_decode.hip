@@ -289,20 +289,32 @@ decode_attention_kernel(const float* __restrict__ q, float* __restrict__ part, i
     }
 }
 
+// One workgroup per query head; thread d owns output element d.  The per-split (max, sum) pairs are
+// read by one lane each and reduced across the wave, so no thread walks the splits one dependent
+// load after another.
 template <int HD>
 __global__ void __launch_bounds__(HD) decode_combine_kernel(const float* __restrict__ part, float* __restrict__ out,
                                                             int n_splits) {
+    __shared__ float coef[DEC_MAX_SPLITS];
+    __shared__ float den_s;
     const int h = blockIdx.x, d = threadIdx.x;
     const float* p = part + size_t(h) * n_splits * (HD + 2);
-    float m = -INFINITY;
-    for (int s = 0; s < n_splits; ++s) m = fmaxf(m, p[s * (HD + 2) + HD]);
-    float num = 0.f, den = 0.f;
-    for (int s = 0; s < n_splits; ++s) {
-        const float c = __expf(p[s * (HD + 2) + HD] - m);
-        num += p[s * (HD + 2) + d] * c;
-        den += p[s * (HD + 2) + HD + 1] * c;
+    if (d < 64) {   // first wave: splits d and d + 64
+        const float m0 = d < n_splits ? p[d * (HD + 2) + HD] : -INFINITY;
+        const float m1 = d + 64 < n_splits ? p[(d + 64) * (HD + 2) + HD] : -INFINITY;
+        const float m = wmax(fmaxf(m0, m1));
+        const float c0 = d < n_splits ? __expf(m0 - m) : 0.f, c1 = d + 64 < n_splits ? __expf(m1 - m) : 0.f;
+        float den = (d < n_splits ? p[d * (HD + 2) + HD + 1] * c0 : 0.f) + (d + 64 < n_splits ? p[(d + 64) * (HD + 2) + HD + 1] * c1 : 0.f);
+        den = wsum(den);
+        coef[d] = c0;
+        coef[d + 64] = c1;
+        if (d == 0) den_s = den;
     }
-    out[size_t(h) * HD + d] = num / den;
+    __syncthreads();
+    float num = 0.f;
+#pragma unroll 8
+    for (int s = 0; s < n_splits; ++s) num += p[s * (HD + 2) + d] * coef[s];
+    out[size_t(h) * HD + d] = num / den_s;
 }
 
 int decode_attention_splits(int n_keys, int n_kv) {
