@@ -188,7 +188,7 @@ typedef struct {
     uint64_t prior_compute_ns, prior_compute_flops; /* default 1e9 ns per 5e14 FLOP */
     uint64_t piece_bytes;                           /* largest single DMA; default 4 MiB */
     int32_t kernel_path; /* 0: MFMA kernels where the shape allows (bf16); 1: generic kernels only */
-    int32_t gemm_config; /* 0: tile shape chosen per GEMM; 1..4: force 256x256 / 256x128 / 128x128 / 128x192 (testing) */
+    int32_t gemm_config; /* 0: tile shape chosen per GEMM; 1..5: force 256x256 / 256x128 / 128x128 / 128x192 / 128x64 (testing) */
     int32_t attn_variant; /* 0: eight-wave attention kernel; 1: four-wave kernel (testing) */
     int32_t pad_;
 } cake_tuning;

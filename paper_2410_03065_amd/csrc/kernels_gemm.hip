@@ -139,7 +139,8 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
     auto interleave = [&]() {
 #pragma unroll
         for (int i = 0; i < WTM + WTN; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, (WTM * WTN) / (WTM + WTN), 0);  // MFMA
+            if constexpr ((WTM * WTN) / (WTM + WTN) > 0)
+                __builtin_amdgcn_sched_group_barrier(0x008, (WTM * WTN) / (WTM + WTN), 0);  // MFMA
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                          // DS read
         }
     };
@@ -204,13 +205,13 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
 
 // Tile configurations.  Chosen per GEMM by gemm_pick() from how well the grid fills 256 CUs.
 struct GemmCfg { int bm, bn; };
-enum { GCFG_256x256 = 0, GCFG_256x128 = 1, GCFG_128x128 = 2, GCFG_128x192 = 3, GCFG_COUNT = 4 };
-static const GemmCfg kGemmCfg[GCFG_COUNT] = {{256, 256}, {256, 128}, {128, 128}, {128, 192}};
+enum { GCFG_256x256 = 0, GCFG_256x128 = 1, GCFG_128x128 = 2, GCFG_128x192 = 3, GCFG_128x64 = 4, GCFG_COUNT = 5 };
+static const GemmCfg kGemmCfg[GCFG_COUNT] = {{256, 256}, {256, 128}, {128, 128}, {128, 192}, {128, 64}};
 
 static int out_cols_per_tile(int cfg, int epi) { return epi == EPI_SWIGLU ? kGemmCfg[cfg].bn / 2 : kGemmCfg[cfg].bn; }
 
 static bool gemm_cfg_ok(int cfg, int epi, int M, int N, int K) {
-    if (cfg == GCFG_128x192 && epi == EPI_SWIGLU) return false;   // three n-tiles per wave: no gate/up pairs
+    if ((cfg == GCFG_128x192 || cfg == GCFG_128x64) && epi == EPI_SWIGLU) return false;   // odd n-tiles per wave: no gate/up pairs
     return M > 0 && N > 0 && K >= 32 && (K % 32) == 0 && (N % out_cols_per_tile(cfg, epi)) == 0;
 }
 
@@ -220,7 +221,7 @@ bool gemm_mfma_supported(int epi, int M, int N, int K) { return gemm_cfg_ok(GCFG
 // area divided by a per-shape efficiency (measured: larger tiles feed the MFMAs better because
 // they pull fewer bytes per flop through L2).
 static int gemm_pick(int epi, int M, int N, int K) {
-    static const double eff[GCFG_COUNT] = {1.0, 0.85, 0.80, 0.82};
+    static const double eff[GCFG_COUNT] = {1.0, 0.85, 0.80, 0.82, 0.60};
     int best = GCFG_128x128;
     double best_cost = 1e30;
     for (int cfg = GCFG_COUNT - 1; cfg >= 0; --cfg) {
@@ -261,6 +262,13 @@ static hipError_t gemm_launch_cfg(int cfg, const bf16_t* A, const bf16_t* W, con
         case GCFG_128x192:
             if constexpr (EPI != EPI_SWIGLU) return gemm_launch_t<2, 3, 2, 2, 32, 4, EPI>(A, W, W2, out, M, N, K, st);
             else return hipErrorInvalidValue;
+        case GCFG_128x64:   // half-size chunks (M = 512): the only shape that still gives N = 4096 GEMMs 256 tiles
+            if constexpr (EPI != EPI_SWIGLU) {
+                if ((K % 64) == 0) return gemm_launch_t<2, 1, 2, 2, 64, 4, EPI>(A, W, W2, out, M, N, K, st);
+                return gemm_launch_t<2, 1, 2, 2, 32, 4, EPI>(A, W, W2, out, M, N, K, st);
+            } else {
+                return hipErrorInvalidValue;
+            }
         default:
             // one workgroup per CU at most: spend the whole LDS on a deep ring of 64-deep slices
             // (96 KB in flight per CU); more tiles than CUs: 64 KB rings so two workgroups share a CU

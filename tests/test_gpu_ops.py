@@ -51,6 +51,7 @@ def test_rmsnorm(kind, rows, d):
     ("bf16", 0, 257, 256, 32, 1), ("bf16", 0, 257, 256, 64, 2), ("bf16", 0, 129, 256, 160, 3),  # short K, ragged M
     ("bf16", 0, 1024, 2048, 1024, 1),
     ("bf16", 0, 700, 384, 96, 4), ("bf16", 0, 129, 768, 160, 4), ("bf16", 0, 1024, 6144, 512, 0),   # 128x192 tiles
+    ("bf16", 0, 300, 192, 96, 5), ("bf16", 0, 512, 4096, 1024, 0), ("bf16", 0, 129, 64, 192, 5),   # 128x64 tiles
 ])
 def test_gemm_variants(kind, path, M, N, K, cfg):
     import torch
