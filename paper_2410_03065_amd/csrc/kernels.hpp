@@ -43,7 +43,8 @@ bool gemm_mfma_supported(int epi, int M, int N, int K);
 hipError_t launch_gemm_mfma(int epi, const void* a, const void* w, const void* w2, void* out,
                             int M, int N, int K, hipStream_t st, int cfg_override = -1);
 bool attention_mfma_supported(int head_dim, int page_tokens);
-// variant: 0 = eight waves per workgroup (two per SIMD, keys split between the halves); 1 = four waves.
+// variant: 0 = eight-wave kernel, 128 or 64 queries per workgroup by grid size; 1 = four-wave kernel;
+// 2 / 3 = eight-wave kernel with 128 / 64 queries per workgroup (testing).
 hipError_t launch_attention_mfma(const void* q, void* out, int n_q, int tok_begin, int rows,
                                  const KvView& kv, hipStream_t st, int variant = 0);
 

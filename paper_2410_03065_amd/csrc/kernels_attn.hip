@@ -359,13 +359,19 @@ constexpr int A8_RING = 2 * A_KBYTES;        // one ring slot: group A's tile th
 constexpr int A8_VBASE = 2 * A8_RING;        // V^T ring after the K ring
 constexpr int A8_TABLE = 4 * A8_RING;        // page offsets after both rings
 
-__global__ void __launch_bounds__(512)
+// QW = query waves per half (4: 128 queries per workgroup; 2: 64 queries, for launches whose
+// 128-query grid would leave CUs idle, e.g. 512-token chunks of a 32-head model).
+template <int QW>
+__global__ void __launch_bounds__(128 * QW)
 attention_mfma8_kernel(const bf16_t* __restrict__ q, bf16_t* __restrict__ out, int n_q, int tok_begin, int rows,
                        KvView kv, int q_tiles) {
+    constexpr int AQW = 32 * QW;        // queries per workgroup
+    constexpr int PER = 16 / QW;        // wave-loads per wave per K (or V^T) tile
+    constexpr int KP = QW >= 4 ? 1 : 4 / QW;   // period after which the K swizzle term of a wave's loads repeats
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave8 = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wave = wave8 & 3, grp = wave8 >> 2;
+    const int wave = wave8 % QW, grp = wave8 / QW;
     const int lrow = lane & 31, lhalf = lane >> 5;
     const int G = kv.n_kv, r = n_q / G;
     int g, rest;
@@ -378,13 +384,13 @@ attention_mfma8_kernel(const bf16_t* __restrict__ q, bf16_t* __restrict__ out, i
         rest = blockIdx.x / G;
     }
     const int h = g * r + rest % r;
-    const int q0 = (rest / r) * AQ;
+    const int q0 = (rest / r) * AQW;
     const int pt = kv.page_tokens;
 
     const int my_row = min(q0 + wave * 32 + lrow, rows - 1);
     const int my_pos = tok_begin + my_row;
     const int wave_first_pos = tok_begin + min(q0 + wave * 32, rows - 1);
-    const int wg_last_pos = tok_begin + min(q0 + AQ, rows) - 1;
+    const int wg_last_pos = tok_begin + min(q0 + AQW, rows) - 1;
     const int n_tiles = wg_last_pos / AK + 1;
     const int n_pairs = (n_tiles + 1) >> 1;
     const int first_masked = (wave_first_pos + 1) / AK;   // first tile with a key some query of this wave must not see
@@ -395,12 +401,17 @@ attention_mfma8_kernel(const bf16_t* __restrict__ q, bf16_t* __restrict__ out, i
 #pragma unroll
         for (int ks = 0; ks < AHD / 16; ++ks) qreg[ks] = *(const bf16x8*)(qp + 16 * ks);
     }
-    // lane offsets of this wave's first K / V^T wave-load of a tile; the other three are a
-    // wave-uniform distance further (16 key rows / 32 head-dim rows), the swizzle term repeats
-    unsigned koff0, voff0;
+    // lane offsets of this wave's K / V^T wave-loads of a tile: load i covers 1 KB = key rows
+    // 4j .. 4j+3 (V^T: head-dim rows 8j .. 8j+7) with j = wave + QW*i.  The swizzle term of the K
+    // rows repeats every KP loads, that of the V^T rows with every load, so the other loads are a
+    // wave-uniform distance from these.
+    unsigned koffp[KP], voff0;
+#pragma unroll
+    for (int i = 0; i < KP; ++i) {
+        int krow = 4 * (wave + QW * i) + (lane >> 4), kpos = lane & 15;
+        koffp[i] = unsigned(krow * AHD + ((kpos ^ (krow & 15)) << 3)) * 2u;
+    }
     {
-        int krow = 4 * wave + (lane >> 4), kpos = lane & 15;
-        koff0 = unsigned(krow * AHD + ((kpos ^ (krow & 15)) << 3)) * 2u;
         int vrow = 8 * wave + (lane >> 3), vpos = lane & 7;
         voff0 = unsigned(vrow * pt + ((vpos ^ ((vrow >> 1) & 7)) << 3)) * 2u;
     }
@@ -409,7 +420,7 @@ attention_mfma8_kernel(const bf16_t* __restrict__ q, bf16_t* __restrict__ out, i
     {
         const size_t layer_base = size_t(kv.layer) * kv.n_physical_pages;
         const size_t page_bytes = kv.page_elems() * 2, k_head = size_t(g) * pt * AHD * 2;
-        for (int i = tid; i <= last_page; i += 512) pg_lds[i] = (layer_base + kv.block_table[i]) * page_bytes + k_head;
+        for (int i = tid; i <= last_page; i += 128 * QW) pg_lds[i] = (layer_base + kv.block_table[i]) * page_bytes + k_head;
     }
     __syncthreads();
     const unsigned long long k_to_v = (size_t(G - g) * pt * AHD + size_t(g) * AHD * pt) * 2;
@@ -428,18 +439,18 @@ attention_mfma8_kernel(const bf16_t* __restrict__ q, bf16_t* __restrict__ out, i
         const char* kp = page_base(tile_of(pair), &in_page0) + size_t(in_page0) * (AHD * 2);
         unsigned char* sa = lds + (pair & 1) * A8_RING + grp * A_KBYTES;
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-            __builtin_amdgcn_global_load_lds((const CAKE_GLOBAL_AS void*)(kp + size_t(i) * (16 * AHD * 2) + koff0),
-                                             (CAKE_LDS_AS void*)(sa + (wave + 4 * i) * 1024), 16, 0, 0);
+        for (int i = 0; i < PER; ++i)
+            __builtin_amdgcn_global_load_lds((const CAKE_GLOBAL_AS void*)(kp + size_t(i / KP) * (4 * QW * KP * AHD * 2) + koffp[i % KP]),
+                                             (CAKE_LDS_AS void*)(sa + (wave + QW * i) * 1024), 16, 0, 0);
     };
     auto issue_v = [&](int pair) {
         unsigned in_page0;
         const char* vp = page_base(tile_of(pair), &in_page0) + k_to_v + size_t(in_page0) * 2;
         unsigned char* sa = lds + A8_VBASE + (pair & 1) * A8_RING + grp * A_KBYTES;
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-            __builtin_amdgcn_global_load_lds((const CAKE_GLOBAL_AS void*)(vp + size_t(i) * 32 * pt * 2 + voff0),
-                                             (CAKE_LDS_AS void*)(sa + (wave + 4 * i) * 1024), 16, 0, 0);
+        for (int i = 0; i < PER; ++i)
+            __builtin_amdgcn_global_load_lds((const CAKE_GLOBAL_AS void*)(vp + size_t(i) * (8 * QW) * pt * 2 + voff0),
+                                             (CAKE_LDS_AS void*)(sa + (wave + QW * i) * 1024), 16, 0, 0);
     };
 
     const int sk = sigma16(lrow & 15);
@@ -579,9 +590,9 @@ attention_mfma8_kernel(const bf16_t* __restrict__ q, bf16_t* __restrict__ out, i
     issue_v(0);
     if (n_pairs > 1) {
         issue_k(1);
-        asm volatile("s_waitcnt vmcnt(8)");
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * PER));
     } else {
-        asm volatile("s_waitcnt vmcnt(4)");
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PER));
     }
     __builtin_amdgcn_s_barrier();
     f32x16 s_a[2], s_b[2];
@@ -817,7 +828,8 @@ hipError_t launch_attention_mfma(const void* q, void* out, int n_q, int tok_begi
     const int q_tiles = (rows + AQ - 1) / AQ;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)attention_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_MAX);
-        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attention_mfma8_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_MAX);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attention_mfma8_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_MAX);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attention_mfma8_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_MAX);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
@@ -829,8 +841,14 @@ hipError_t launch_attention_mfma(const void* q, void* out, int n_q, int tok_begi
     } else {
         const int LDS = A8_TABLE + table;
         if (LDS > LDS_MAX) return hipErrorInvalidValue;
-        hipLaunchKernelGGL(attention_mfma8_kernel, dim3(q_tiles * n_q), dim3(512), LDS, st, (const bf16_t*)q, (bf16_t*)out, n_q,
-                           tok_begin, rows, kv, q_tiles);
+        // 64-query workgroups when 128-query ones would not fill the chip
+        const int q_tiles64 = (rows + 63) / 64;
+        if (variant == 3 || (variant == 0 && q_tiles * n_q < 256 && q_tiles64 > q_tiles))
+            hipLaunchKernelGGL(attention_mfma8_kernel<2>, dim3(q_tiles64 * n_q), dim3(256), LDS, st, (const bf16_t*)q, (bf16_t*)out,
+                               n_q, tok_begin, rows, kv, q_tiles64);
+        else
+            hipLaunchKernelGGL(attention_mfma8_kernel<4>, dim3(q_tiles * n_q), dim3(512), LDS, st, (const bf16_t*)q, (bf16_t*)out,
+                               n_q, tok_begin, rows, kv, q_tiles);
     }
     return hipGetLastError();
 }

@@ -115,7 +115,8 @@ def _rounded(cache, kind):
     return out
 
 
-@pytest.mark.parametrize("kind,path,variant", [("f32", 0, 0), ("bf16", 1, 0), ("bf16", 0, 0), ("bf16", 0, 1)])
+@pytest.mark.parametrize("kind,path,variant", [("f32", 0, 0), ("bf16", 1, 0), ("bf16", 0, 0), ("bf16", 0, 1), ("bf16", 0, 2),
+                                               ("bf16", 0, 3)])
 @pytest.mark.parametrize("tok_begin,rows", [(0, 130), (256, 256), (448, 77), (1, 1), (0, 64), (64, 1), (960, 200)])
 def test_attention(kind, path, variant, tok_begin, rows):
     import torch
