@@ -221,7 +221,7 @@ bool gemm_mfma_supported(int epi, int M, int N, int K) { return gemm_cfg_ok(GCFG
 // area divided by a per-shape efficiency (measured: larger tiles feed the MFMAs better because
 // they pull fewer bytes per flop through L2).
 static int gemm_pick(int epi, int M, int N, int K) {
-    static const double eff[GCFG_COUNT] = {1.0, 0.85, 0.80, 0.82, 0.60};
+    static const double eff[GCFG_COUNT] = {1.0, 0.77, 0.62, 0.61, 0.45};   // measured TFLOP/s per busy CU, relative to 256x256
     int best = GCFG_128x128;
     double best_cost = 1e30;
     for (int cfg = GCFG_COUNT - 1; cfg >= 0; --cfg) {
