@@ -121,13 +121,24 @@ typedef struct {
  *   arrival (float32 product, rounded once to the KV element type). */
 typedef enum { CAKE_STORE_RAW = 0, CAKE_STORE_INT8 = 1 } cake_store_format;
 
+/* Where a store's bytes are.  CAKE_STORE_PINNED: pinned host memory at `base` (one hop, DMA reads it
+ * directly).  CAKE_STORE_FILE: a file open for reading (`fd`, page p at file_offset + p * stride):
+ * the load worker preads each piece into one of two pinned staging buffers and the DMA out of one
+ * runs while the other is filled (the paper's second hop: storage -> CPU memory -> GPU). */
+typedef enum { CAKE_STORE_PINNED = 0, CAKE_STORE_FILE = 1 } cake_store_source;
+
 typedef struct {
-    const void* base;           /* pinned host */
+    const void* base;           /* CAKE_STORE_PINNED: pinned host; else ignored */
     uint64_t page_stride_bytes; /* >= the page image size of `format` */
     int32_t page_tokens;        /* must equal cake_kv.page_tokens */
-    int32_t n_pages;            /* logical pages held */
+    int32_t n_pages;            /* logical pages held, from page 0: the stored prefix.  It may be shorter
+                                   than the prompt: chunks not wholly inside it are computed after the
+                                   race over the stored part has ended (App. A step 2: total_tokens) */
     int32_t format;             /* cake_store_format */
+    int32_t source;             /* cake_store_source */
+    int32_t fd;                 /* CAKE_STORE_FILE: descriptor, stays the caller's */
     int32_t pad_;
+    uint64_t file_offset;       /* CAKE_STORE_FILE: byte offset of page 0 */
 } cake_kv_store;
 
 /* One record per chunk, indexed by chunk number. */
@@ -173,7 +184,7 @@ typedef struct {
     /* out */
     int32_t n_chunks;
     int32_t n_decisions;       /* number recorded (<= cap) */
-    int32_t meet_point;        /* chunks [0,meet_point) were computed, the rest loaded */
+    int32_t meet_point;        /* chunks [0,meet_point) were computed, chunks [meet_point, stored_chunks) loaded */
     int32_t load_failed_chunk; /* -1, or the chunk whose load failed and was recomputed */
     uint64_t ttft_ns;          /* entry -> every chunk's KV resident */
     uint64_t compute_busy_ns;  /* sum of computed chunks' wall times */
@@ -181,6 +192,9 @@ typedef struct {
     uint64_t compute_flops;    /* algorithmic FLOPs of the computed chunks */
     uint64_t load_busy_ns;
     uint64_t load_bytes;
+    int32_t stored_chunks;     /* chunks wholly inside the stored prefix (= n_chunks when the store covers the
+                                  prompt); chunks [stored_chunks, n_chunks) were computed after the race */
+    int32_t pad_;
 } cake_result;
 
 /* Priors used before the first measurement, and pacing granularity. 0 = default. */
@@ -332,6 +346,20 @@ int32_t cake_adaptive_serve(cake_ctx* ctx, cake_request* requests, int32_t n_req
 int32_t cake_first_token(cake_ctx* ctx, const int32_t* token_ids, int32_t n_tokens,
                          const cake_kv* kv, int32_t* token_out, float* logits_out,
                          uint64_t* device_ns_out);
+
+/* Chunk-prefix keys (App. A step 2; App. B: the store hashes token chunks into keys).  One key per
+ * FULL chunk of chunk_tokens ids; key i identifies the whole prefix [0, (i+1)*chunk_tokens):
+ *   key_i = FNV-1a-64(8 bytes of key_{i-1}, little-endian, then the chunk's ids as little-endian
+ *   32-bit integers), key_{-1} = the FNV offset basis 0xcbf29ce484222325.
+ * Writes min(n_tokens / chunk_tokens, keys_cap) keys to keys_out (host) and returns
+ * n_tokens / chunk_tokens, or CAKE_E_INVAL.  Pure; no context, no GPU. */
+int32_t cake_prefix_keys(const int32_t* token_ids, int32_t n_tokens, int32_t chunk_tokens,
+                         uint64_t* keys_out, int32_t keys_cap);
+/* How many LEADING keys of `keys` occur in `stored_sorted` (ascending): the number of chunks of the
+ * prompt whose KV the store holds (the paper's total_tokens / chunk).  A key found behind a
+ * missing one does not count.  Returns the count, or CAKE_E_INVAL (also when not sorted). */
+int32_t cake_prefix_lookup(const uint64_t* stored_sorted, int32_t n_stored, const uint64_t* keys,
+                           int32_t n_keys);
 
 /* Bytes of one page image in a store of `format`. */
 uint64_t cake_store_image_bytes(const cake_model_desc* model, int32_t page_tokens, int32_t format);

@@ -31,9 +31,10 @@ EXPORTS = [
     "cake_range_flops", "cake_page_image_bytes", "cake_simulate_race", "cake_op_rmsnorm",
     "cake_op_gemm", "cake_op_gemm_residual", "cake_op_gemm_swiglu", "cake_op_rope_kv_write",
     "cake_op_attention", "cake_profile_enable", "cake_profile_read", "cake_adaptive_serve", "cake_first_token",
-    "cake_op_decode_attention", "cake_set_traces", "cake_store_image_bytes", "cake_write_store",
+    "cake_op_decode_attention", "cake_set_traces", "cake_store_image_bytes", "cake_write_store", "cake_prefix_keys", "cake_prefix_lookup",
 ]
 STORE_RAW, STORE_INT8 = 0, 1
+STORE_PINNED, STORE_FILE = 0, 1
 KERNEL_CLASSES = ["embed", "rmsnorm", "gemm_qkv", "rope_kv", "attention", "gemm_o", "gemm_gateup", "gemm_down",
                   "gemv", "decode_attention"]
 
@@ -65,7 +66,8 @@ class Kv(C.Structure):
 
 class KvStore(C.Structure):
     _fields_ = [("base", C.c_void_p), ("page_stride_bytes", C.c_uint64), ("page_tokens", C.c_int32),
-                ("n_pages", C.c_int32), ("format", C.c_int32), ("pad_", C.c_int32)]
+                ("n_pages", C.c_int32), ("format", C.c_int32), ("source", C.c_int32), ("fd", C.c_int32),
+                ("pad_", C.c_int32), ("file_offset", C.c_uint64)]
 
 
 class ChunkLog(C.Structure):
@@ -105,7 +107,7 @@ class Result(C.Structure):
                 ("n_chunks", C.c_int32), ("n_decisions", C.c_int32), ("meet_point", C.c_int32),
                 ("load_failed_chunk", C.c_int32), ("ttft_ns", C.c_uint64), ("compute_busy_ns", C.c_uint64),
                 ("compute_device_ns", C.c_uint64), ("compute_flops", C.c_uint64), ("load_busy_ns", C.c_uint64),
-                ("load_bytes", C.c_uint64)]
+                ("load_bytes", C.c_uint64), ("stored_chunks", C.c_int32), ("pad_", C.c_int32)]
 
 
 class KernelStats(C.Structure):
@@ -139,6 +141,8 @@ def load_library():
         "cake_first_token": (i32, [vp, vp, i32, P(Kv), P(i32), vp, P(u64)]),
         "cake_set_traces": (i32, [vp, P(Traces)]),
         "cake_store_image_bytes": (u64, [P(ModelDesc), i32, i32]),
+        "cake_prefix_keys": (i32, [vp, i32, i32, vp, i32]),
+        "cake_prefix_lookup": (i32, [vp, i32, vp, i32]),
         "cake_write_store": (i32, [vp, P(Kv), i32, P(KvStore)]),
         "cake_op_decode_attention": (i32, [vp, vp, vp, i32, i32, P(Kv)]),
         "cake_set_bandwidth": (i32, [vp, dbl]),
@@ -209,6 +213,29 @@ def simulate_race(chunk_flops, chunk_bytes, actual_compute_ns, actual_load_ns, p
     return t.value, [int(s) for s in src[:n]], _decisions_to_list(dec, nd.value)
 
 
+def prefix_keys(tokens, chunk_tokens):
+    """cake_prefix_keys -> list of uint64 keys, one per full chunk."""
+    lib = load_library()
+    ids = np.ascontiguousarray(tokens, dtype=np.int32)
+    n = len(ids) // chunk_tokens if chunk_tokens > 0 else 0
+    out = np.zeros(max(n, 1), dtype=np.uint64)
+    rc = lib.cake_prefix_keys(ids.ctypes.data, len(ids), chunk_tokens, out.ctypes.data, n)
+    if rc < 0:
+        raise CakeError(rc, "cake_prefix_keys")
+    return [int(k) for k in out[:n]]
+
+
+def prefix_lookup(stored_sorted, keys):
+    """cake_prefix_lookup -> number of leading chunks held by the store."""
+    lib = load_library()
+    st = np.ascontiguousarray(stored_sorted, dtype=np.uint64)
+    ks = np.ascontiguousarray(keys, dtype=np.uint64)
+    rc = lib.cake_prefix_lookup(st.ctypes.data if len(st) else None, len(st), ks.ctypes.data if len(ks) else None, len(ks))
+    if rc < 0:
+        raise CakeError(rc, "cake_prefix_lookup")
+    return rc
+
+
 def model_desc(shape) -> ModelDesc:
     return ModelDesc(shape.n_layers, shape.d_model, shape.n_q, shape.n_kv, shape.head_dim, shape.ffn, shape.vocab,
                      F32 if shape.dtype == "f32" else BF16, shape.rms_eps, shape.rope_theta)
@@ -237,6 +264,7 @@ class PrefillResult:
     chunks: List[dict] = field(default_factory=list)
     decisions: List[dict] = field(default_factory=list)
     status: int = 0
+    stored_chunks: int = -1
 
     @property
     def achieved_gbps(self) -> float:
@@ -353,7 +381,12 @@ class Engine:
     def _set_store_tensor(self, t, fmt=STORE_RAW):
         self.store_tensor = t
         stride = t.shape[1] * t.element_size()
-        self.store = KvStore(t.data_ptr(), stride, self.page_tokens, t.shape[0], fmt, 0)
+        self.store = KvStore(t.data_ptr(), stride, self.page_tokens, t.shape[0], fmt, STORE_PINNED, -1, 0, 0)
+
+    def set_file_store(self, fd, n_pages, stride, fmt=STORE_RAW, file_offset=0):
+        """A store read from an open file (two hops: file -> pinned staging -> pages)."""
+        self.store_tensor = None
+        self.store = KvStore(None, stride, self.page_tokens, n_pages, fmt, STORE_FILE, fd, 0, file_offset)
 
     def set_store_int8(self, images: np.ndarray):
         """images: [n_pages, L, 2, bytes] uint8 in the int8 store format (codes then scales per layer and K|V)."""
@@ -454,7 +487,8 @@ class Engine:
                                                  MODES[mode], forced_m, C.byref(self.kv), C.byref(res))
         self._check(rc, "cake_bidirectional_prefill", allow=(E_CAPACITY,))
         out = PrefillResult(res.meet_point, res.ttft_ns, res.n_chunks, res.load_failed_chunk, res.compute_busy_ns,
-                            res.compute_device_ns, res.compute_flops, res.load_busy_ns, res.load_bytes, status=rc)
+                            res.compute_device_ns, res.compute_flops, res.load_busy_ns, res.load_bytes, status=rc,
+                            stored_chunks=res.stored_chunks)
         if log:
             ck = [f[0] for f in ChunkLog._fields_]
             out.chunks = [{k: getattr(chunks[i], k) for k in ck} for i in range(min(n, res.n_chunks))]

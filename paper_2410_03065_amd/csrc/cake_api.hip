@@ -1,6 +1,8 @@
 // C ABI: context, chunk prefill, throttled chunk load, bidirectional prefill.
 // See include/cake.h for the contract of every entry point.
 #include <hip/hip_runtime.h>
+#include <errno.h>
+#include <unistd.h>
 
 #include <algorithm>
 #include <atomic>
@@ -43,6 +45,10 @@ struct cake_ctx {
     int32_t* t_tok = nullptr;
     void* q_stage = nullptr;   // device staging for int8 page images (allocated at the first use)
     size_t q_stage_bytes = 0;
+    // second hop of a file-backed store: two pinned buffers of one DMA piece each
+    void* f_stage[2] = {nullptr, nullptr};
+    size_t f_stage_bytes = 0;
+    int f_next = 0;
     hipEvent_t ev_a = nullptr, ev_b = nullptr;
     std::atomic<double> gbps{0.0};
     int step_after = -1;
@@ -87,6 +93,18 @@ static int fail(cake_ctx* ctx, int code, const char* fmt, ...) {
     } while (0)
 
 static size_t esize(const cake_ctx* c) { return c->m.dtype == CAKE_F32 ? 4 : 2; }
+
+static int check_store(cake_ctx* c, const cake_kv_store* st, const cake_kv* kv) {
+    if (!st) return fail(c, CAKE_E_INVAL, "store: null");
+    if (st->source == CAKE_STORE_PINNED ? !st->base : (st->source != CAKE_STORE_FILE || st->fd < 0))
+        return fail(c, CAKE_E_INVAL, "store: no memory / file given (source %d)", st->source);
+    if (st->format != CAKE_STORE_RAW && st->format != CAKE_STORE_INT8) return fail(c, CAKE_E_INVAL, "store: unknown format %d", st->format);
+    if (st->n_pages < 0) return fail(c, CAKE_E_INVAL, "store: negative page count");
+    if (st->page_tokens != kv->page_tokens) return fail(c, CAKE_E_INVAL, "store/page size mismatch");
+    if (st->page_stride_bytes < cake::store_image_bytes(c->m, kv->page_tokens, st->format))
+        return fail(c, CAKE_E_INVAL, "store: page stride smaller than a page image");
+    return CAKE_OK;
+}
 
 static int check_kv(cake_ctx* ctx, const cake_kv* kv, int tok_end) {
     if (!kv || !kv->pool || !kv->block_table_host || !kv->block_table_dev) return fail(ctx, CAKE_E_INVAL, "kv: null pointer");
@@ -244,11 +262,44 @@ static int ensure_stage(cake_ctx* c, uint64_t bytes) {
     return CAKE_OK;
 }
 
+static int ensure_file_stage(cake_ctx* c, uint64_t bytes) {
+    if (c->f_stage_bytes >= bytes) return CAKE_OK;
+    if (hipStreamSynchronize(c->ls) != hipSuccess) return fail(c, CAKE_E_HIP, "stream sync before staging growth");
+    for (int i = 0; i < 2; ++i) {
+        if (c->f_stage[i]) (void)hipHostFree(c->f_stage[i]);
+        c->f_stage[i] = nullptr;
+    }
+    c->f_stage_bytes = 0;
+    for (int i = 0; i < 2; ++i)
+        if (hipHostMalloc(&c->f_stage[i], bytes, hipHostMallocDefault) != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(c, CAKE_E_NOMEM, "pinned staging buffer of %llu bytes", (unsigned long long)bytes);
+        }
+    c->f_stage_bytes = bytes;
+    return CAKE_OK;
+}
+
+// Reads exactly n bytes at `off`; a short file or an I/O error is a store miss.
+static int pread_all(cake_ctx* c, int fd, void* dst, uint64_t n, uint64_t off) {
+    char* p = (char*)dst;
+    while (n > 0) {
+        ssize_t got = pread(fd, p, size_t(n), off_t(off));
+        if (got <= 0)
+            return fail(c, CAKE_E_STORE_MISS, "store file: read of %llu bytes at %llu failed (%s)", (unsigned long long)n,
+                        (unsigned long long)off, got == 0 ? "end of file" : strerror(errno));
+        p += got; off += uint64_t(got); n -= uint64_t(got);
+    }
+    return CAKE_OK;
+}
+
 // fixed_gbps > 0: that rate; == 0: unthrottled; < 0: the context's live rate.
 static int enqueue_load(cake_ctx* c, const cake_kv_store* st, int tok_begin, int tok_count, const cake_kv* kv,
                         double fixed_gbps) {
     const cake_model_desc& m = c->m;
-    if (!st || !st->base) return fail(c, CAKE_E_INVAL, "store: null");
+    if (!st) return fail(c, CAKE_E_INVAL, "store: null");
+    const bool from_file = st->source == CAKE_STORE_FILE;
+    if (st->source != CAKE_STORE_PINNED && !from_file) return fail(c, CAKE_E_INVAL, "store: unknown source %d", st->source);
+    if (from_file ? st->fd < 0 : !st->base) return fail(c, CAKE_E_INVAL, "store: no memory / file given");
     if (tok_count <= 0) return CAKE_OK;
     if (st->page_tokens != kv->page_tokens) return fail(c, CAKE_E_INVAL, "store/page size mismatch");
     const int pt = kv->page_tokens;
@@ -264,11 +315,16 @@ static int enqueue_load(cake_ctx* c, const cake_kv_store* st, int tok_begin, int
         int rc = ensure_stage(c, uint64_t(p1 - p0) * image_bytes);
         if (rc != CAKE_OK) return rc;
     }
+    if (from_file) {
+        int rc = ensure_file_stage(c, piece_max);
+        if (rc != CAKE_OK) return rc;
+    }
     const uint64_t start = mono_ns();
     c->load_bytes_done.store(0);
     c->load_start_ns.store(start);
     double release = 0.0;  // ns after start at which the tier has delivered everything issued so far
-    auto paced_copy = [&](char* dst, const char* src, uint64_t bytes) -> int {
+    // src: address in pinned memory, or byte position in the file
+    auto paced_copy = [&](char* dst, uint64_t src, uint64_t bytes) -> int {
         for (uint64_t off = 0; off < bytes; off += piece_max) {
             uint64_t n = std::min(piece_max, bytes - off);
             double rate = fixed_gbps < 0 ? live_rate(c) : fixed_gbps;
@@ -276,13 +332,27 @@ static int enqueue_load(cake_ctx* c, const cake_kv_store* st, int tok_begin, int
                 release += double(n) / rate;  // GB/s = bytes per ns
                 wait_until_ns(start + uint64_t(release));
             }
-            HIP_TRY(c, hipMemcpyAsync(dst + off, src + off, n, hipMemcpyHostToDevice, c->ls));
+            const void* from = (const void*)(uintptr_t)(src + off);
+            if (from_file) {
+                // two buffers: this piece is read from the file while the previous piece's DMA runs
+                const int b = c->f_next;
+                c->f_next ^= 1;
+                int rc = pread_all(c, st->fd, c->f_stage[b], n, src + off);
+                if (rc != CAKE_OK) return rc;
+                // the copy stream is in order: once it has drained, the DMA out of the OTHER buffer (issued one
+                // piece ago, running while this piece was read) is done and that buffer may be refilled next
+                HIP_TRY(c, hipStreamSynchronize(c->ls));
+                from = c->f_stage[b];
+                HIP_TRY(c, hipMemcpyAsync(dst + off, from, n, hipMemcpyHostToDevice, c->ls));
+            } else {
+                HIP_TRY(c, hipMemcpyAsync(dst + off, from, n, hipMemcpyHostToDevice, c->ls));
+            }
             c->load_bytes_done.fetch_add(n, std::memory_order_relaxed);
         }
         return CAKE_OK;
     };
     for (int p = p0; p < p1; ++p) {
-        const char* img = (const char*)st->base + uint64_t(p) * st->page_stride_bytes;
+        const uint64_t img = (from_file ? st->file_offset : uint64_t((uintptr_t)st->base)) + uint64_t(p) * st->page_stride_bytes;
         const int pp = kv->block_table_host[p];
         if (st->format == CAKE_STORE_INT8) {
             // the whole image lands in the staging buffer, then one kernel on the copy stream
@@ -410,6 +480,8 @@ int32_t cake_destroy(cake_ctx* c) {
     (void)hipFree(c->t_h); (void)hipFree(c->t_q); (void)hipFree(c->t_qr); (void)hipFree(c->t_ao);
     (void)hipFree(c->t_act); (void)hipFree(c->t_logits); (void)hipFree(c->t_part); (void)hipFree(c->t_tok);
     (void)hipFree(c->q_stage);
+    for (int i = 0; i < 2; ++i)
+        if (c->f_stage[i]) (void)hipHostFree(c->f_stage[i]);
     for (hipEvent_t e : c->prof_events) (void)hipEventDestroy(e);
     if (c->ev_a) (void)hipEventDestroy(c->ev_a);
     if (c->ev_b) (void)hipEventDestroy(c->ev_b);
@@ -477,17 +549,10 @@ int32_t cake_bidirectional_prefill(cake_ctx* c, const int32_t* token_ids, int32_
     const int n = (n_tokens + chunk - 1) / chunk;
     if (mode == CAKE_FORCED_SPLIT && (forced_m < 0 || forced_m > n)) return fail(c, CAKE_E_INVAL, "forced_m %d outside [0,%d]", forced_m, n);
     if (mode != CAKE_COMPUTE_ONLY) {
-        if (!store || !store->base) return fail(c, CAKE_E_INVAL, "store: null");
-        if (store->page_tokens != kv->page_tokens) return fail(c, CAKE_E_INVAL, "store/page size mismatch");
-        if (store->format != CAKE_STORE_RAW && store->format != CAKE_STORE_INT8) return fail(c, CAKE_E_INVAL, "store: unknown format %d", store->format);
-        if (store->page_stride_bytes < cake::store_image_bytes(c->m, kv->page_tokens, store->format))
-            return fail(c, CAKE_E_INVAL, "store: page stride smaller than a page image");
+        rc = check_store(c, store, kv);
+        if (rc != CAKE_OK) return rc;
         if (!(gbps > 0)) return fail(c, CAKE_E_INVAL, "gbps must be positive");
     }
-    if (mode != CAKE_LOAD_ONLY)
-        for (int i = 0; i < n_tokens; ++i)
-            if (token_ids[i] < 0 || token_ids[i] >= c->m.vocab) return fail(c, CAKE_E_INVAL, "token id at %d outside the vocabulary", i);
-
     std::vector<int32_t> tb(n), tc(n);
     std::vector<uint64_t> flops(n), bytes(n);
     const uint64_t image = cake::store_image_bytes(c->m, kv->page_tokens, store ? store->format : CAKE_STORE_RAW);
@@ -497,6 +562,20 @@ int32_t cake_bidirectional_prefill(cake_ctx* c, const int32_t* token_ids, int32_
         flops[i] = cake::range_flops(c->m, tb[i], tc[i]);
         bytes[i] = uint64_t((tc[i] + kv->page_tokens - 1) / kv->page_tokens) * image;
     }
+    // The store may hold only a prefix of the prompt (App. A step 2): the race covers the chunks
+    // wholly inside it, the others are computed once the raced part is complete.
+    int n_race = n;
+    if (mode != CAKE_COMPUTE_ONLY) {
+        const int64_t stored_tokens = std::min<int64_t>(n_tokens, int64_t(store->n_pages) * kv->page_tokens);
+        n_race = 0;
+        while (n_race < n && tb[n_race] + tc[n_race] <= stored_tokens) ++n_race;
+    }
+    if (mode == CAKE_FORCED_SPLIT && forced_m > n_race) return fail(c, CAKE_E_INVAL, "forced_m %d beyond the %d stored chunks", forced_m, n_race);
+    const bool computes = mode != CAKE_LOAD_ONLY || n_race < n;
+    if (computes)
+        for (int i = 0; i < n_tokens; ++i)
+            if (token_ids[i] < 0 || token_ids[i] >= c->m.vocab) return fail(c, CAKE_E_INVAL, "token id at %d outside the vocabulary", i);
+
     c->status.reset(new std::atomic<int32_t>[n]);
     c->n_status = n;
     for (int i = 0; i < n; ++i) c->status[i].store(CAKE_CHUNK_EMPTY);
@@ -508,7 +587,7 @@ int32_t cake_bidirectional_prefill(cake_ctx* c, const int32_t* token_ids, int32_
     ex.core.est.prior_l_ns = 1000000000ull;
     ex.core.est.prior_l_bytes = gbps > 0 ? uint64_t(gbps * 1e9) : 4000000000ull;
     if (ex.core.est.prior_l_bytes == 0) ex.core.est.prior_l_bytes = 1;
-    ex.core.init(n, flops.data(), bytes.data(), mode, forced_m);
+    ex.core.init(n_race, flops.data(), bytes.data(), mode, forced_m);
     ex.core.tok_begin = tb.data(); ex.core.tok_count = tc.data(); ex.core.model = &c->m;
     ex.core.log = res->decisions;
     ex.core.log_cap = res->decisions ? res->decisions_cap : 0;
@@ -518,11 +597,22 @@ int32_t cake_bidirectional_prefill(cake_ctx* c, const int32_t* token_ids, int32_
 
     HipBackend be(c, store, kv, tb.data(), tc.data());
     const uint64_t t_entry = mono_ns();
-    if (mode != CAKE_LOAD_ONLY) {
+    if (computes) {
         HIP_TRY(c, hipMemcpyAsync(c->d_ids, token_ids, size_t(n_tokens) * 4, hipMemcpyHostToDevice, c->cs));
     }
     uint64_t race_ns = 0;
     rc = ex.run(be, &race_ns);
+    // chunks beyond the stored prefix: they attend to everything before them, so they start after the join
+    ex.chunk_log.resize(size_t(n), cake_chunk_log{CAKE_SRC_NONE, 0, 0, 0, 0, 0, 0});
+    for (int i = n_race; i < n && rc == CAKE_OK; ++i) {
+        c->status[i].store(CAKE_CHUNK_COMPUTING);
+        cake_chunk_log& cl = ex.chunk_log[i];
+        cl.start_ns = ex.now();
+        rc = be.compute_chunk(i, &cl.device_ns);
+        if (rc != CAKE_OK) break;
+        cl.source = CAKE_SRC_COMPUTE; cl.tok_begin = tb[i]; cl.tok_count = tc[i]; cl.end_ns = ex.now(); cl.work = flops[i];
+        c->status[i].store(CAKE_CHUNK_RESIDENT);
+    }
     const uint64_t ttft = mono_ns() - t_entry;
     c->step_after = -1;  // a scheduled bandwidth step applies to one run
 
@@ -531,11 +621,13 @@ int32_t cake_bidirectional_prefill(cake_ctx* c, const int32_t* token_ids, int32_
     res->load_failed_chunk = ex.load_failed_chunk;
     res->ttft_ns = ttft;
     res->meet_point = 0;
+    res->stored_chunks = n_race;
+    res->pad_ = 0;
     res->compute_busy_ns = res->compute_device_ns = res->compute_flops = res->load_busy_ns = res->load_bytes = 0;
     for (int i = 0; i < n; ++i) {
         const cake_chunk_log& cl = ex.chunk_log[i];
         if (cl.source == CAKE_SRC_COMPUTE) {
-            ++res->meet_point;
+            if (i < n_race) ++res->meet_point;
             res->compute_busy_ns += cl.end_ns - cl.start_ns;
             res->compute_device_ns += cl.device_ns;
             res->compute_flops += cl.work;
@@ -668,7 +760,11 @@ int32_t cake_adaptive_serve(cake_ctx* c, cake_request* reqs, int32_t n_reqs, int
     int nc = 0;
     if (P >= 0) {
         const cake_request& r = reqs[P];
-        if (!r.store || !r.store->base) return fail(c, CAKE_E_INVAL, "prefix request without a store");
+        {
+            int rcs = check_store(c, r.store, r.kv);
+            if (rcs != CAKE_OK) return rcs;
+            if (int64_t(r.store->n_pages) * r.kv->page_tokens < r.n_tokens) return fail(c, CAKE_E_INVAL, "adaptive mode needs the whole prompt stored");
+        }
         if (fetch_chunk <= 0 || fetch_chunk % r.kv->page_tokens) return fail(c, CAKE_E_INVAL, "fetch_chunk must be a multiple of page_tokens");
         if (r.store->format != CAKE_STORE_RAW && r.store->format != CAKE_STORE_INT8) return fail(c, CAKE_E_INVAL, "store: unknown format %d", r.store->format);
         if (r.store->page_tokens != r.kv->page_tokens ||

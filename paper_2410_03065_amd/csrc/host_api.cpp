@@ -52,6 +52,47 @@ uint64_t cake_range_flops(const cake_model_desc* model, int32_t tok_begin, int32
     return cake::range_flops(*model, tok_begin, tok_count);
 }
 
+// FNV-1a, 64 bit: h = (h xor byte) * prime for every byte
+static inline uint64_t fnv1a64_bytes(uint64_t h, const unsigned char* p, size_t n) {
+    for (size_t i = 0; i < n; ++i) h = (h ^ p[i]) * 0x100000001B3ull;
+    return h;
+}
+
+int32_t cake_prefix_keys(const int32_t* token_ids, int32_t n_tokens, int32_t chunk_tokens, uint64_t* keys_out,
+                         int32_t keys_cap) {
+    if (!token_ids || n_tokens < 0 || chunk_tokens <= 0 || (!keys_out && keys_cap > 0) || keys_cap < 0) return CAKE_E_INVAL;
+    const int32_t n = n_tokens / chunk_tokens;
+    uint64_t prev = 0xCBF29CE484222325ull;
+    for (int32_t i = 0; i < n && i < keys_cap; ++i) {
+        unsigned char kb[8];
+        for (int b = 0; b < 8; ++b) kb[b] = (unsigned char)(prev >> (8 * b));
+        uint64_t h = fnv1a64_bytes(0xCBF29CE484222325ull, kb, 8);
+        for (int32_t t = 0; t < chunk_tokens; ++t) {
+            const uint32_t id = (uint32_t)token_ids[size_t(i) * chunk_tokens + t];
+            unsigned char tb[4] = {(unsigned char)id, (unsigned char)(id >> 8), (unsigned char)(id >> 16), (unsigned char)(id >> 24)};
+            h = fnv1a64_bytes(h, tb, 4);
+        }
+        keys_out[i] = prev = h;
+    }
+    return n;
+}
+
+int32_t cake_prefix_lookup(const uint64_t* stored_sorted, int32_t n_stored, const uint64_t* keys, int32_t n_keys) {
+    if (n_stored < 0 || n_keys < 0 || (n_stored > 0 && !stored_sorted) || (n_keys > 0 && !keys)) return CAKE_E_INVAL;
+    for (int32_t i = 1; i < n_stored; ++i)
+        if (stored_sorted[i - 1] > stored_sorted[i]) return CAKE_E_INVAL;
+    int32_t hit = 0;
+    for (; hit < n_keys; ++hit) {
+        int32_t lo = 0, hi = n_stored;   // binary search for keys[hit]
+        while (lo < hi) {
+            const int32_t mid = lo + (hi - lo) / 2;
+            if (stored_sorted[mid] < keys[hit]) lo = mid + 1; else hi = mid;
+        }
+        if (lo == n_stored || stored_sorted[lo] != keys[hit]) break;
+    }
+    return hit;
+}
+
 uint64_t cake_store_image_bytes(const cake_model_desc* model, int32_t page_tokens, int32_t format) {
     if (!model || page_tokens <= 0 || (format != CAKE_STORE_RAW && format != CAKE_STORE_INT8)) return 0;
     return cake::store_image_bytes(*model, page_tokens, format);

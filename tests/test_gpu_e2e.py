@@ -225,22 +225,118 @@ def test_bandwidth_step_moves_the_meet_point():
     assert max(stars[len(stars) // 2:]) > min(stars[:3])
 
 
-def test_load_failure_is_recomputed():
-    """A store that lacks the last pages: the loader's first claim fails (CAKE_E_STORE_MISS inside the
+def _file_store(tmp_path, images, name="store.bin", keep_bytes=None):
+    """Page images written to a file; returns (fd, n_pages, stride)."""
+    import os
+    flat = np.ascontiguousarray(images).reshape(images.shape[0], -1)
+    path = os.path.join(str(tmp_path), name)
+    flat.tofile(path)
+    if keep_bytes is not None:
+        os.truncate(path, keep_bytes)
+    return os.open(path, os.O_RDONLY), flat.shape[0], flat.shape[1] * flat.itemsize
+
+
+def test_load_failure_is_recomputed(tmp_path):
+    """A store file that has lost its tail: the loader's first claim fails (CAKE_E_STORE_MISS inside the
     worker), the chunk returns to the range, the loader retires and compute finishes everything."""
+    import os
     shape, T, C, pt = BF_NARROW_GQA4, 4096, 1024, 256
     w, toks, eng = _setup(shape, T, C, pt, seed=9)
     ref = otf.prefill_chunked(w, shape, toks, C, kv_dtype="bf16")
     images = ostore.pack_store(ref, pt, "bf16")
     want = ostore.decode_words(images, "bf16")
-    eng.set_store(images[:12])                       # pages 12..15 (= chunk 3) are missing
+    stride = images[0].size * 2
+    fd, n_pages, stride = _file_store(tmp_path, images, keep_bytes=12 * stride + 1000)   # pages 12..15 (= chunk 3) are cut off
+    eng.set_file_store(fd, n_pages, stride)
     res = eng.bidirectional_prefill(toks, C, 4.0, mode="greedy")    # unplanned race: the loader claims chunk 3 at once
-    assert res.load_failed_chunk == 3 and res.meet_point == 4
+    assert res.load_failed_chunk == 3 and res.meet_point == 4 and res.stored_chunks == 4
     assert _errs(eng.pool_images(T), want).max() < TOL["bf16"]
     import paper_2410_03065_amd as cake
     with pytest.raises(cake.CakeError) as ei:        # load-only cannot recover
         eng.bidirectional_prefill(toks, C, 4.0, mode="load_only")
     assert ei.value.code == cake.E_STORE_MISS
+    os.close(fd)
+
+
+def test_file_backed_store_two_hops(tmp_path):
+    """The second hop: page images read from a file through two pinned staging buffers.  Same bytes in
+    the pages as from a pinned store, raw and 8-bit; the throttle still holds."""
+    import os
+    import paper_2410_03065_amd as cake
+    shape, T, C, pt = BF_NARROW_GQA4, 4096, 1024, 256
+    w, toks, eng = _setup(shape, T, C, pt, seed=11, scramble=True)
+    ref = otf.prefill_chunked(w, shape, toks, C, kv_dtype="bf16")
+    raw = ostore.pack_store(ref, pt, "bf16")
+    img8 = ostore.pack_store_int8(ref, pt)
+    deq = ostore.pack_store(ostore.unpack_store_int8(img8, T, shape.n_kv, shape.head_dim, pt, "bf16"), pt, "bf16")
+    eng.set_tuning(piece_bytes=1 << 18)                              # several pieces per slab: both buffers cycle
+    for images, fmt, want_raw in ((raw, cake.STORE_RAW, raw), (img8, cake.STORE_INT8, deq)):
+        fd, n_pages, stride = _file_store(tmp_path, images, name="s%d.bin" % fmt)
+        eng.set_file_store(fd, n_pages, stride, fmt)
+        eng.clear_pool()
+        res = eng.bidirectional_prefill(toks, C, 2.0, mode="load_only")
+        assert res.meet_point == 0 and res.load_bytes == images.size * images.itemsize
+        assert res.achieved_gbps <= 2.0 * 1.001
+        np.testing.assert_array_equal(eng.pool_raw(T).view(np.uint16), want_raw)
+        eng.clear_pool()
+        res = eng.bidirectional_prefill(toks, C, 2.0, mode="forced", forced_m=2)
+        np.testing.assert_array_equal(eng.pool_raw(T)[2 * (C // pt):].view(np.uint16), want_raw[2 * (C // pt):])
+        assert _errs(eng.pool_images(T), ostore.decode_words(raw, "bf16")).max() < TOL["bf16"]
+        os.close(fd)
+    # a file store at an offset inside a larger file
+    path = os.path.join(str(tmp_path), "off.bin")
+    with open(path, "wb") as f:
+        f.write(b"\x55" * 4096)
+        f.write(np.ascontiguousarray(raw).tobytes())
+    fd = os.open(path, os.O_RDONLY)
+    eng.set_file_store(fd, raw.shape[0], raw[0].size * 2, cake.STORE_RAW, file_offset=4096)
+    eng.clear_pool()
+    eng.bidirectional_prefill(toks, C, 8.0, mode="load_only")
+    np.testing.assert_array_equal(eng.pool_raw(T).view(np.uint16), raw)
+    os.close(fd)
+
+
+def test_stored_prefix_shorter_than_the_prompt():
+    """App. A step 2: the prefix keys of the prompt's chunks are looked up in the store's index; the
+    store holds the first chunks only (an earlier, shorter prompt), so the race covers those and the
+    rest of the prompt is computed after the two sides have met."""
+    import paper_2410_03065_amd as cake
+    from oracle import prefix as opx
+    shape, T, C, pt = BF_NARROW_GQA4, 4096 + 300, 1024, 256
+    w, toks, eng = _setup(shape, T, C, pt, seed=13)
+    earlier = toks[:3 * C + 17]                                      # the conversation so far: 3 full chunks were stored
+    index = sorted(cake.prefix_keys(earlier, C) + [123456789])
+    keys = cake.prefix_keys(toks, C)
+    assert keys == opx.prefix_keys(toks, C) and len(keys) == 4
+    hit = cake.prefix_lookup(index, keys)
+    assert hit == opx.longest_stored_prefix(keys, index) == 3
+    ref = otf.prefill_chunked(w, shape, toks, C, kv_dtype="bf16")
+    images = ostore.pack_store(ref, pt, "bf16")
+    want = ostore.decode_words(images, "bf16")
+    eng.set_store(images[:hit * (C // pt)])                          # the store ends with the stored prefix
+    ppc = C // pt
+    for mode, kw in (("forced", dict(forced_m=1)), ("load_only", {}), ("bidir", {})):
+        eng.clear_pool()
+        res = eng.bidirectional_prefill(toks, C, 4.0, mode=mode, **kw)
+        assert res.n_chunks == 5 and res.stored_chunks == 3 and res.load_failed_chunk == -1
+        m = res.meet_point
+        assert m == {"forced": 1, "load_only": 0}.get(mode, m) and 0 <= m <= 3
+        assert [c["source"] for c in res.chunks] == [0] * m + [1] * (3 - m) + [0, 0]
+        assert _errs(eng.pool_images(T), want).max() < TOL["bf16"]
+        np.testing.assert_array_equal(eng.pool_raw(T)[m * ppc:3 * ppc].view(np.uint16), images[m * ppc:3 * ppc])
+        # the chunks past the stored prefix start after everything before them is resident
+        last_raced = max(c["end_ns"] for c in res.chunks[:3])
+        assert res.chunks[3]["start_ns"] >= last_raced and res.chunks[4]["start_ns"] >= res.chunks[3]["end_ns"]
+        assert res.chunks[4]["tok_count"] == 300
+    with pytest.raises(cake.CakeError):                              # a forced split cannot reach past the stored prefix
+        eng.bidirectional_prefill(toks, C, 4.0, mode="forced", forced_m=4)
+    # nothing stored at all: everything is computed
+    eng.set_store(images[:0].reshape(0, *images.shape[1:]) if False else images[:1])
+    eng.store.n_pages = 0
+    eng.clear_pool()
+    res = eng.bidirectional_prefill(toks, C, 4.0, mode="bidir")
+    assert res.stored_chunks == 0 and res.meet_point == 0 and all(c["source"] == 0 for c in res.chunks)
+    assert _errs(eng.pool_images(T), want).max() < TOL["bf16"]
 
 
 def test_argument_errors_are_reported_not_run():

@@ -34,7 +34,7 @@ def test_struct_sizes_match_the_header_layout():
     assert ctypes.sizeof(cake.ModelDesc) == 40
     assert ctypes.sizeof(cake.Tuning) == 40
     assert ctypes.sizeof(cake.Kv) == 40
-    assert ctypes.sizeof(cake.KvStore) == 32 and ctypes.sizeof(cake.Traces) == 56
+    assert ctypes.sizeof(cake.KvStore) == 48 and ctypes.sizeof(cake.Traces) == 56
 
 
 def test_planner_equals_brute_force_bit_exactly():
@@ -181,3 +181,22 @@ def test_threaded_executor_under_thread_sanitizer(tmp_path):
     env = dict(os.environ, TSAN_OPTIONS="halt_on_error=1")
     p = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=300)
     assert p.returncode == 0 and "ok" in p.stdout, p.stdout + p.stderr
+
+
+def test_prefix_keys_and_lookup_match_the_oracle():
+    from oracle import prefix as opx
+    rng = np.random.default_rng(1)
+    for n, chunk in ((0, 16), (15, 16), (16, 16), (1000, 128), (4096, 1024), (777, 1)):
+        toks = rng.integers(0, 2 ** 31 - 1, n).astype(np.int32)
+        keys = cake.prefix_keys(toks, chunk)
+        assert keys == opx.prefix_keys(toks, chunk)
+        for have in (0, len(keys) // 2, len(keys)):
+            stored = sorted(keys[:have] + [int(k) for k in rng.integers(0, 2 ** 63, 5)])
+            assert cake.prefix_lookup(stored, keys) == opx.longest_stored_prefix(keys, stored)
+        if len(keys) > 2:                                    # a gap ends the prefix
+            stored = sorted(keys[:1] + keys[2:])
+            assert cake.prefix_lookup(stored, keys) == 1
+    with pytest.raises(cake.CakeError):
+        cake.prefix_lookup([3, 2, 1], [1])                   # index not ascending
+    with pytest.raises(cake.CakeError):
+        cake.prefix_keys(np.zeros(4, dtype=np.int32), 0)
