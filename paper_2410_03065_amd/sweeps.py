@@ -3,6 +3,7 @@
 
     python -m paper_2410_03065_amd.sweeps --grid          # Sec. 5.2 / Table 3 layout
     python -m paper_2410_03065_amd.sweeps --fluctuation   # Sec. 5.6 / Fig. 5 layout
+    python -m paper_2410_03065_amd.sweeps --mix           # Sec. 5.7 layout: prefix request + arriving requests
 
 Grid: one prefix-cached prompt (default: Llama3-8B shape, 32768 random tokens) is produced by the
 adaptive engine while other users hold 0 / 12.5 / 50 / 87.5 % of every step's token budget, at the
@@ -25,6 +26,10 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--grid", action="store_true")
     ap.add_argument("--fluctuation", action="store_true")
+    ap.add_argument("--mix", action="store_true", help="one prefix-cached request among Poisson arrivals of 4K-token requests, "
+                    "bandwidth stepping 25 -> 2 GB/s when the loader has completed its 8th chunk")
+    ap.add_argument("--rate", type=float, default=2.0, help="arrivals per second of the other requests (--mix)")
+    ap.add_argument("--other-tokens", type=int, default=4096)
     ap.add_argument("--shape", default="llama3-8b-shape")
     ap.add_argument("--tokens", type=int, default=32768)
     ap.add_argument("--budget", type=int, default=1024, help="token budget of an engine step")
@@ -72,6 +77,39 @@ def main():
                 cells.append("%.3f (%.2f \\\\ %.2f) m=%d" % (t, load_only[gb] / t, t_c / t, per_req[0]["tokens_computed"]))
             print("| %.1f %% | %.3f | %s |" % (share * 100, t_c, " | ".join(cells)))
         print("\nload-only s: " + ", ".join("%g Gbps %.3f" % (g, load_only[g]) for g in args.gbit))
+    if args.mix:
+        # arrivals drawn from t = -2 s so the GPU is already shared when the prefix request comes in (t = 0 here = 2 s)
+        rng = np.random.default_rng(2)
+        t, arrivals = 0.0, []
+        while True:
+            t += rng.exponential(1.0 / args.rate)
+            if t > 4.0:
+                break
+            arrivals.append(t)
+        C = B
+        others = []
+        for j, ta in enumerate(arrivals):
+            kv, pool = eng.new_kv(args.other_tokens)
+            others.append(dict(tokens=si.make_tokens(args.other_tokens, shape.vocab, seed=100 + j), arrival_ns=int(ta * 1e9),
+                               prefix=False, kv=kv, pool=pool))
+        mix = others + [dict(tokens=toks, arrival_ns=int(2.0e9), prefix=True)]
+        for label, step_after in (("constant 4 GB/s", None), ("25 GB/s, then 2 GB/s after the loader's 8th chunk", 8)):
+            gb = 4.0 if step_after is None else 25.0
+            if step_after is not None:
+                eng.schedule_bandwidth_step(step_after, 2.0)
+            res, per_req, steps = eng.adaptive_serve(mix, B, C, gb)
+            print("\nmix, %s: %d requests of %d tokens at %.1f /s (Poisson, seed 2) + the %d-token prefix request at t = 2 s"
+                  % (label, len(others), args.other_tokens, args.rate, T))
+            print("prefix request: TTFT %.3f s, %d tokens computed, %d loaded (meet point chunk %d of %d), %d engine steps"
+                  % (per_req[-1]["ttft_ns"] / 1e9, per_req[-1]["tokens_computed"], per_req[-1]["tokens_loaded"], res.meet_point,
+                     res.n_chunks, len(steps)))
+            print("other requests: TTFT ms " + ", ".join("%.0f" % (p["ttft_ns"] / 1e6) for p in per_req[:-1]))
+            seen, line = -1, []
+            for d in res.decisions:
+                if d["m_star"] != seen:
+                    seen = d["m_star"]
+                    line.append("%d@%.0fms" % (seen, d["now_ns"] / 1e6 - 2000.0))
+            print("planned meet point over time (chunk @ ms after the prefix request arrived): " + " ".join(line))
     if args.fluctuation:
         rng = np.random.default_rng(3)
         other = (B - rng.integers(0, B // 2 // 64 + 1, 64) * 64).astype(np.int32)      # the request gets 0 .. B/2 tokens a step
