@@ -400,6 +400,12 @@ attention_mfma8_kernel(const bf16_t* __restrict__ q, bf16_t* __restrict__ out, i
         const bf16_t* qp = q + (size_t(h) * rows + my_row) * AHD + 8 * lhalf;
 #pragma unroll
         for (int ks = 0; ks < AHD / 16; ++ks) qreg[ks] = *(const bf16x8*)(qp + 16 * ks);
+        // softmax scale and log2(e) go into Q once, so a score leaves the MFMA in the exponent's units
+        const float sl2q = 0.08838834764831845f * 1.4426950408889634f;
+#pragma unroll
+        for (int ks = 0; ks < AHD / 16; ++ks)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) qreg[ks][e] = bf16_t(float(qreg[ks][e]) * sl2q);
     }
     // lane offsets of this wave's K / V^T wave-loads of a tile: load i covers 1 KB = key rows
     // 4j .. 4j+3 (V^T: head-dim rows 8j .. 8j+7) with j = wave + QW*i.  The swizzle term of the K
@@ -468,10 +474,14 @@ attention_mfma8_kernel(const bf16_t* __restrict__ q, bf16_t* __restrict__ out, i
     for (int t = 0; t < 4; ++t)
 #pragma unroll
         for (int v = 0; v < 16; ++v) o[t][v] = 0.f;
-    float m_run = A8_NEG, l_part = 0.f;
-    const float sl2 = 0.08838834764831845f * 1.4426950408889634f;
+    // The running reference m_run of a query (log2 units) is SUBTRACTED INSIDE THE MFMA: the score
+    // accumulators start from negm = -m_run instead of zero, so a finished score is already
+    // s - m_run and the exponential needs no multiply-add of its own.  When the reference moves
+    // (rarely, see RESCALE_LOG2) the scores formed against the old one are shifted by hand.
+    float m_run = 0.f, l_part = 0.f;
     const f32x16 zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-    float mx_cur = A8_NEG, corr_cur = 0.f;
+    f32x16 negm = zero16;
+    float corr_cur = 1.f, delta_cur = 0.f;
     bool moved_cur = false;
     constexpr float RESCALE_LOG2 = 6.0f;
     auto mask_tile = [&](f32x16* s, int tile) {
@@ -489,19 +499,19 @@ attention_mfma8_kernel(const bf16_t* __restrict__ q, bf16_t* __restrict__ out, i
         for (int i = 0; i < 8; ++i) acc = fmaxf(acc, s[part >> 1][8 * (part & 1) + i]);
         return acc;
     };
+    // raw: this lane's largest score of the next tile, already relative to m_run
     auto finish_max = [&](float raw) {
-        float mx = raw * sl2;
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        moved_cur = mx > m_run + RESCALE_LOG2;
+        raw = fmaxf(raw, __shfl_xor(raw, 32, 64));
+        moved_cur = raw > RESCALE_LOG2;
         if (__builtin_amdgcn_ballot_w64(moved_cur) != 0) {
-            mx = fmaxf(mx, m_run);
-            corr_cur = __builtin_amdgcn_exp2f(m_run - mx);
-            m_run = mx;
+            delta_cur = fmaxf(raw, 0.f);            // the reference only ever rises; -inf (all masked) leaves it
+            corr_cur = __builtin_amdgcn_exp2f(-delta_cur);
+            m_run += delta_cur;
             moved_cur = true;
         } else {
+            delta_cur = 0.f;
             corr_cur = 1.0f;
         }
-        mx_cur = m_run;
     };
 
     // iteration i: this group's tile 2i+grp is in K slot i&1 (scores already formed) and V slot i&1
@@ -510,7 +520,6 @@ attention_mfma8_kernel(const bf16_t* __restrict__ q, bf16_t* __restrict__ out, i
         __builtin_amdgcn_s_barrier();
         if (i + 1 < n_pairs) issue_v(i + 1);
         if (i + 2 < n_pairs) issue_k(i + 2);
-        const float mx = mx_cur;
         const unsigned char* stk = lds + ((i + 1) & 1) * A8_RING;   // past the last pair: stale, result unused
         const unsigned char* stv = lds + (i & 1) * A8_RING;
         bf16x8 opa[4], opb[4], p[4];
@@ -527,13 +536,13 @@ attention_mfma8_kernel(const bf16_t* __restrict__ q, bf16_t* __restrict__ out, i
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int ks = 2 * grpk + (e >> 1), t = e & 1;
-                s_nxt[t] = mfma32(src[e], qreg[ks], ks == 0 ? zero16 : s_nxt[t]);
+                s_nxt[t] = mfma32(src[e], qreg[ks], ks == 0 ? negm : s_nxt[t]);
             }
         };
         auto expo = [&](int grpe) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                float x = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[grpe >> 1][8 * (grpe & 1) + e], sl2, -mx));
+                float x = __builtin_amdgcn_exp2f(s_cur[grpe >> 1][8 * (grpe & 1) + e]);
                 l_part += x;
                 p[grpe][e] = bf16_t(x);
             }
@@ -582,6 +591,12 @@ attention_mfma8_kernel(const bf16_t* __restrict__ q, bf16_t* __restrict__ out, i
             for (int t = 0; t < 4; ++t)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) o[t][v] *= corr_cur;
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) s_nxt[t][v] -= delta_cur;   // formed against the old reference
+#pragma unroll
+            for (int v = 0; v < 16; ++v) negm[v] = -m_run;
         }
     };
 
@@ -608,10 +623,19 @@ attention_mfma8_kernel(const bf16_t* __restrict__ q, bf16_t* __restrict__ out, i
     }
     if (grp >= first_masked) mask_tile(s_a, grp);
     {
+        // the first tile fixes the reference exactly; a row that sees none of its keys (possible for
+        // the second wave half only) keeps reference 0 and contributes nothing
         float raw = s_a[0][0];
 #pragma unroll
         for (int part = 0; part < 4; ++part) raw = part_max(s_a, part, raw);
-        finish_max(raw);
+        raw = fmaxf(raw, __shfl_xor(raw, 32, 64));
+        m_run = raw > -INFINITY ? raw : 0.f;
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) s_a[t][v] -= m_run;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) negm[v] = -m_run;
     }
     for (int i = 0; i < n_pairs; i += 2) {
         step(i, s_a, s_b);
@@ -631,7 +655,9 @@ attention_mfma8_kernel(const bf16_t* __restrict__ q, bf16_t* __restrict__ out, i
     }
     __syncthreads();
     if (grp == 0) {
-        const float m_b = park[65 * 64], l_b = park[64 * 64];
+        const float l_b = park[64 * 64];
+        const float l_b_row = l_b + park[64 * 64 + ((lane ^ 32) - lane)];   // both half-waves of the row
+        const float m_b = l_b_row > 0.f ? park[65 * 64] : -1.0e30f;         // a half that saw no key has no reference
         const float m = fmaxf(m_run, m_b);
         const float ca = __builtin_amdgcn_exp2f(m_run - m), cb = __builtin_amdgcn_exp2f(m_b - m);
         float l_mine = l_part * ca + l_b * cb;
