@@ -410,7 +410,10 @@ int32_t cake_simulate_race(int32_t n_chunks, const uint64_t* chunk_flops,
  * HIP events on the compute stream.  cake_profile_read drains the stream, adds the elapsed
  * times of all pairs recorded since the last read into `out[CAKE_K_COUNT]` (overwritten) and
  * forgets them.  flops / bytes are the algorithmic work of the launches (bytes: operands read
- * once + results written once). */
+ * once + results written once).  cake_profile_enable: on = 0 stops, on = 1 brackets every class,
+ * on = 2 * mask brackets only the classes whose bit (1 << class) is set in mask -- an event pair
+ * costs a few microseconds of stream time, so timing one class perturbs a run about a tenth as
+ * much as timing all of them (measured: 10 % against 1 % on a 1024-token chunk). */
 typedef enum {
     CAKE_K_EMBED = 0, CAKE_K_RMSNORM = 1, CAKE_K_GEMM_QKV = 2, CAKE_K_ROPE_KV = 3, CAKE_K_ATTENTION = 4,
     CAKE_K_GEMM_O = 5, CAKE_K_GEMM_GATEUP = 6, CAKE_K_GEMM_DOWN = 7,

@@ -594,8 +594,12 @@ class Engine:
         self._check(self.lib.cake_schedule_bandwidth_step(self.ctx, after_loaded_chunks, float(gbps)),
                     "cake_schedule_bandwidth_step")
 
-    def profile_enable(self, on=True):
-        self._check(self.lib.cake_profile_enable(self.ctx, 1 if on else 0), "cake_profile_enable")
+    def profile_enable(self, on=True, classes=None):
+        """classes: names from KERNEL_CLASSES to bracket (default: all)."""
+        arg = 1 if on else 0
+        if on and classes:
+            arg = 2 * sum(1 << KERNEL_CLASSES.index(n) for n in classes)
+        self._check(self.lib.cake_profile_enable(self.ctx, arg), "cake_profile_enable")
 
     def profile_read(self):
         """{class name: dict(launches, total_ns, flops, bytes)} since the last read."""

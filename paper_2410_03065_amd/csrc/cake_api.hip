@@ -67,7 +67,8 @@ struct cake_ctx {
     // progress of the paced load in flight (written by the load thread, read by planners)
     std::atomic<uint64_t> load_start_ns{0}, load_bytes_done{0};
     // per-kernel-class timing (compute thread only)
-    bool prof_on = false;
+    bool prof_on = false, prof_open = false;
+    uint32_t prof_mask = 0xffffffffu;   // kernel classes that are bracketed while profiling is on
     struct ProfRec { int cls; uint64_t flops, bytes; };
     std::vector<hipEvent_t> prof_events;  // pairs: [2i] before, [2i+1] after
     std::vector<ProfRec> prof_recs;
@@ -145,7 +146,8 @@ static hipError_t attention(cake_ctx* c, const void* q, void* out, int tok_begin
 }
 
 static hipError_t prof_before(cake_ctx* c, int cls, uint64_t flops, uint64_t bytes) {
-    if (!c->prof_on) return hipSuccess;
+    c->prof_open = c->prof_on && ((c->prof_mask >> cls) & 1u);
+    if (!c->prof_open) return hipSuccess;
     size_t i = c->prof_recs.size();
     while (c->prof_events.size() < 2 * (i + 1)) {
         hipEvent_t e;
@@ -157,7 +159,7 @@ static hipError_t prof_before(cake_ctx* c, int cls, uint64_t flops, uint64_t byt
     return hipEventRecord(c->prof_events[2 * i], c->cs);
 }
 static hipError_t prof_after(cake_ctx* c) {
-    if (!c->prof_on) return hipSuccess;
+    if (!c->prof_open) return hipSuccess;
     return hipEventRecord(c->prof_events[2 * c->prof_recs.size() - 1], c->cs);
 }
 #define KLAUNCH(c, cls, fl, by, expr)                       \
@@ -999,6 +1001,7 @@ int32_t cake_profile_enable(cake_ctx* c, int32_t on) {
     if (!c) return CAKE_E_INVAL;
     HIP_TRY(c, hipStreamSynchronize(c->cs));
     c->prof_on = on != 0;
+    c->prof_mask = on > 1 ? uint32_t(on) >> 1 : 0xffffffffu;
     c->prof_recs.clear();
     return CAKE_OK;
 }

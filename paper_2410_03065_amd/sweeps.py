@@ -3,7 +3,8 @@
 
     python -m paper_2410_03065_amd.sweeps --grid          # Sec. 5.2 / Table 3 layout
     python -m paper_2410_03065_amd.sweeps --fluctuation   # Sec. 5.6 / Fig. 5 layout
-    python -m paper_2410_03065_amd.sweeps --mix           # Sec. 5.7 layout: prefix request + arriving requests
+    python -m paper_2410_03065_amd.sweeps --mix           # prefix request + Poisson arrivals, bandwidth step
+    python -m paper_2410_03065_amd.sweeps --burst         # Sec. 5.7 layout: prefix request + a burst of short requests
 
 Grid: one prefix-cached prompt (default: Llama3-8B shape, 32768 random tokens) is produced by the
 adaptive engine while other users hold 0 / 12.5 / 50 / 87.5 % of every step's token budget, at the
@@ -28,6 +29,8 @@ def main():
     ap.add_argument("--fluctuation", action="store_true")
     ap.add_argument("--mix", action="store_true", help="one prefix-cached request among Poisson arrivals of 4K-token requests, "
                     "bandwidth stepping 25 -> 2 GB/s when the loader has completed its 8th chunk")
+    ap.add_argument("--burst", action="store_true", help="prefix request, then 22 requests of 32-448 tokens: finish time when the "
+                    "prefix request runs to completion first against the adaptive mode")
     ap.add_argument("--rate", type=float, default=2.0, help="arrivals per second of the other requests (--mix)")
     ap.add_argument("--other-tokens", type=int, default=4096)
     ap.add_argument("--shape", default="llama3-8b-shape")
@@ -110,6 +113,35 @@ def main():
                     seen = d["m_star"]
                     line.append("%d@%.0fms" % (seen, d["now_ns"] / 1e6 - 2000.0))
             print("planned meet point over time (chunk @ ms after the prefix request arrived): " + " ".join(line))
+    if args.burst:
+        import time
+        rng = np.random.default_rng(4)
+        lens = np.clip(rng.gamma(2.0, 60.0, 22).astype(int) + 32, 32, 448)        # spiked towards short prompts
+        arr = np.sort(rng.uniform(0.02, 0.30, 22))                                  # all arrive while the prefix request is in flight
+        burst = []
+        for j, (n_tok, ta) in enumerate(zip(lens, arr)):
+            kv, pool = eng.new_kv(int(n_tok))
+            burst.append(dict(tokens=si.make_tokens(int(n_tok), shape.vocab, seed=200 + j), arrival_ns=int(ta * 1e9), prefix=False,
+                              kv=kv, pool=pool))
+        pre = dict(tokens=toks, arrival_ns=0, prefix=True)
+        eng.adaptive_serve(burst + [pre], B, U, 4.0)                                # warm-up of the small shapes
+        # (a) the prefix request first, to completion; the burst waits for it
+        t0 = time.perf_counter()
+        r_first, _, _ = eng.adaptive_serve([pre], B, U, 4.0)
+        waited = [dict(b, arrival_ns=0) for b in burst]
+        eng.adaptive_serve(waited, B, U, 4.0)
+        t_seq = time.perf_counter() - t0
+        # (b) adaptive mode: the burst is served as it arrives, the prefix request takes what is left of each step
+        t0 = time.perf_counter()
+        r_ad, per_req, steps = eng.adaptive_serve(burst + [pre], B, U, 4.0)
+        t_ad = time.perf_counter() - t0
+        print("\nburst: %d-token prefix request at t = 0, then 22 requests of %d..%d tokens (total %d) arriving within 0.3 s, 4 GB/s"
+              % (T, lens.min(), lens.max(), lens.sum()))
+        print("prefix request first, burst after it: all done after %.3f s (prefix TTFT %.3f s; a burst request waits up to %.3f s)"
+              % (t_seq, r_first.ttft_ns / 1e9, r_first.ttft_ns / 1e9 - arr.min()))
+        print("adaptive mode: all done after %.3f s (prefix TTFT %.3f s, %d tokens computed; burst TTFT ms: median %.1f, max %.1f)"
+              % (t_ad, per_req[-1]["ttft_ns"] / 1e9, per_req[-1]["tokens_computed"],
+                 float(np.median([p["ttft_ns"] for p in per_req[:-1]])) / 1e6, max(p["ttft_ns"] for p in per_req[:-1]) / 1e6))
     if args.fluctuation:
         rng = np.random.default_rng(3)
         other = (B - rng.integers(0, B // 2 // 64 + 1, 64) * 64).astype(np.int32)      # the request gets 0 .. B/2 tokens a step
