@@ -39,7 +39,9 @@
  * The storage tier holds one image per logical page,
  *     image[layer][0|1][...as above...],   at base + logical_page * page_stride_bytes,
  * so loading a page is n_layers contiguous copies and the bytes land exactly
- * as stored.
+ * as stored.  A store may instead hold 8-bit images (cake_store_format), sit
+ * in a file rather than in pinned memory (cake_store_source), and cover only
+ * a prefix of the prompt (cake_kv_store.n_pages).
  */
 #ifndef CAKE_H
 #define CAKE_H
@@ -261,6 +263,9 @@ int32_t cake_plan_meet_point(const uint64_t* compute_ns, const uint64_t* load_ns
  * chunk is produced twice.  Returns when both have drained; ttft_ns covers entry to that
  * point.  A failed load returns its chunk to the range, retires the loader and is reported
  * in load_failed_chunk (the call still succeeds if compute can finish the range).
+ * If the store holds fewer pages than the prompt needs (the stored prefix found by
+ * cake_prefix_lookup, App. A step 2), the race covers the chunks wholly inside the stored
+ * prefix and the remaining chunks are computed afterwards; res->stored_chunks tells which.
  * Errors: CAKE_E_INVAL, CAKE_E_STORE_MISS (load-only mode and the store lacks a page),
  * CAKE_E_HIP, CAKE_E_CAPACITY (logs truncated; KV and scalars valid). */
 int32_t cake_bidirectional_prefill(cake_ctx* ctx, const int32_t* token_ids, int32_t n_tokens,
