@@ -201,6 +201,29 @@ def test_bf16_full_width_llama3_8b_two_layers():
     assert e.max() < TOL["bf16"], e
 
 
+@pytest.mark.parametrize("shape,T,C,pt", [
+    (si.LLAMA2_7B.with_(n_layers=2, vocab=4096), 1024, 512, 256),    # MHA, FFN 11008, chunk 512
+    (si.LLAMA2_70B.with_(n_layers=2, vocab=4096), 1024, 512, 256),   # d 8192, 64 query / 8 KV heads, FFN 28672
+])
+def test_bf16_full_width_two_layers_other_models(shape, T, C, pt):
+    """The other model widths of the paper's evaluation (Sec. 5.1), 2 layers, two chunks, bidirectional too."""
+    w, toks, eng = _setup(shape, T, C, pt, seed=9)
+    ref = otf.prefill_chunked(w, shape, toks, C, kv_dtype="bf16")
+    images = ostore.pack_store(ref, pt, "bf16")
+    want = ostore.decode_words(images, "bf16")
+    eng.bidirectional_prefill(toks, C, 4.0, mode="compute_only")
+    e = _errs(eng.pool_images(T), want)
+    assert e.max() < TOL["bf16"], e
+    eng.set_store(images)
+    eng.clear_pool()
+    res = eng.bidirectional_prefill(toks, C, 4.0, mode="forced", forced_m=1)
+    assert res.meet_point == 1
+    raw = eng.pool_raw(T)
+    ppc = C // pt
+    np.testing.assert_array_equal(raw[ppc:].view(np.uint16), images[ppc:])
+    assert _errs(eng.pool_images(T), want).max() < TOL["bf16"]
+
+
 def test_bandwidth_step_moves_the_meet_point():
     """Sec. 5.6: when the I/O rate drops mid-run the planned merge point shifts towards
     more computed chunks; the throttle follows the new rate."""
