@@ -237,6 +237,7 @@ def test_bandwidth_step_moves_the_meet_point():
     # pick a rate at which load-only takes about as long as compute-only, so the race is balanced
     res_c = eng.bidirectional_prefill(toks, C, 4.0, mode="compute_only")
     rate = kv_bytes / res_c.ttft_ns
+    eng.bidirectional_prefill(toks, C, rate, mode="bidir")        # first race: loader thread and staging set up
     res_a = eng.bidirectional_prefill(toks, C, rate, mode="bidir")
     eng.schedule_bandwidth_step(2, rate / 10)
     res_b = eng.bidirectional_prefill(toks, C, rate, mode="bidir")
@@ -735,9 +736,11 @@ def test_bidirectional_with_int8_store_moves_the_meet_point_left():
     eng.bidirectional_prefill(toks, C, 4.0, mode="compute_only")
     r_c = eng.bidirectional_prefill(toks, C, 4.0, mode="compute_only")
     rate = T * otf.kv_bytes_per_token(shape.n_layers, shape.n_kv, shape.head_dim, 2) / r_c.ttft_ns
+    eng.bidirectional_prefill(toks, C, rate, mode="bidir")        # first race: loader thread and staging set up
     eng.clear_pool()
     r16 = eng.bidirectional_prefill(toks, C, rate, mode="bidir")
     eng.set_store_int8(img8)
+    eng.bidirectional_prefill(toks, C, rate, mode="bidir")        # first 8-bit load: its staging buffer
     eng.clear_pool()
     r8 = eng.bidirectional_prefill(toks, C, rate, mode="bidir")
     m, ppc = r8.meet_point, C // pt
