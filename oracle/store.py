@@ -151,3 +151,87 @@ def unpack_store_int8(images: np.ndarray, n_tokens: int, n_kv: int, hd: int,
                 dst[l, t0:t1] = np.transpose(x[:, :n, :], (1, 0, 2))
     cache.filled = n_tokens
     return cache
+
+
+# --------------------------------------------------------------------------- #
+# 4-bit stored KV (Sec. 5.5 / Table 6 pair the method with a second, stronger compression level;
+# the paper takes a published 3-bit scheme that needs calibration data, so it is not reproduced)
+# --------------------------------------------------------------------------- #
+# Reading taken here: the 8-bit scheme above with 15 levels instead of 255:
+#     scale = max|x| / 7             code = round_half_even(x / scale), clipped to [-7, 7]
+# again in float32, one scale per (token, KV head) row.  Two codes share a byte: element 2i in the
+# low nibble, element 2i+1 in the high nibble, each as a 4-bit two's complement number.  An image
+# of one page, per layer and per K|V:
+#     uint8  packed codes [kv_head][token_in_page][hd / 2]
+#     float32 scales      [kv_head][token_in_page]
+# i.e. n_kv * page_tokens * (hd / 2 + 4) bytes.
+
+def quantize_rows_int4(x: np.ndarray):
+    """x [..., hd] -> (int8 codes in [-7, 7], float32 scales [...])."""
+    x32 = np.ascontiguousarray(x, dtype=np.float32)
+    scale = (np.abs(x32).max(axis=-1) / np.float32(7.0)).astype(np.float32)
+    safe = np.where(scale > 0, scale, np.float32(1.0)).astype(np.float32)
+    q = np.rint((x32 / safe[..., None]).astype(np.float32))
+    q = np.clip(q, -7, 7).astype(np.int8)
+    q[scale == 0] = 0
+    return q, scale
+
+
+def pack_nibbles(codes: np.ndarray) -> np.ndarray:
+    """int8 codes [..., hd] in [-8, 7] -> uint8 [..., hd / 2]; even element low, odd element high."""
+    u = codes.astype(np.int16) & 0xF
+    return (u[..., 0::2] | (u[..., 1::2] << 4)).astype(np.uint8)
+
+
+def unpack_nibbles(packed: np.ndarray) -> np.ndarray:
+    """Inverse of pack_nibbles: uint8 [..., n] -> int8 [..., 2 n] (sign-extended nibbles)."""
+    lo = (packed & 0xF).astype(np.int16)
+    hi = (packed >> 4).astype(np.int16)
+    lo = np.where(lo >= 8, lo - 16, lo)
+    hi = np.where(hi >= 8, hi - 16, hi)
+    out = np.empty(packed.shape[:-1] + (packed.shape[-1] * 2,), dtype=np.int8)
+    out[..., 0::2] = lo
+    out[..., 1::2] = hi
+    return out
+
+
+def int4_image_bytes(n_layers: int, n_kv: int, hd: int, page_tokens: int) -> int:
+    return n_layers * 2 * n_kv * page_tokens * (hd // 2 + 4)
+
+
+def pack_store_int4(cache: KVCache, page_tokens: int) -> np.ndarray:
+    """[n_logical_pages, L, 2, n_kv * page_tokens * (hd / 2 + 4)] bytes (uint8)."""
+    L, T, n_kv, hd = cache.k.shape
+    n_pages = (T + page_tokens - 1) // page_tokens
+    nc = n_kv * page_tokens * (hd // 2)
+    out = np.zeros((n_pages, L, 2, n_kv * page_tokens * (hd // 2 + 4)), dtype=np.uint8)
+    for p in range(n_pages):
+        t0, t1 = p * page_tokens, min((p + 1) * page_tokens, T)
+        n = t1 - t0
+        for l in range(L):
+            for which, src in ((0, cache.k), (1, cache.v)):
+                blk = np.zeros((n_kv, page_tokens, hd), dtype=np.float64)
+                blk[:, :n, :] = np.transpose(src[l, t0:t1], (1, 0, 2))        # [kv, tok, hd]
+                q, sc = quantize_rows_int4(blk)
+                out[p, l, which, :nc] = pack_nibbles(q).reshape(-1)
+                out[p, l, which, nc:] = sc.reshape(-1).view(np.uint8)
+    return out
+
+
+def unpack_store_int4(images: np.ndarray, n_tokens: int, n_kv: int, hd: int,
+                      page_tokens: int, dtype: str) -> KVCache:
+    """The cache a loader must produce from 4-bit images: dequantised and storage-rounded."""
+    n_pages, L = images.shape[0], images.shape[1]
+    nc = n_kv * page_tokens * (hd // 2)
+    cache = KVCache(L, n_tokens, n_kv, hd)
+    for p in range(n_pages):
+        t0, t1 = p * page_tokens, min((p + 1) * page_tokens, n_tokens)
+        n = t1 - t0
+        for l in range(L):
+            for which, dst in ((0, cache.k), (1, cache.v)):
+                q = unpack_nibbles(images[p, l, which, :nc].reshape(n_kv, page_tokens, hd // 2))
+                sc = np.ascontiguousarray(images[p, l, which, nc:]).view(np.float32).reshape(n_kv, page_tokens)
+                x = dequantize_rows_int8(q, sc, dtype)      # code * scale, storage-rounded: same rule for both widths
+                dst[l, t0:t1] = np.transpose(x[:, :n, :], (1, 0, 2))
+    cache.filled = n_tokens
+    return cache

@@ -414,3 +414,53 @@ def test_int8_store_properties():
     q, sc = ostore.quantize_rows_int8(cache.k[0])
     q2, _ = ostore.quantize_rows_int8(q.astype(np.float32) * sc[..., None])
     np.testing.assert_array_equal(q, q2)
+
+
+def test_int4_rows_hand_worked():
+    from oracle import store as ostore
+    x = np.array([[7.0, -3.5, 1.0, 0.49, -0.51, 0.0, 2.5, -7.0],           # scale 1: ties to even, clipping at the ends
+                  [0.0] * 8,                                               # zero row: scale 0, codes 0
+                  [0.5, -0.25, 0.125, 0.0, 14.0, -14.0, 1.0, 3.0]])        # scale 2: 0.25 -> 0, -0.125 -> -0, 0.5 -> 0 (even), 1.5 -> 2
+    q, sc = ostore.quantize_rows_int4(x)
+    assert sc[0] == 1.0 and q[0].tolist() == [7, -4, 1, 0, -1, 0, 2, -7]          # -3.5 -> -4 (even), 2.5 -> 2 (even)
+    assert sc[1] == 0.0 and not q[1].any()
+    assert sc[2] == 2.0 and q[2].tolist() == [0, 0, 0, 0, 7, -7, 0, 2]
+    # two codes per byte: even element low nibble, odd element high nibble, two's complement
+    packed = ostore.pack_nibbles(q)
+    assert packed[0].tolist() == [0x07 | (0xC << 4), 0x01 | (0x0 << 4), 0xF | (0x0 << 4), 0x2 | (0x9 << 4)]
+    np.testing.assert_array_equal(ostore.unpack_nibbles(packed), q)
+    every = np.arange(-8, 8, dtype=np.int8).reshape(1, 16)
+    np.testing.assert_array_equal(ostore.unpack_nibbles(ostore.pack_nibbles(every)), every)
+    d = ostore.dequantize_rows_int8(q, sc, "f32")
+    assert d[0].tolist() == [7.0, -4.0, 1.0, 0.0, -1.0, 0.0, 2.0, -7.0] and d[2].tolist()[4:] == [14.0, -14.0, 0.0, 4.0]
+
+
+def test_int4_store_properties():
+    from oracle import store as ostore
+    rng = np.random.default_rng(4)
+    L, T, n_kv, hd, pt = 2, 150, 2, 64, 64
+    cache = otf.KVCache(L, T, n_kv, hd)
+    cache.k[:] = otf.round_storage(rng.standard_normal(cache.k.shape) * 3, "bf16")
+    cache.v[:] = otf.round_storage(rng.standard_normal(cache.v.shape), "bf16")
+    img = ostore.pack_store_int4(cache, pt)
+    assert img.shape == (3, L, 2, n_kv * pt * (hd // 2 + 4)) and img[0].size == ostore.int4_image_bytes(L, n_kv, hd, pt)
+    # 68 / 256 of the bf16 image and 68 / 132 of the 8-bit image at head_dim 128
+    assert ostore.int4_image_bytes(32, 8, 128, 256) * 132 == ostore.int8_image_bytes(32, 8, 128, 256) * 68
+    back = ostore.unpack_store_int4(img, T, n_kv, hd, pt, "bf16")
+    for a, b in ((cache.k, back.k), (cache.v, back.v)):
+        amax = np.abs(a).max(axis=-1, keepdims=True)
+        # half a quantisation step (1/14 of the row's maximum) plus the bf16 rounding of the result
+        assert np.all(np.abs(a - b) <= amax / 14 * (1 + 1e-6) + np.abs(b) * 2.0 ** -8)
+        hit = np.abs(a) == amax
+        assert np.all(np.abs(a[hit] - b[hit]) <= np.abs(a[hit]) * 2.0 ** -7)
+        # coarser than the 8-bit store on the same data, and not trivially exact
+        b8 = ostore.unpack_store_int8(ostore.pack_store_int8(cache, pt), T, n_kv, hd, pt, "bf16")
+        assert np.abs(a - b).max() > 4 * np.abs(a - (b8.k if a is cache.k else b8.v)).max()
+    codes = ostore.unpack_nibbles(img[..., :n_kv * pt * (hd // 2)])
+    assert codes.min() == -7 and codes.max() == 7
+    tail = codes[2].reshape(L, 2, n_kv, pt, hd)[:, :, :, T - 2 * pt:, :]
+    assert not tail.any()
+    # quantising what was dequantised (before storage rounding) reproduces the codes
+    q, sc = ostore.quantize_rows_int4(cache.k[0])
+    q2, _ = ostore.quantize_rows_int4(q.astype(np.float32) * sc[..., None])
+    np.testing.assert_array_equal(q, q2)
