@@ -179,6 +179,16 @@ def main():
                   "load_only_s": round(r8_l.ttft_ns / 1e9, 5), "store_bytes": int(r8_l.load_bytes),
                   "achieved_gbps_load_only": round(r8_l.achieved_gbps, 4)}
 
+    # and with the 4-bit store (two codes per byte)
+    eng.bidirectional_prefill(toks, C, args.gbps, mode="compute_only", log=False)
+    eng.write_store(T, cake.STORE_INT4)
+    eng.bidirectional_prefill(toks, C, args.gbps, mode="bidir", log=False)
+    r4 = [eng.bidirectional_prefill(toks, C, args.gbps, mode="bidir") for _ in range(2)]
+    r4_l = eng.bidirectional_prefill(toks, C, args.gbps, mode="load_only")
+    int4_store = {"ttft_s": round(float(np.mean([r.ttft_ns for r in r4])) / 1e9, 5), "meet_point": [r.meet_point for r in r4],
+                  "load_only_s": round(r4_l.ttft_ns / 1e9, 5), "store_bytes": int(r4_l.load_bytes),
+                  "achieved_gbps_load_only": round(r4_l.achieved_gbps, 4)}
+
     ttft = float(np.mean([r.ttft_ns for r in runs])) / 1e9
     comp_flops = sum(r.compute_flops for r in runs)
     comp_dev_ns = sum(r.compute_device_ns for r in runs)
@@ -242,6 +252,7 @@ def main():
         "first_token": dict(first_token, ttft_to_first_token_s=round(ttft + ft_wall, 5)),
         "fine_fetch_unit": fine,
         "int8_store": int8_store,
+        "int4_store": int4_store,
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:

@@ -120,8 +120,13 @@ typedef struct {
  *   int8 codes [kv_head][token][head_dim] then float32 scales [kv_head][token];
  *   value = code * scale, one scale per token and KV head (absmax / 127), V not transposed.
  *   n_layers*2*n_kv*page_tokens*(head_dim+4) bytes per page.  Loaded pages are dequantised on
- *   arrival (float32 product, rounded once to the KV element type). */
-typedef enum { CAKE_STORE_RAW = 0, CAKE_STORE_INT8 = 1 } cake_store_format;
+ *   arrival (float32 product, rounded once to the KV element type).
+ * CAKE_STORE_INT4 (the stronger compression level of Sec. 5.5 / Table 6; the paper's own 3-bit scheme
+ *   needs calibration data and is not reproduced): as CAKE_STORE_INT8 with 15 levels, absmax / 7,
+ *   codes in [-7, 7] as 4-bit two's complement, two per byte (element 2i low nibble, 2i+1 high
+ *   nibble): uint8 [kv_head][token][head_dim/2] then the float32 scales;
+ *   n_layers*2*n_kv*page_tokens*(head_dim/2+4) bytes per page. */
+typedef enum { CAKE_STORE_RAW = 0, CAKE_STORE_INT8 = 1, CAKE_STORE_INT4 = 2 } cake_store_format;
 
 /* Where a store's bytes are.  CAKE_STORE_PINNED: pinned host memory at `base` (one hop, DMA reads it
  * directly).  CAKE_STORE_FILE: a file open for reading (`fd`, page p at file_offset + p * stride):
@@ -369,8 +374,9 @@ int32_t cake_prefix_lookup(const uint64_t* stored_sorted, int32_t n_stored, cons
 /* Bytes of one page image in a store of `format`. */
 uint64_t cake_store_image_bytes(const cake_model_desc* model, int32_t page_tokens, int32_t format);
 /* Writes the pages that hold tokens [0, n_tokens) of `kv` into `dst` (pinned host, writable
- * despite the const base) in dst->format: CAKE_STORE_RAW copies, CAKE_STORE_INT8 quantises on the
- * GPU (scale = absmax / 127 per token and KV head, codes rounded half to even).  Blocking.
+ * despite the const base) in dst->format: CAKE_STORE_RAW copies, CAKE_STORE_INT8 / CAKE_STORE_INT4
+ * quantise on the GPU (scale = absmax / 127 resp. / 7 per token and KV head, codes rounded half to
+ * even).  Blocking.
  * Errors: CAKE_E_INVAL, CAKE_E_NOMEM (staging), CAKE_E_HIP. */
 int32_t cake_write_store(cake_ctx* ctx, const cake_kv* kv, int32_t n_tokens, const cake_kv_store* dst);
 

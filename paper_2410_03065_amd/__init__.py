@@ -33,7 +33,7 @@ EXPORTS = [
     "cake_op_attention", "cake_profile_enable", "cake_profile_read", "cake_adaptive_serve", "cake_first_token",
     "cake_op_decode_attention", "cake_set_traces", "cake_store_image_bytes", "cake_write_store", "cake_prefix_keys", "cake_prefix_lookup",
 ]
-STORE_RAW, STORE_INT8 = 0, 1
+STORE_RAW, STORE_INT8, STORE_INT4 = 0, 1, 2
 STORE_PINNED, STORE_FILE = 0, 1
 KERNEL_CLASSES = ["embed", "rmsnorm", "gemm_qkv", "rope_kv", "attention", "gemm_o", "gemm_gateup", "gemm_down",
                   "gemv", "decode_attention"]
@@ -388,13 +388,17 @@ class Engine:
         self.store_tensor = None
         self.store = KvStore(None, stride, self.page_tokens, n_pages, fmt, STORE_FILE, fd, 0, file_offset)
 
-    def set_store_int8(self, images: np.ndarray):
-        """images: [n_pages, L, 2, bytes] uint8 in the int8 store format (codes then scales per layer and K|V)."""
+    def set_store_int8(self, images: np.ndarray, fmt=STORE_INT8):
+        """images: [n_pages, L, 2, bytes] uint8 in a quantised store format (codes then scales per layer and K|V)."""
         torch = self.torch
         flat = np.ascontiguousarray(images).reshape(images.shape[0], -1)
         t = torch.empty(flat.shape, dtype=torch.uint8, pin_memory=True)
         t.numpy()[:] = flat
-        self._set_store_tensor(t, STORE_INT8)
+        self._set_store_tensor(t, fmt)
+
+    def set_store_int4(self, images: np.ndarray):
+        """As set_store_int8 for the 4-bit format (two codes per byte)."""
+        self.set_store_int8(images, STORE_INT4)
 
     def write_store(self, n_tokens, fmt=STORE_INT8):
         """The pool's KV of [0, n_tokens) written into a new pinned store of the given format (cake_write_store)."""

@@ -43,7 +43,7 @@ struct cake_ctx {
     float *t_h = nullptr, *t_q = nullptr, *t_qr = nullptr, *t_ao = nullptr, *t_act = nullptr, *t_logits = nullptr,
           *t_part = nullptr;
     int32_t* t_tok = nullptr;
-    void* q_stage = nullptr;   // device staging for int8 page images (allocated at the first use)
+    void* q_stage = nullptr;   // device staging for quantised page images (allocated at the first use)
     size_t q_stage_bytes = 0;
     // second hop of a file-backed store: two pinned buffers of one DMA piece each
     void* f_stage[2] = {nullptr, nullptr};
@@ -94,12 +94,15 @@ static int fail(cake_ctx* ctx, int code, const char* fmt, ...) {
     } while (0)
 
 static size_t esize(const cake_ctx* c) { return c->m.dtype == CAKE_F32 ? 4 : 2; }
+static bool store_format_known(int f) { return f == CAKE_STORE_RAW || f == CAKE_STORE_INT8 || f == CAKE_STORE_INT4; }
+// bits per stored code of a quantised format, 0 for the raw format
+static int store_code_bits(int f) { return f == CAKE_STORE_INT8 ? 8 : f == CAKE_STORE_INT4 ? 4 : 0; }
 
 static int check_store(cake_ctx* c, const cake_kv_store* st, const cake_kv* kv) {
     if (!st) return fail(c, CAKE_E_INVAL, "store: null");
     if (st->source == CAKE_STORE_PINNED ? !st->base : (st->source != CAKE_STORE_FILE || st->fd < 0))
         return fail(c, CAKE_E_INVAL, "store: no memory / file given (source %d)", st->source);
-    if (st->format != CAKE_STORE_RAW && st->format != CAKE_STORE_INT8) return fail(c, CAKE_E_INVAL, "store: unknown format %d", st->format);
+    if (!store_format_known(st->format)) return fail(c, CAKE_E_INVAL, "store: unknown format %d", st->format);
     if (st->n_pages < 0) return fail(c, CAKE_E_INVAL, "store: negative page count");
     if (st->page_tokens != kv->page_tokens) return fail(c, CAKE_E_INVAL, "store/page size mismatch");
     if (st->page_stride_bytes < cake::store_image_bytes(c->m, kv->page_tokens, st->format))
@@ -307,13 +310,14 @@ static int enqueue_load(cake_ctx* c, const cake_kv_store* st, int tok_begin, int
     const int pt = kv->page_tokens;
     if (tok_begin % pt) return fail(c, CAKE_E_INVAL, "load range must start on a page boundary");
     const int p0 = tok_begin / pt, p1 = (tok_begin + tok_count + pt - 1) / pt;
-    if (st->format != CAKE_STORE_RAW && st->format != CAKE_STORE_INT8) return fail(c, CAKE_E_INVAL, "store: unknown format %d", st->format);
+    if (!store_format_known(st->format)) return fail(c, CAKE_E_INVAL, "store: unknown format %d", st->format);
     const uint64_t layer_bytes = uint64_t(2) * m.n_kv_heads * pt * m.head_dim * esize(c);
     const uint64_t image_bytes = cake::store_image_bytes(m, pt, st->format);
     if (st->page_stride_bytes < image_bytes) return fail(c, CAKE_E_INVAL, "store: page stride smaller than a page image");
     if (p1 > st->n_pages) return fail(c, CAKE_E_STORE_MISS, "store holds %d pages, page %d requested", st->n_pages, p1 - 1);
     const uint64_t piece_max = c->tun.piece_bytes ? c->tun.piece_bytes : (4ull << 20);
-    if (st->format == CAKE_STORE_INT8) {
+    const int bits = store_code_bits(st->format);
+    if (bits) {
         int rc = ensure_stage(c, uint64_t(p1 - p0) * image_bytes);
         if (rc != CAKE_OK) return rc;
     }
@@ -356,13 +360,13 @@ static int enqueue_load(cake_ctx* c, const cake_kv_store* st, int tok_begin, int
     for (int p = p0; p < p1; ++p) {
         const uint64_t img = (from_file ? st->file_offset : uint64_t((uintptr_t)st->base)) + uint64_t(p) * st->page_stride_bytes;
         const int pp = kv->block_table_host[p];
-        if (st->format == CAKE_STORE_INT8) {
+        if (bits) {
             // the whole image lands in the staging buffer, then one kernel on the copy stream
             // dequantises it into the page of every layer; stream order keeps the two apart
             char* stage = (char*)c->q_stage + uint64_t(p - p0) * image_bytes;
             int rc = paced_copy(stage, img, image_bytes);
             if (rc != CAKE_OK) return rc;
-            HIP_TRY(c, launch_dequant_page(m.dtype, stage, make_view(c, kv, 0), pp, m.n_layers, c->ls));
+            HIP_TRY(c, launch_dequant_page(m.dtype, stage, make_view(c, kv, 0), pp, m.n_layers, bits, c->ls));
             continue;
         }
         for (int l = 0; l < m.n_layers; ++l) {
@@ -678,22 +682,23 @@ int32_t cake_write_store(cake_ctx* c, const cake_kv* kv, int32_t n_tokens, const
     if (n_tokens <= 0 || n_tokens > c->max_tokens) return fail(c, CAKE_E_INVAL, "n_tokens %d outside (0, %d]", n_tokens, c->max_tokens);
     int rc = check_kv(c, kv, n_tokens);
     if (rc != CAKE_OK) return rc;
-    if (dst->format != CAKE_STORE_RAW && dst->format != CAKE_STORE_INT8) return fail(c, CAKE_E_INVAL, "store: unknown format %d", dst->format);
+    if (!store_format_known(dst->format)) return fail(c, CAKE_E_INVAL, "store: unknown format %d", dst->format);
     const int pt = kv->page_tokens, n_pages = (n_tokens + pt - 1) / pt;
     const uint64_t image = cake::store_image_bytes(c->m, pt, dst->format);
     if (dst->page_tokens != pt || dst->page_stride_bytes < image || dst->n_pages < n_pages)
         return fail(c, CAKE_E_INVAL, "store does not fit %d pages of %llu bytes", n_pages, (unsigned long long)image);
     const uint64_t layer_bytes = uint64_t(2) * c->m.n_kv_heads * pt * c->m.head_dim * esize(c);
-    if (dst->format == CAKE_STORE_INT8) {
+    const int bits = store_code_bits(dst->format);
+    if (bits) {
         rc = ensure_stage(c, image);
         if (rc != CAKE_OK) return rc;
     }
     for (int p = 0; p < n_pages; ++p) {
         char* out = (char*)dst->base + uint64_t(p) * dst->page_stride_bytes;
         const int pp = kv->block_table_host[p];
-        if (dst->format == CAKE_STORE_INT8) {
+        if (bits) {
             char* stage = (char*)c->q_stage;   // quantise, copy out, next page: one stream keeps them in order
-            HIP_TRY(c, launch_quant_page(c->m.dtype, stage, make_view(c, kv, 0), pp, c->m.n_layers, c->cs));
+            HIP_TRY(c, launch_quant_page(c->m.dtype, stage, make_view(c, kv, 0), pp, c->m.n_layers, bits, c->cs));
             HIP_TRY(c, hipMemcpyAsync(out, stage, image, hipMemcpyDeviceToHost, c->cs));
         } else {
             for (int l = 0; l < c->m.n_layers; ++l) {
@@ -768,7 +773,7 @@ int32_t cake_adaptive_serve(cake_ctx* c, cake_request* reqs, int32_t n_reqs, int
             if (int64_t(r.store->n_pages) * r.kv->page_tokens < r.n_tokens) return fail(c, CAKE_E_INVAL, "adaptive mode needs the whole prompt stored");
         }
         if (fetch_chunk <= 0 || fetch_chunk % r.kv->page_tokens) return fail(c, CAKE_E_INVAL, "fetch_chunk must be a multiple of page_tokens");
-        if (r.store->format != CAKE_STORE_RAW && r.store->format != CAKE_STORE_INT8) return fail(c, CAKE_E_INVAL, "store: unknown format %d", r.store->format);
+        if (!store_format_known(r.store->format)) return fail(c, CAKE_E_INVAL, "store: unknown format %d", r.store->format);
         if (r.store->page_tokens != r.kv->page_tokens ||
             r.store->page_stride_bytes < cake::store_image_bytes(c->m, r.kv->page_tokens, r.store->format))
             return fail(c, CAKE_E_INVAL, "store does not match the page layout");

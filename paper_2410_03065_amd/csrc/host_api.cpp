@@ -94,7 +94,7 @@ int32_t cake_prefix_lookup(const uint64_t* stored_sorted, int32_t n_stored, cons
 }
 
 uint64_t cake_store_image_bytes(const cake_model_desc* model, int32_t page_tokens, int32_t format) {
-    if (!model || page_tokens <= 0 || (format != CAKE_STORE_RAW && format != CAKE_STORE_INT8)) return 0;
+    if (!model || page_tokens <= 0 || (format != CAKE_STORE_RAW && format != CAKE_STORE_INT8 && format != CAKE_STORE_INT4)) return 0;
     return cake::store_image_bytes(*model, page_tokens, format);
 }
 

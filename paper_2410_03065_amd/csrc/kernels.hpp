@@ -52,10 +52,10 @@ bool decode_attention_mfma_supported(int dtype, int head_dim, int page_tokens, i
 hipError_t launch_decode_attention_mfma(const float* q, float* part, int n_q, int n_keys, int tiles_per_split,
                                         int n_splits, const KvView& kv, hipStream_t st);
 
-// ---- 8-bit stored KV: one page image (all layers) <-> the layer pages of physical page phys_page ----
-hipError_t launch_dequant_page(int dtype, const void* image, const KvView& kv, int phys_page, int n_layers,
+// ---- quantised stored KV (bits = 8 or 4): one page image (all layers) <-> the layer pages of physical page phys_page ----
+hipError_t launch_dequant_page(int dtype, const void* image, const KvView& kv, int phys_page, int n_layers, int bits,
                                hipStream_t st);
-hipError_t launch_quant_page(int dtype, void* image, const KvView& kv, int phys_page, int n_layers,
+hipError_t launch_quant_page(int dtype, void* image, const KvView& kv, int phys_page, int n_layers, int bits,
                              hipStream_t st);
 
 // ---- first-token step (one row of activations: matrix-vector products, one-token attention) ----

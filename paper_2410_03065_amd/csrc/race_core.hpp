@@ -77,6 +77,7 @@ inline uint64_t page_image_bytes(const cake_model_desc& m, int page_tokens) {
 // Bytes of one page image in a store of the given format (cake_store_format).
 inline uint64_t store_image_bytes(const cake_model_desc& m, int page_tokens, int format) {
     if (format == CAKE_STORE_INT8) return uint64_t(m.n_layers) * 2 * m.n_kv_heads * page_tokens * (uint64_t(m.head_dim) + 4);
+    if (format == CAKE_STORE_INT4) return uint64_t(m.n_layers) * 2 * m.n_kv_heads * page_tokens * (uint64_t(m.head_dim) / 2 + 4);
     return page_image_bytes(m, page_tokens);
 }
 

@@ -720,6 +720,77 @@ def test_int8_store_load_is_bit_exact_and_quantiser_matches():
         np.testing.assert_array_equal(t.view(want.dtype).reshape(want.shape), want)
 
 
+def test_int4_store_load_is_bit_exact_and_quantiser_matches():
+    """The 4-bit store (two codes per byte): loaded pages equal the oracle's dequantised values
+    bit for bit, the GPU's writer produces the oracle's packed codes and scales, and a file-backed
+    4-bit store loads the same bytes."""
+    import paper_2410_03065_amd as cake
+    for kind, shape, T, pt in (("bf16", BF_NARROW_GQA4, 1000, 256), ("f32", si.TINY, 500, 128)):
+        rng = np.random.default_rng(19)
+        eng = cake.Engine(shape, si.make_weights(shape, seed=1), max_tokens=((T + pt - 1) // pt) * pt, max_chunk=pt,
+                          page_tokens=pt, block_table=np.random.default_rng(2).permutation((T + pt - 1) // pt).astype(np.int32))
+        cache = otf.KVCache(shape.n_layers, T, shape.n_kv, shape.head_dim)
+        cache.k[:] = otf.round_storage(rng.standard_normal(cache.k.shape) * 4, kind)
+        cache.v[:] = otf.round_storage(rng.standard_normal(cache.v.shape), kind)
+        cache.v[0, 5] = 0.0                                                  # a row of zeros: scale 0
+        cache.k[0, 7, 0, :] = np.arange(shape.head_dim) % 15 - 7.0           # every code value, in both nibbles
+        img4 = ostore.pack_store_int4(cache, pt)
+        assert img4[0].size == ostore.int4_image_bytes(shape.n_layers, shape.n_kv, shape.head_dim, pt)
+        eng.set_store_int4(img4)
+        toks = si.make_tokens(T, shape.vocab, seed=3)
+        res = eng.bidirectional_prefill(toks, pt, 2.0, mode="load_only")
+        assert res.meet_point == 0 and res.load_bytes == img4.size
+        want = ostore.pack_store(ostore.unpack_store_int4(img4, T, shape.n_kv, shape.head_dim, pt, kind), pt, kind)
+        np.testing.assert_array_equal(eng.pool_raw(T).view(want.dtype), want)
+        t = eng.write_store(T, cake.STORE_INT4).numpy().reshape(img4.shape)
+        held = ostore.unpack_store(eng.pool_raw(T).view(want.dtype), T, shape.n_kv, shape.head_dim, pt, kind)
+        np.testing.assert_array_equal(t, ostore.pack_store_int4(held, pt))
+        # the writer on the original (unquantised) values
+        eng.set_store(ostore.pack_store(cache, pt, kind))
+        eng.clear_pool()
+        eng.bidirectional_prefill(toks, pt, 2.0, mode="load_only")
+        t = eng.write_store(T, cake.STORE_INT4).numpy().reshape(img4.shape)
+        np.testing.assert_array_equal(t, img4)
+
+
+def test_bidirectional_with_int4_store_moves_the_meet_point_further_left():
+    """Table 6's trend with two compression levels: at one tier bandwidth the 4-bit store (0.27 of
+    the 16-bit bytes) leaves more chunks to the loader than the 8-bit one (0.52)."""
+    shape, T, C, pt = BF_NARROW_GQA4, 16384, 1024, 256
+    import paper_2410_03065_amd as cake
+    eng = cake.Engine(shape, None, max_tokens=T, max_chunk=C, page_tokens=pt, seed=1)
+    toks = si.make_tokens(T, shape.vocab, seed=2)
+    eng.bidirectional_prefill(toks, C, 4.0, mode="compute_only")
+    r_c = eng.bidirectional_prefill(toks, C, 4.0, mode="compute_only")
+    full = eng.pool_raw(T).copy()
+    rate = T * otf.kv_bytes_per_token(shape.n_layers, shape.n_kv, shape.head_dim, 2) / r_c.ttft_ns
+    meet, ppc = {}, C // pt
+    for fmt in (cake.STORE_INT8, cake.STORE_INT4):
+        eng.bidirectional_prefill(toks, C, 4.0, mode="compute_only", log=False)
+        t = eng.write_store(T, fmt).numpy().copy()
+        eng.bidirectional_prefill(toks, C, rate, mode="bidir")               # first load of this format: staging set up
+        eng.clear_pool()
+        r = eng.bidirectional_prefill(toks, C, rate, mode="bidir")
+        m = meet[fmt] = r.meet_point
+        raw = eng.pool_raw(T)
+        np.testing.assert_array_equal(raw[:m * ppc], full[:m * ppc])         # computed chunks: the compute-only bytes
+        per_page = int(eng.lib.cake_store_image_bytes(C_byref_model(eng), pt, fmt))
+        assert r.load_bytes == (T // C - m) * ppc * per_page
+        _check_decisions(r, shape, T, C, pt, page_bytes=per_page)
+        # loaded pages: the oracle's dequantisation of the very codes the store holds
+        if fmt == cake.STORE_INT4:
+            img = t.reshape(T // pt, shape.n_layers, 2, -1)
+            deq = ostore.pack_store(ostore.unpack_store_int4(img, T, shape.n_kv, shape.head_dim, pt, "bf16"), pt, "bf16")
+            np.testing.assert_array_equal(raw[m * ppc:].view(np.uint16), deq[m * ppc:])
+    assert 0 < meet[cake.STORE_INT4] < meet[cake.STORE_INT8] < T // C
+
+
+def C_byref_model(eng):
+    import ctypes
+    import paper_2410_03065_amd as cake
+    return ctypes.byref(cake.model_desc(eng.shape))
+
+
 def test_bidirectional_with_int8_store_moves_the_meet_point_left():
     """Sec. 5.5: the same tier bandwidth with an 8-bit store.  Computed chunks match the oracle's
     bf16 KV as before, loaded chunks are the dequantised store (within half a quantisation step of

@@ -158,6 +158,17 @@ def test_sizes():
             shape.n_layers, shape.n_kv, shape.head_dim, shape.elem_bytes)
     assert cake.range_flops(si.LLAMA3_8B, 1000, 24) + cake.range_flops(si.LLAMA3_8B, 1024, 1000) == \
         cake.range_flops(si.LLAMA3_8B, 1000, 1024)
+    # page image sizes of the three store formats, against the oracle's
+    import ctypes
+    from oracle import store as ostore
+    lib = cake.load_library()
+    for shape in (si.LLAMA3_8B, si.LLAMA2_70B, si.TINY):
+        md = ctypes.byref(cake.model_desc(shape))
+        a = (shape.n_layers, shape.n_kv, shape.head_dim, 256)
+        assert lib.cake_store_image_bytes(md, 256, cake.STORE_RAW) == cake.page_image_bytes(shape, 256)
+        assert lib.cake_store_image_bytes(md, 256, cake.STORE_INT8) == ostore.int8_image_bytes(*a)
+        assert lib.cake_store_image_bytes(md, 256, cake.STORE_INT4) == ostore.int4_image_bytes(*a)
+        assert lib.cake_store_image_bytes(md, 256, 3) == 0 and lib.cake_store_image_bytes(md, 0, cake.STORE_RAW) == 0
 
 
 def test_engine_refuses_to_run_without_gpu():
