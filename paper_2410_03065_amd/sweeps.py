@@ -5,6 +5,7 @@
     python -m paper_2410_03065_amd.sweeps --fluctuation   # Sec. 5.6 / Fig. 5 layout
     python -m paper_2410_03065_amd.sweeps --mix           # prefix request + Poisson arrivals, bandwidth step
     python -m paper_2410_03065_amd.sweeps --burst         # Sec. 5.7 layout: prefix request + a burst of short requests
+    python -m paper_2410_03065_amd.sweeps --compression   # Sec. 5.5 / Table 6 layout: bandwidth x stored-KV precision
 
 Grid: one prefix-cached prompt (default: Llama3-8B shape, 32768 random tokens) is produced by the
 adaptive engine while other users hold 0 / 12.5 / 50 / 87.5 % of every step's token budget, at the
@@ -31,6 +32,8 @@ def main():
                     "bandwidth stepping 25 -> 2 GB/s when the loader has completed its 8th chunk")
     ap.add_argument("--burst", action="store_true", help="prefix request, then 22 requests of 32-448 tokens: finish time when the "
                     "prefix request runs to completion first against the adaptive mode")
+    ap.add_argument("--compression", action="store_true", help="tier bandwidth x store format (16-bit, 8-bit, 4-bit): "
+                    "speed-up over load-only and over compute-only, the request alone on the GPU")
     ap.add_argument("--rate", type=float, default=2.0, help="arrivals per second of the other requests (--mix)")
     ap.add_argument("--other-tokens", type=int, default=4096)
     ap.add_argument("--shape", default="llama3-8b-shape")
@@ -80,6 +83,27 @@ def main():
                 cells.append("%.3f (%.2f \\\\ %.2f) m=%d" % (t, load_only[gb] / t, t_c / t, per_req[0]["tokens_computed"]))
             print("| %.1f %% | %.3f | %s |" % (share * 100, t_c, " | ".join(cells)))
         print("\nload-only s: " + ", ".join("%g Gbps %.3f" % (g, load_only[g]) for g in args.gbit))
+    if args.compression:
+        r_c = eng.bidirectional_prefill(toks, B, 4.0, mode="compute_only", log=False)     # also refills the pool for the writers
+        t_c = r_c.ttft_ns / 1e9
+        rows = {gb: [] for gb in args.gbit}
+        sizes = []
+        for name, fmt in (("16-bit", cake.STORE_RAW), ("8-bit", cake.STORE_INT8), ("4-bit", cake.STORE_INT4)):
+            eng.bidirectional_prefill(toks, B, 4.0, mode="compute_only", log=False)
+            eng.write_store(T, fmt)
+            eng.bidirectional_prefill(toks, B, 4.0, mode="bidir", log=False)              # staging of this format set up
+            for gb in args.gbit:
+                r_l = eng.bidirectional_prefill(toks, B, gb / 8.0, mode="load_only", log=False)
+                r_b = eng.bidirectional_prefill(toks, B, gb / 8.0, mode="bidir", log=False)
+                t = r_b.ttft_ns / 1e9
+                rows[gb].append("%.3f (%.2f \\\\ %.2f) m=%d" % (t, r_l.ttft_ns / 1e9 / t, t_c / t, r_b.meet_point))
+            sizes.append("%s %.2f GB" % (name, r_l.load_bytes / 1e9))
+        print("\ncompute-only %.3f s; store sizes: %s; cell = TTFT s (x load-only \\\\ x compute-only) meet point of %d chunks"
+              % (t_c, ", ".join(sizes), r_c.n_chunks))
+        print("| bandwidth | 16-bit | 8-bit | 4-bit |")
+        print("|---|---|---|---|")
+        for gb in args.gbit:
+            print("| %g Gbps | %s |" % (gb, " | ".join(rows[gb])))
     if args.mix:
         # arrivals drawn from t = -2 s so the GPU is already shared when the prefix request comes in (t = 0 here = 2 s)
         rng = np.random.default_rng(2)
