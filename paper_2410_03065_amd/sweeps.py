@@ -6,6 +6,8 @@
     python -m paper_2410_03065_amd.sweeps --mix           # prefix request + Poisson arrivals, bandwidth step
     python -m paper_2410_03065_amd.sweeps --burst         # Sec. 5.7 layout: prefix request + a burst of short requests
     python -m paper_2410_03065_amd.sweeps --compression   # Sec. 5.5 / Table 6 layout: bandwidth x stored-KV precision
+    python -m paper_2410_03065_amd.sweeps --lengths --shape longalpaca-13b-shape --tokens 16384 --budget 512
+                                                          # Sec. 5.3 / Table 4 layout: prompt length x bandwidth
 
 Grid: one prefix-cached prompt (default: Llama3-8B shape, 32768 random tokens) is produced by the
 adaptive engine while other users hold 0 / 12.5 / 50 / 87.5 % of every step's token budget, at the
@@ -33,6 +35,8 @@ def main():
     ap.add_argument("--burst", action="store_true", help="prefix request, then 22 requests of 32-448 tokens: finish time when the "
                     "prefix request runs to completion first against the adaptive mode")
     ap.add_argument("--compression", action="store_true", help="tier bandwidth x store format (16-bit, 8-bit, 4-bit): "
+                    "speed-up over load-only and over compute-only, the request alone on the GPU")
+    ap.add_argument("--lengths", action="store_true", help="prompt length (quarters of --tokens) x tier bandwidth: "
                     "speed-up over load-only and over compute-only, the request alone on the GPU")
     ap.add_argument("--rate", type=float, default=2.0, help="arrivals per second of the other requests (--mix)")
     ap.add_argument("--other-tokens", type=int, default=4096)
@@ -104,6 +108,22 @@ def main():
         print("|---|---|---|---|")
         for gb in args.gbit:
             print("| %g Gbps | %s |" % (gb, " | ".join(rows[gb])))
+    if args.lengths:
+        print("\ncell = TTFT s (x load-only \\\\ x compute-only) meet point / chunks; chunk %d" % B)
+        print("| prompt tokens | compute-only s | " + " | ".join("%g Gbps" % g for g in args.gbit) + " |")
+        print("|---|---|" + "---|" * len(args.gbit))
+        for quarter in (1, 2, 3, 4):
+            n = max(B, (T * quarter // 4) // U * U)
+            part = toks[:n]                                  # the stored KV of a prefix is the prefix of the stored KV
+            eng.bidirectional_prefill(part, B, 4.0, mode="compute_only", log=False)
+            t_c = eng.bidirectional_prefill(part, B, 4.0, mode="compute_only", log=False).ttft_ns / 1e9
+            cells = []
+            for gb in args.gbit:
+                r_l = eng.bidirectional_prefill(part, B, gb / 8.0, mode="load_only", log=False)
+                r_b = eng.bidirectional_prefill(part, B, gb / 8.0, mode="bidir", log=False)
+                t = r_b.ttft_ns / 1e9
+                cells.append("%.3f (%.2f \\\\ %.2f) %d/%d" % (t, r_l.ttft_ns / 1e9 / t, t_c / t, r_b.meet_point, r_b.n_chunks))
+            print("| %d | %.3f | %s |" % (n, t_c, " | ".join(cells)))
     if args.mix:
         # arrivals drawn from t = -2 s so the GPU is already shared when the prefix request comes in (t = 0 here = 2 s)
         rng = np.random.default_rng(2)
