@@ -72,6 +72,8 @@ struct cake_ctx {
     struct ProfRec { int cls; uint64_t flops, bytes; };
     std::vector<hipEvent_t> prof_events;  // pairs: [2i] before, [2i+1] after
     std::vector<ProfRec> prof_recs;
+    // the load worker of every race of this context (bound to the context's device when it starts)
+    WorkerThread load_thread;
 };
 
 static int fail(cake_ctx* ctx, int code, const char* fmt, ...) {
@@ -289,6 +291,7 @@ static int pread_all(cake_ctx* c, int fd, void* dst, uint64_t n, uint64_t off) {
     char* p = (char*)dst;
     while (n > 0) {
         ssize_t got = pread(fd, p, size_t(n), off_t(off));
+        if (got < 0 && errno == EINTR) continue;
         if (got <= 0)
             return fail(c, CAKE_E_STORE_MISS, "store file: read of %llu bytes at %llu failed (%s)", (unsigned long long)n,
                         (unsigned long long)off, got == 0 ? "end of file" : strerror(errno));
@@ -399,8 +402,6 @@ struct HipBackend : Backend {
         return CAKE_OK;
     }
     int load_chunk(int i) override {
-        static thread_local bool dev_set = false;
-        if (!dev_set) { (void)hipSetDevice(c->device); dev_set = true; }
         int rc = enqueue_load(c, store, tb[i], tc[i], kv, -1.0);
         if (rc != CAKE_OK) return rc;
         if (hipStreamSynchronize(c->ls) != hipSuccess) return fail(c, CAKE_E_HIP, "copy stream failed in chunk %d", i);
@@ -474,12 +475,15 @@ int32_t cake_create(cake_ctx** out, const cake_model_desc* model, const cake_wei
         cake_destroy(c);
         return CAKE_E_NOMEM;
     }
+    const int device = c->device;
+    c->load_thread.start([device] { (void)hipSetDevice(device); });
     *out = c;
     return CAKE_OK;
 }
 
 int32_t cake_destroy(cake_ctx* c) {
     if (!c) return CAKE_OK;
+    c->load_thread.stop();
     if (c->cs || c->ls) (void)hipDeviceSynchronize();
     (void)hipFree(c->x); (void)hipFree(c->h); (void)hipFree(c->qkv); (void)hipFree(c->q);
     (void)hipFree(c->ao); (void)hipFree(c->act); (void)hipFree(c->rope_cs); (void)hipFree(c->d_ids);
@@ -607,7 +611,7 @@ int32_t cake_bidirectional_prefill(cake_ctx* c, const int32_t* token_ids, int32_
         HIP_TRY(c, hipMemcpyAsync(c->d_ids, token_ids, size_t(n_tokens) * 4, hipMemcpyHostToDevice, c->cs));
     }
     uint64_t race_ns = 0;
-    rc = ex.run(be, &race_ns);
+    rc = ex.run(be, &race_ns, &c->load_thread);
     // chunks beyond the stored prefix: they attend to everything before them, so they start after the join
     ex.chunk_log.resize(size_t(n), cake_chunk_log{CAKE_SRC_NONE, 0, 0, 0, 0, 0, 0});
     for (int i = n_race; i < n && rc == CAKE_OK; ++i) {
@@ -813,7 +817,6 @@ int32_t cake_adaptive_serve(cake_ctx* c, cake_request* reqs, int32_t n_reqs, int
     std::vector<char> done(n_reqs, 0);
     int n_done = 0, n_steps = 0, hard = CAKE_OK;
     bool steps_overflow = false, loader_started = false;
-    std::thread loader;
     uint64_t prefix_compute_end = 0, starved_ns = 0;
     ex.t0 = mono_ns();
 
@@ -823,7 +826,7 @@ int32_t cake_adaptive_serve(cake_ctx* c, cake_request* reqs, int32_t n_reqs, int
     while (n_done < n_reqs && hard == CAKE_OK) {
         uint64_t now = ex.now();
         if (P >= 0 && !loader_started && reqs[P].arrival_ns <= now) {
-            loader = std::thread([&] { ex.worker(W_LOAD, be); });
+            c->load_thread.submit([&] { ex.worker(W_LOAD, be); });
             loader_started = true;
         }
         // ---- deal the budget out: (1) decoding requests: none, a request leaves once its KV is
@@ -939,7 +942,7 @@ int32_t cake_adaptive_serve(cake_ctx* c, cake_request* reqs, int32_t n_reqs, int
         ++ex.gen;
         ex.cv.notify_all();
     }
-    if (loader_started) loader.join();
+    if (loader_started) c->load_thread.wait();
     if (hard == CAKE_OK && ex.first_error != CAKE_OK) hard = ex.first_error;
     (void)hipStreamSynchronize(c->cs);
     c->step_after = -1;

@@ -6,6 +6,7 @@
 #include <atomic>
 #include <chrono>
 #include <condition_variable>
+#include <functional>
 #include <mutex>
 #include <thread>
 #include <vector>
@@ -29,6 +30,65 @@ inline uint64_t mono_ns() {
     return uint64_t(std::chrono::duration_cast<std::chrono::nanoseconds>(
                         std::chrono::steady_clock::now().time_since_epoch()).count());
 }
+
+// A thread that lives as long as its owner and runs one job at a time: the load worker of every
+// race of a context runs here, so that no thread is created on the path whose latency is measured.
+class WorkerThread {
+public:
+    WorkerThread() = default;
+    WorkerThread(const WorkerThread&) = delete;
+    WorkerThread& operator=(const WorkerThread&) = delete;
+    ~WorkerThread() { stop(); }
+    // on_start runs once on the new thread before the first job (e.g. binding the thread to a device)
+    void start(std::function<void()> on_start) {
+        if (th_.joinable()) return;
+        th_ = std::thread([this, on_start] {
+            if (on_start) on_start();
+            std::unique_lock<std::mutex> lk(mu_);
+            for (;;) {
+                cv_.wait(lk, [&] { return quit_ || job_; });
+                if (quit_) return;
+                std::function<void()> j = std::move(job_);
+                job_ = nullptr;
+                lk.unlock();
+                j();
+                lk.lock();
+                busy_ = false;
+                cv_.notify_all();
+            }
+        });
+    }
+    bool running() const { return th_.joinable(); }
+    // one job at a time: the caller waits for the previous one first
+    void submit(std::function<void()> job) {
+        std::unique_lock<std::mutex> lk(mu_);
+        cv_.wait(lk, [&] { return !busy_; });
+        busy_ = true;
+        job_ = std::move(job);
+        cv_.notify_all();
+    }
+    void wait() {
+        std::unique_lock<std::mutex> lk(mu_);
+        cv_.wait(lk, [&] { return !busy_; });
+    }
+    void stop() {
+        if (!th_.joinable()) return;
+        {
+            std::unique_lock<std::mutex> lk(mu_);
+            cv_.wait(lk, [&] { return !busy_; });
+            quit_ = true;
+            cv_.notify_all();
+        }
+        th_.join();
+    }
+
+private:
+    std::thread th_;
+    std::mutex mu_;
+    std::condition_variable cv_;
+    std::function<void()> job_;
+    bool busy_ = false, quit_ = false;
+};
 
 struct Executor {
     RaceCore core;
@@ -104,8 +164,9 @@ struct Executor {
         }
     }
 
-    // Runs the race to the end.  Returns the first hard error, or CAKE_OK.
-    int run(Backend& be, uint64_t* ttft_ns) {
+    // Runs the race to the end.  Returns the first hard error, or CAKE_OK.  The load worker runs on
+    // `pool` if one is given and running, else on a thread of its own.
+    int run(Backend& be, uint64_t* ttft_ns, WorkerThread* pool = nullptr) {
         chunk_log.assign(size_t(core.n), cake_chunk_log{CAKE_SRC_NONE, 0, 0, 0, 0, 0, 0});
         first_error = CAKE_OK;
         load_failed_chunk = -1;
@@ -113,10 +174,13 @@ struct Executor {
         gen = 0;
         t0 = mono_ns();
         std::thread loader;
-        bool have_loader = !core.w[W_LOAD].retired && core.n > 0;
-        if (have_loader) loader = std::thread([&] { worker(W_LOAD, be); });
+        const bool have_loader = !core.w[W_LOAD].retired && core.n > 0;
+        const bool pooled = have_loader && pool && pool->running();
+        if (pooled) pool->submit([&] { worker(W_LOAD, be); });
+        else if (have_loader) loader = std::thread([&] { worker(W_LOAD, be); });
         if (!core.w[W_COMPUTE].retired) worker(W_COMPUTE, be);
-        if (have_loader) loader.join();
+        if (pooled) pool->wait();
+        else if (have_loader) loader.join();
         *ttft_ns = now();
         if (first_error != CAKE_OK) return first_error;
         std::lock_guard<std::mutex> g(mu);

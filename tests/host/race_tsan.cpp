@@ -32,6 +32,8 @@ struct FakeBackend : Backend {
     }
 };
 
+static WorkerThread* g_pool = nullptr;   // the load worker runs here when set, else on a thread per race
+
 static int run_case(int n, int mode, int forced, int fail) {
     std::vector<uint64_t> flops(n), bytes(n);
     std::vector<int32_t> tb(n), tc(n);
@@ -47,7 +49,7 @@ static int run_case(int n, int mode, int forced, int fail) {
     ex.status = status.data(); ex.tok_begin = tb.data(); ex.tok_count = tc.data();
     FakeBackend be(n, fail);
     uint64_t ttft = 0;
-    int rc = ex.run(be, &ttft);
+    int rc = ex.run(be, &ttft, g_pool);
     if (mode == CAKE_LOAD_ONLY && fail >= 0) return rc == CAKE_E_STORE_MISS ? 0 : 1;
     if (rc != CAKE_OK) { std::printf("case n=%d mode=%d: rc %d\n", n, mode, rc); return 1; }
     bool seen_load = false;
@@ -64,7 +66,11 @@ static int run_case(int n, int mode, int forced, int fail) {
 
 int main() {
     int bad = 0;
-    for (int rep = 0; rep < 5; ++rep) {
+    WorkerThread pool;
+    std::atomic<int> started{0};
+    pool.start([&] { started++; });
+    for (int rep = 0; rep < 6; ++rep) {
+        g_pool = (rep & 1) ? &pool : nullptr;
         for (int n : {1, 2, 7, 24}) {
             bad += run_case(n, CAKE_BIDIR, 0, -1);
             bad += run_case(n, CAKE_GREEDY, 0, -1);
@@ -76,6 +82,10 @@ int main() {
         bad += run_case(24, CAKE_GREEDY, 0, 20);
         bad += run_case(8, CAKE_LOAD_ONLY, 0, 7);
     }
+    g_pool = nullptr;
+    pool.stop();
+    pool.stop();                                  // a second stop is a no-op
+    if (started != 1) { std::printf("start hook ran %d times\n", started.load()); ++bad; }
     std::printf(bad ? "FAILED %d\n" : "ok\n", bad);
     return bad ? 1 : 0;
 }
