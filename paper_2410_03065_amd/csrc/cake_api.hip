@@ -2,6 +2,8 @@
 // See include/cake.h for the contract of every entry point.
 #include <hip/hip_runtime.h>
 #include <errno.h>
+#include <sys/prctl.h>
+#include <time.h>
 #include <unistd.h>
 
 #include <algorithm>
@@ -50,6 +52,7 @@ struct cake_ctx {
     size_t f_stage_bytes = 0;
     int f_next = 0;
     hipEvent_t ev_a = nullptr, ev_b = nullptr;
+    hipEvent_t ev_load = nullptr;   // blocking-sync event: the load worker sleeps until the copy stream has drained
     std::atomic<double> gbps{0.0};
     int step_after = -1;
     double step_gbps = 0.0;
@@ -236,14 +239,22 @@ static int enqueue_first_token(cake_ctx* c, int n_tokens, const cake_kv* kv) {
 }
 
 // ------------------------------------------------------------------ throttled load
+// The load worker never spins: a spinning thread that the scheduler puts on the compute thread's core
+// keeps that thread off it for a whole timeslice.  It sleeps to an absolute deadline on the monotonic
+// clock (the worker thread runs with a timer slack of 1 us, so it wakes within a few us); what a wake-up
+// is late by is made up at the next piece, because the pacing deadlines are cumulative.
 static void wait_until_ns(uint64_t deadline) {
-    for (;;) {
-        uint64_t now = mono_ns();
-        if (now >= deadline) return;
-        uint64_t left = deadline - now;
-        if (left > 200000) std::this_thread::sleep_for(std::chrono::nanoseconds(left - 100000));
-        // short remainders are spun: a sleep overshoots by tens of microseconds
-    }
+    timespec ts;
+    ts.tv_sec = time_t(deadline / 1000000000ull);
+    ts.tv_nsec = long(deadline % 1000000000ull);
+    while (mono_ns() < deadline)
+        if (clock_nanosleep(CLOCK_MONOTONIC, TIMER_ABSTIME, &ts, nullptr) != 0 && errno != EINTR) break;
+}
+
+// Blocks (no spinning) until everything issued to the copy stream so far has completed.
+static hipError_t drain_copy_stream(cake_ctx* c) {
+    hipError_t e = hipEventRecord(c->ev_load, c->ls);
+    return e != hipSuccess ? e : hipEventSynchronize(c->ev_load);
 }
 
 // The tier's rate right now: the bandwidth trace if one is running (never below 0.01 GB/s, so a
@@ -350,7 +361,7 @@ static int enqueue_load(cake_ctx* c, const cake_kv_store* st, int tok_begin, int
                 if (rc != CAKE_OK) return rc;
                 // the copy stream is in order: once it has drained, the DMA out of the OTHER buffer (issued one
                 // piece ago, running while this piece was read) is done and that buffer may be refilled next
-                HIP_TRY(c, hipStreamSynchronize(c->ls));
+                HIP_TRY(c, drain_copy_stream(c));
                 from = c->f_stage[b];
                 HIP_TRY(c, hipMemcpyAsync(dst + off, from, n, hipMemcpyHostToDevice, c->ls));
             } else {
@@ -404,7 +415,7 @@ struct HipBackend : Backend {
     int load_chunk(int i) override {
         int rc = enqueue_load(c, store, tb[i], tc[i], kv, -1.0);
         if (rc != CAKE_OK) return rc;
-        if (hipStreamSynchronize(c->ls) != hipSuccess) return fail(c, CAKE_E_HIP, "copy stream failed in chunk %d", i);
+        if (drain_copy_stream(c) != hipSuccess) return fail(c, CAKE_E_HIP, "copy stream failed in chunk %d", i);
         return CAKE_OK;
     }
     void on_load_completed(int n_loaded) override {
@@ -458,6 +469,7 @@ int32_t cake_create(cake_ctx** out, const cake_model_desc* model, const cake_wei
     ok = ok && hipMalloc((void**)&c->rope_cs, R * m.head_dim * 4) == hipSuccess;
     ok = ok && hipMalloc((void**)&c->d_ids, size_t(max_tokens) * 4) == hipSuccess;
     ok = ok && hipEventCreate(&c->ev_a) == hipSuccess && hipEventCreate(&c->ev_b) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&c->ev_load, hipEventBlockingSync | hipEventDisableTiming) == hipSuccess;
     if (weights->final_norm && weights->lm_head) {
         c->final_norm = weights->final_norm;
         c->lm_head = weights->lm_head;
@@ -476,7 +488,10 @@ int32_t cake_create(cake_ctx** out, const cake_model_desc* model, const cake_wei
         return CAKE_E_NOMEM;
     }
     const int device = c->device;
-    c->load_thread.start([device] { (void)hipSetDevice(device); });
+    c->load_thread.start([device] {
+        (void)hipSetDevice(device);
+        (void)prctl(PR_SET_TIMERSLACK, 1000UL, 0UL, 0UL, 0UL);   // this thread's sleeps end within ~1 us of their deadline
+    });
     *out = c;
     return CAKE_OK;
 }
@@ -495,6 +510,7 @@ int32_t cake_destroy(cake_ctx* c) {
     for (hipEvent_t e : c->prof_events) (void)hipEventDestroy(e);
     if (c->ev_a) (void)hipEventDestroy(c->ev_a);
     if (c->ev_b) (void)hipEventDestroy(c->ev_b);
+    if (c->ev_load) (void)hipEventDestroy(c->ev_load);
     delete c;
     return CAKE_OK;
 }
