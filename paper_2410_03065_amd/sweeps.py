@@ -6,6 +6,7 @@
     python -m paper_2410_03065_amd.sweeps --mix           # prefix request + Poisson arrivals, bandwidth step
     python -m paper_2410_03065_amd.sweeps --burst         # Sec. 5.7 layout: prefix request + a burst of short requests
     python -m paper_2410_03065_amd.sweeps --compression   # Sec. 5.5 / Table 6 layout: bandwidth x stored-KV precision
+    python -m paper_2410_03065_amd.sweeps --chunks        # Sec. 3.2 / Fig. 4 layout: per-chunk compute and load time
     python -m paper_2410_03065_amd.sweeps --lengths --shape longalpaca-13b-shape --tokens 16384 --budget 512
                                                           # Sec. 5.3 / Table 4 layout: prompt length x bandwidth
 
@@ -36,6 +37,8 @@ def main():
                     "prefix request runs to completion first against the adaptive mode")
     ap.add_argument("--compression", action="store_true", help="tier bandwidth x store format (16-bit, 8-bit, 4-bit): "
                     "speed-up over load-only and over compute-only, the request alone on the GPU")
+    ap.add_argument("--chunks", action="store_true", help="time of every chunk when computed (grows with its position) "
+                    "and when loaded (constant), at the first --gbit bandwidth")
     ap.add_argument("--lengths", action="store_true", help="prompt length (quarters of --tokens) x tier bandwidth: "
                     "speed-up over load-only and over compute-only, the request alone on the GPU")
     ap.add_argument("--rate", type=float, default=2.0, help="arrivals per second of the other requests (--mix)")
@@ -108,6 +111,15 @@ def main():
         print("|---|---|---|---|")
         for gb in args.gbit:
             print("| %g Gbps | %s |" % (gb, " | ".join(rows[gb])))
+    if args.chunks:
+        gb = args.gbit[0]
+        r_c = eng.bidirectional_prefill(toks, B, gb / 8.0, mode="compute_only")
+        r_l = eng.bidirectional_prefill(toks, B, gb / 8.0, mode="load_only")
+        print("\n| chunk (of %d tokens) | computed: ms on the GPU | PFLOP/s | loaded at %g Gbps: ms |" % (B, gb))
+        print("|---|---|---|---|")
+        for i, (cc, cl) in enumerate(zip(r_c.chunks, r_l.chunks)):
+            ms_c = cc["device_ns"] / 1e6
+            print("| %d | %.2f | %.2f | %.2f |" % (i, ms_c, cc["work"] / max(1, cc["device_ns"]) / 1e6, (cl["end_ns"] - cl["start_ns"]) / 1e6))
     if args.lengths:
         print("\ncell = TTFT s (x load-only \\\\ x compute-only) meet point / chunks; chunk %d" % B)
         print("| prompt tokens | compute-only s | " + " | ".join("%g Gbps" % g for g in args.gbit) + " |")
