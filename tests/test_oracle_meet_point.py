@@ -77,6 +77,33 @@ def test_paper_table3_cells_follow_the_split_model(golden):
         assert abs(sum(c) / t / b - 1) < 0.08, (hw, util, gbps)
 
 
+def test_paper_table6_cells_follow_the_split_model_and_the_store_sizes(golden):
+    """Sec. 5.5 / Table 6.  Every cell fits the split model as in Table 3.  Between the 16-bit and
+    the 8-bit column only the load time changes, so the ratio of the two T_c/T_l values is the ratio
+    of the store sizes: the oracle's 8-bit image, (hd + 4) / (2 hd) of the 16-bit one at head_dim 128,
+    predicts the paper's column within 4 %; its 4-bit image lies between the 8-bit and 3-bit columns."""
+    from oracle import store as ostore
+    rows = golden("table6_compression.txt")
+    assert len(rows) == 12
+    ratio = {}
+    for gbps, bits, a, b in rows:
+        a, b = float(a), float(b)
+        c = [int(round(b / a * 10000))] * 32
+        l = [10000] * 32
+        _, t = mp.brute_force_meet_point(c, l)
+        assert abs(sum(l) / t / a - 1) < 0.08 and abs(sum(c) / t / b - 1) < 0.08, (gbps, bits)
+        ratio[(gbps, bits)] = b / a                                  # T_c / T_l of that cell
+    size16 = 2 * 128                                                 # bytes per (token, KV head) row, K or V
+    size8 = ostore.int8_image_bytes(1, 1, 128, 64) / (2 * 64)
+    size4 = ostore.int4_image_bytes(1, 1, 128, 64) / (2 * 64)
+    assert (size8, size4) == (132, 68)
+    for gbps in ("7", "25", "32", "56"):
+        faster8 = ratio[(gbps, "8")] / ratio[(gbps, "16")]           # how much faster the 8-bit store loads
+        faster3 = ratio[(gbps, "3")] / ratio[(gbps, "16")]
+        assert abs(faster8 / (size16 / size8) - 1) < 0.04, (gbps, faster8)
+        assert faster8 < size16 / size4 < faster3 * 1.05, (gbps, faster3)
+
+
 def test_literal_race_matches_alg1_behaviour():
     # balanced: 4 chunks, both sides one unit per chunk -> each takes two, done at t = 2
     assert mp.literal_race([1] * 4, [1] * 4) == (2, 2, 2)
