@@ -251,10 +251,22 @@ static void wait_until_ns(uint64_t deadline) {
         if (clock_nanosleep(CLOCK_MONOTONIC, TIMER_ABSTIME, &ts, nullptr) != 0 && errno != EINTR) break;
 }
 
-// Blocks (no spinning) until everything issued to the copy stream so far has completed.
+// Waits until everything issued to the copy stream so far has completed.  The last DMA piece of a chunk
+// is usually a fraction of a millisecond away: the event is polled for that long, offering the CPU to
+// other runnable threads between polls (an interrupt-driven wake-up costs up to hundreds of us on a busy
+// host); a longer wait sleeps on the blocking-sync event.
 static hipError_t drain_copy_stream(cake_ctx* c) {
     hipError_t e = hipEventRecord(c->ev_load, c->ls);
-    return e != hipSuccess ? e : hipEventSynchronize(c->ev_load);
+    if (e != hipSuccess) return e;
+    const uint64_t t0 = mono_ns();
+    for (;;) {
+        e = hipEventQuery(c->ev_load);
+        if (e != hipErrorNotReady) return e;
+        if (mono_ns() - t0 > 300000) break;
+        std::this_thread::yield();
+    }
+    (void)hipGetLastError();   // hipErrorNotReady is sticky for hipGetLastError only; clear it
+    return hipEventSynchronize(c->ev_load);
 }
 
 // The tier's rate right now: the bandwidth trace if one is running (never below 0.01 GB/s, so a

@@ -814,7 +814,8 @@ def test_bidirectional_with_int4_store_moves_the_meet_point_further_left():
     eng.bidirectional_prefill(toks, C, 4.0, mode="compute_only")
     r_c = eng.bidirectional_prefill(toks, C, 4.0, mode="compute_only")
     full = eng.pool_raw(T).copy()
-    rate = T * otf.kv_bytes_per_token(shape.n_layers, shape.n_kv, shape.head_dim, 2) / r_c.ttft_ns
+    # a tier half as fast as this GPU computes 16-bit KV: the transfer then outweighs the fixed cost of a load
+    rate = 0.5 * T * otf.kv_bytes_per_token(shape.n_layers, shape.n_kv, shape.head_dim, 2) / r_c.ttft_ns
     meet, ppc = {}, C // pt
     for fmt in (cake.STORE_INT8, cake.STORE_INT4):
         eng.bidirectional_prefill(toks, C, 4.0, mode="compute_only", log=False)
