@@ -858,7 +858,8 @@ def test_bidirectional_with_int8_store_moves_the_meet_point_left():
     eng.set_store(raw)
     eng.bidirectional_prefill(toks, C, 4.0, mode="compute_only")
     r_c = eng.bidirectional_prefill(toks, C, 4.0, mode="compute_only")
-    rate = T * otf.kv_bytes_per_token(shape.n_layers, shape.n_kv, shape.head_dim, 2) / r_c.ttft_ns
+    # a tier somewhat slower than this GPU computes 16-bit KV: the transfer outweighs the fixed cost of a load
+    rate = 0.7 * T * otf.kv_bytes_per_token(shape.n_layers, shape.n_kv, shape.head_dim, 2) / r_c.ttft_ns
     eng.bidirectional_prefill(toks, C, rate, mode="bidir")        # first race: loader thread and staging set up
     eng.clear_pool()
     r16 = eng.bidirectional_prefill(toks, C, rate, mode="bidir")
@@ -874,5 +875,5 @@ def test_bidirectional_with_int8_store_moves_the_meet_point_left():
     assert all(c["work"] == ppc * per_page8 for c in r8.chunks if c["source"] == 1)
     assert r8.load_bytes == (T // C - m) * ppc * per_page8
     _check_decisions(r8, shape, T, C, pt, page_bytes=per_page8)
-    # tier as fast as the GPU on 16-bit KV: about 8 of 16 chunks loaded there, about 11 with 8-bit KV
+    # about 6 of 16 chunks loaded with 16-bit KV, about 9 with 8-bit KV
     assert 0 < r8.meet_point < r16.meet_point
