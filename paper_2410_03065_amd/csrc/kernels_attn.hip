@@ -867,9 +867,12 @@ hipError_t launch_attention_mfma(const void* q, void* out, int n_q, int tok_begi
     } else {
         const int LDS = A8_TABLE + table;
         if (LDS > LDS_MAX) return hipErrorInvalidValue;
-        // 64-query workgroups when 128-query ones would not fill the chip
+        // 64-query workgroups (four waves, one per SIMD: about 0.85 of the eight-wave kernel's rate per CU) when
+        // they shorten the busiest CU's work: rounds of workgroups over 256 CUs times queries per workgroup
         const int q_tiles64 = (rows + 63) / 64;
-        if (variant == 3 || (variant == 0 && q_tiles * n_q < 256 && q_tiles64 > q_tiles))
+        const long rounds128 = (long(q_tiles) * n_q + 255) / 256, rounds64 = (long(q_tiles64) * n_q + 255) / 256;
+        const bool small_wins = q_tiles64 > q_tiles && double(rounds64) * 64 / 0.85 < double(rounds128) * 128;
+        if (variant == 3 || (variant == 0 && small_wins))
             hipLaunchKernelGGL(attention_mfma8_kernel<2>, dim3(q_tiles64 * n_q), dim3(256), LDS, st, (const bf16_t*)q, (bf16_t*)out,
                                n_q, tok_begin, rows, kv, q_tiles64);
         else
