@@ -292,12 +292,16 @@ typedef struct {
     uint64_t ttft_ns;           /* out: arrival -> all KV resident */
     int32_t tokens_computed;    /* out */
     int32_t tokens_loaded;      /* out */
+    int32_t want_first_token;   /* 1: once the KV is complete the request takes one decode step (the first-token
+                                   step of cake_first_token) in the next engine step, at priority 1; ttft_ns then
+                                   runs to the end of that step.  Needs final_norm and lm_head in the weights */
+    int32_t first_token;        /* out: that token, or -1 */
 } cake_request;
 
 /* One engine step: how the token budget was dealt out. */
 typedef struct {
     uint64_t start_ns, end_ns;  /* start = the instant the budget was dealt (requests with arrival <= start count) */
-    int32_t decode_tokens;      /* priority 1 (always 0 here: requests leave once their KV is complete) */
+    int32_t decode_tokens;      /* priority 1: first-token steps of requests whose KV is complete (want_first_token) */
     int32_t nonprefix_tokens;   /* priority 2 */
     int32_t prefix_tokens;      /* priority 3: what was left for the prefix-cached request */
     int32_t prefix_tok_begin;   /* first token of the prefix request's part, or -1 */
@@ -335,7 +339,7 @@ int32_t cake_set_traces(cake_ctx* ctx, const cake_traces* traces);
  * whatever budget is left; meanwhile that request's stored chunks of `fetch_chunk` tokens are
  * loaded back-to-front at `gbps` and the two meet where the planner says, re-planned at every
  * step from the rate the request actually gets.  At most one request may have has_prefix_cache.
- * Blocking; returns when every request's KV is resident.  `res` describes the prefix request's
+ * Blocking; returns when every request's KV is resident (and its first token produced, where asked).  `res` describes the prefix request's
  * race (decision log included); `steps`/`n_steps_out` may be NULL.
  * Errors: CAKE_E_INVAL, CAKE_E_HIP, CAKE_E_STORE_MISS, CAKE_E_CAPACITY (logs truncated). */
 int32_t cake_adaptive_serve(cake_ctx* ctx, cake_request* requests, int32_t n_requests,

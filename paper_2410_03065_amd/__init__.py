@@ -86,7 +86,8 @@ class DecisionLog(C.Structure):
 class Request(C.Structure):
     _fields_ = [("token_ids", C.c_void_p), ("n_tokens", C.c_int32), ("has_prefix_cache", C.c_int32),
                 ("arrival_ns", C.c_uint64), ("kv", C.c_void_p), ("store", C.c_void_p), ("ttft_ns", C.c_uint64),
-                ("tokens_computed", C.c_int32), ("tokens_loaded", C.c_int32)]
+                ("tokens_computed", C.c_int32), ("tokens_loaded", C.c_int32),
+                ("want_first_token", C.c_int32), ("first_token", C.c_int32)]
 
 
 class StepLog(C.Structure):
@@ -551,7 +552,8 @@ class Engine:
         self._check(self.lib.cake_set_traces(self.ctx, C.byref(t)), "cake_set_traces")
 
     def adaptive_serve(self, requests, token_budget, fetch_chunk, gbps):
-        """requests: list of dicts {tokens, arrival_ns, prefix (bool), kv (Kv or None = the engine's own)}.
+        """requests: list of dicts {tokens, arrival_ns, prefix (bool), kv (Kv or None = the engine's own),
+        first_token (bool: the request also takes its first decode step)}.
         Returns (PrefillResult for the prefix request, per-request dicts, step list)."""
         n = len(requests)
         arr = (Request * n)()
@@ -567,6 +569,7 @@ class Engine:
             arr[i].arrival_ns = int(r.get("arrival_ns", 0))
             arr[i].kv = C.addressof(kv)
             arr[i].store = C.addressof(self.store) if r.get("prefix") else None
+            arr[i].want_first_token = 1 if r.get("first_token") else 0
         nc = max(1, max((len(r["tokens"]) + fetch_chunk - 1) // fetch_chunk for r in requests))
         res = Result()
         chunks = (ChunkLog * nc)()
@@ -585,8 +588,8 @@ class Engine:
         ck = [f[0] for f in ChunkLog._fields_]
         out.chunks = [{k: getattr(chunks[i], k) for k in ck} for i in range(res.n_chunks)]
         out.decisions = _decisions_to_list(dec, res.n_decisions)
-        per_req = [dict(ttft_ns=arr[i].ttft_ns, tokens_computed=arr[i].tokens_computed, tokens_loaded=arr[i].tokens_loaded)
-                   for i in range(n)]
+        per_req = [dict(ttft_ns=arr[i].ttft_ns, tokens_computed=arr[i].tokens_computed, tokens_loaded=arr[i].tokens_loaded,
+                        first_token=arr[i].first_token) for i in range(n)]
         sk = [f[0] for f in StepLog._fields_]
         step_list = [{k: getattr(steps[i], k) for k in sk} for i in range(ns.value)]
         return out, per_req, step_list

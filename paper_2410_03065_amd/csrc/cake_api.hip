@@ -791,7 +791,8 @@ int32_t cake_adaptive_serve(cake_ctx* c, cake_request* reqs, int32_t n_reqs, int
             if (P >= 0) return fail(c, CAKE_E_INVAL, "more than one prefix-cached request");
             P = i;
         }
-        r.ttft_ns = 0; r.tokens_computed = 0; r.tokens_loaded = 0;
+        if (r.want_first_token && !c->lm_head) return fail(c, CAKE_E_STATE, "request %d: the first token needs final_norm and lm_head", i);
+        r.ttft_ns = 0; r.tokens_computed = 0; r.tokens_loaded = 0; r.first_token = -1;
     }
     std::vector<int32_t> tb, tc;
     std::vector<uint64_t> flops, bytes;
@@ -843,12 +844,21 @@ int32_t cake_adaptive_serve(cake_ctx* c, cake_request* reqs, int32_t n_reqs, int
     std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return reqs[a].arrival_ns < reqs[b].arrival_ns; });
     std::vector<int32_t> next_tok(n_reqs, 0);
     std::vector<char> done(n_reqs, 0);
+    // a request whose KV is complete either leaves, or waits for its decode step (the first token)
+    std::vector<char> kv_complete(n_reqs, 0), ft_pending(n_reqs, 0);
+    std::vector<int32_t> ft_tok(n_reqs, -1);
+    auto finish_kv = [&](int i, uint64_t at_ns, int* n_done_p) {
+        kv_complete[i] = 1;
+        if (reqs[i].want_first_token) { ft_pending[i] = 1; return; }
+        reqs[i].ttft_ns = at_ns - reqs[i].arrival_ns;
+        done[i] = 1; ++*n_done_p;
+    };
     int n_done = 0, n_steps = 0, hard = CAKE_OK;
     bool steps_overflow = false, loader_started = false;
     uint64_t prefix_compute_end = 0, starved_ns = 0;
     ex.t0 = mono_ns();
 
-    struct Part { int req, first, count; };   // req == -1: the other users' share of the step (trace)
+    struct Part { int req, first, count; bool decode; };   // req == -1: the other users' share of the step (trace)
     std::vector<Part> parts;
     if (!c->tr_gbps.empty()) c->tr_t0.store(mono_ns());
     while (n_done < n_reqs && hard == CAKE_OK) {
@@ -857,33 +867,39 @@ int32_t cake_adaptive_serve(cake_ctx* c, cake_request* reqs, int32_t n_reqs, int
             c->load_thread.submit([&] { ex.worker(W_LOAD, be); });
             loader_started = true;
         }
-        // ---- deal the budget out: (1) decoding requests: none, a request leaves once its KV is
-        // complete; (2) prefill of requests without a stored prefix, oldest first; (3) the rest to
-        // the prefix-cached request, as far as the plan gives it to the compute side
+        // ---- deal the budget out: (1) decoding requests, one token each: here the first-token step
+        // of a request whose KV is complete; (2) prefill of requests without a stored prefix, oldest
+        // first; (3) the rest to the prefix-cached request, as far as the plan gives it to the compute side
         parts.clear();
-        int left = token_budget, np_tokens = 0, first_np = -1, bg_tokens = 0;
+        int left = token_budget, np_tokens = 0, first_np = -1, bg_tokens = 0, dec_tokens = 0;
         if (!c->tr_other.empty()) {
             bg_tokens = std::min(left, c->tr_other[size_t(n_steps) % c->tr_other.size()]);
-            if (bg_tokens > 0) parts.push_back({-1, 0, bg_tokens});
+            if (bg_tokens > 0) parts.push_back({-1, 0, bg_tokens, false});
             left -= bg_tokens;
         }
         for (int k = 0; k < n_reqs && left > 0; ++k) {
             int i = order[k];
-            if (i == P || done[i] || reqs[i].arrival_ns > now) continue;
+            if (!ft_pending[i]) continue;
+            parts.push_back({i, reqs[i].n_tokens - 1, 1, true});
+            left -= 1; ++dec_tokens;
+        }
+        for (int k = 0; k < n_reqs && left > 0; ++k) {
+            int i = order[k];
+            if (i == P || done[i] || kv_complete[i] || reqs[i].arrival_ns > now) continue;
             int nt = std::min(left, reqs[i].n_tokens - next_tok[i]);
-            parts.push_back({i, next_tok[i], nt});
+            parts.push_back({i, next_tok[i], nt, false});
             if (first_np < 0) first_np = i;
             left -= nt; np_tokens += nt;
         }
         int got = 0, first = -1;
-        const bool prefix_live = P >= 0 && !done[P] && reqs[P].arrival_ns <= now;
+        const bool prefix_live = P >= 0 && !kv_complete[P] && reqs[P].arrival_ns <= now;
         if (prefix_live && left > 0) {
             std::lock_guard<std::mutex> g(ex.mu);
             ex.refresh_load_progress(be);
             got = ex.core.claim_front(now, left, &first);
             if (got > 0) { ++ex.gen; ex.cv.notify_all(); }
         }
-        if (got > 0) parts.push_back({P, first, got});
+        if (got > 0) parts.push_back({P, first, got, false});
 
         const bool only_background = parts.size() == 1 && parts[0].req == -1;
         bool prefix_finished_by_loader = false;
@@ -897,8 +913,7 @@ int32_t cake_adaptive_serve(cake_ctx* c, cake_request* reqs, int32_t n_reqs, int
             if (prefix_live && ex.core.range_empty() && !ex.core.w[W_LOAD].busy) {
                 uint64_t end = prefix_compute_end;
                 for (int i = 0; i < nc; ++i) if (ex.chunk_log[i].source == CAKE_SRC_LOAD) end = std::max(end, ex.chunk_log[i].end_ns);
-                reqs[P].ttft_ns = end - reqs[P].arrival_ns;
-                done[P] = 1; ++n_done;
+                finish_kv(P, end, &n_done);
                 continue;
             }
             if (ex.first_error != CAKE_OK) { hard = ex.first_error; break; }
@@ -916,20 +931,26 @@ int32_t cake_adaptive_serve(cake_ctx* c, cake_request* reqs, int32_t n_reqs, int
             const int32_t* ids = p.req < 0 ? c->tr_ids.data() : reqs[p.req].token_ids + p.first;
             const cake_kv* pkv = p.req < 0 ? &c->tr_kv : reqs[p.req].kv;
             if (hipMemcpyAsync(c->d_ids + p.first, ids, size_t(p.count) * 4, hipMemcpyHostToDevice, c->cs) != hipSuccess) { hard = CAKE_E_HIP; break; }
-            int rc = enqueue_prefill(c, p.first, p.count, pkv);
+            int rc = p.decode ? enqueue_first_token(c, reqs[p.req].n_tokens, pkv) : enqueue_prefill(c, p.first, p.count, pkv);
             if (rc != CAKE_OK) { hard = rc; break; }
+            // the token leaves the device before the next decode part overwrites it (one stream)
+            if (p.decode && hipMemcpyAsync(&ft_tok[p.req], c->t_tok, 4, hipMemcpyDeviceToHost, c->cs) != hipSuccess) { hard = CAKE_E_HIP; break; }
         }
         if (hard == CAKE_OK && hipStreamSynchronize(c->cs) != hipSuccess) hard = fail(c, CAKE_E_HIP, "compute stream failed in an adaptive step");
         const uint64_t t_end = ex.now();
         if (hard != CAKE_OK) break;
         for (const Part& p : parts) {
+            if (p.decode) {   // the first token is out: the request leaves
+                reqs[p.req].first_token = ft_tok[p.req];
+                reqs[p.req].ttft_ns = t_end - reqs[p.req].arrival_ns;
+                ft_pending[p.req] = 0;
+                done[p.req] = 1; ++n_done;
+                continue;
+            }
             if (p.req == P || p.req < 0) continue;
             next_tok[p.req] += p.count;
             reqs[p.req].tokens_computed += p.count;
-            if (next_tok[p.req] == reqs[p.req].n_tokens) {
-                reqs[p.req].ttft_ns = t_end - reqs[p.req].arrival_ns;
-                done[p.req] = 1; ++n_done;
-            }
+            if (next_tok[p.req] == reqs[p.req].n_tokens) finish_kv(p.req, t_end, &n_done);
         }
         if (prefix_live) {
             std::lock_guard<std::mutex> g(ex.mu);
@@ -958,7 +979,7 @@ int32_t cake_adaptive_serve(cake_ctx* c, cake_request* reqs, int32_t n_reqs, int
         if (steps) {
             if (n_steps < steps_cap) {
                 cake_step_log& sl = steps[n_steps];
-                sl.start_ns = now; sl.end_ns = t_end; sl.decode_tokens = 0; sl.nonprefix_tokens = np_tokens;
+                sl.start_ns = now; sl.end_ns = t_end; sl.decode_tokens = dec_tokens; sl.nonprefix_tokens = np_tokens;
                 sl.prefix_tokens = got; sl.prefix_tok_begin = got > 0 ? first : -1; sl.first_nonprefix_req = first_np; sl.other_tokens = bg_tokens;
             } else steps_overflow = true;
         }

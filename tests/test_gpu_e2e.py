@@ -547,7 +547,11 @@ def test_adaptive_scheduling_mix():
     res2, _, _ = run(step_after=1)
     assert _errs(eng.pool_images(T), want).max() < TOL["bf16"]
     _check_decisions(res2, shape, T, C, pt)
-    assert res2.meet_point > res.meet_point
+    # seen inside that run (two runs differ by more than the effect when the host hiccups): the plan
+    # after the drop puts the meet point further right than the plan at the start did, and the run ends there
+    stars = [d["m_star"] for d in res2.decisions]
+    assert max(stars[len(stars) // 2:]) > min(stars[:3]), stars
+    assert res2.meet_point > min(stars[:3]), (res2.meet_point, stars)
 
 
 # --------------------------------------------------------------------------- first token
@@ -604,6 +608,73 @@ def test_first_token_needs_head_weights():
     with pytest.raises(cake.CakeError) as e:
         eng.first_token(toks)
     assert e.value.code == cake.E_STATE
+
+
+def test_adaptive_mode_serves_first_tokens_at_priority_one():
+    """Sec. 4 Part 3: decode tokens come first in every engine step.  Here the decode step of a
+    request is its first-token step, taken in the engine step after its KV is complete.  Tokens and
+    budget order against the oracle; the prefix request's KV is raced as before."""
+    import paper_2410_03065_amd as cake
+    shape = si.TINY.with_(vocab=1000)
+    T, unit, budget, pt = 2048, 256, 256, 128
+    w = si.make_weights(shape, seed=80, with_head=True)
+    eng = cake.Engine(shape, w, max_tokens=T, max_chunk=budget, page_tokens=pt)
+    toks = si.make_tokens(T, shape.vocab, seed=81)
+    ref = otf.prefill_chunked(w, shape, toks, unit, kv_dtype="f32")
+    images = ostore.pack_store(ref, pt, "f32")
+    eng.set_store(images)
+    eng.bidirectional_prefill(toks, unit, 4.0, mode="compute_only")
+    r_c = eng.bidirectional_prefill(toks, unit, 4.0, mode="compute_only")
+    rate = T * otf.kv_bytes_per_token(shape.n_layers, shape.n_kv, shape.head_dim, 4) / r_c.ttft_ns
+    others = []
+    for j, n_tok in enumerate((300, 700)):
+        kv, pool = eng.new_kv(n_tok)
+        others.append(dict(tokens=si.make_tokens(n_tok, shape.vocab, seed=90 + j), arrival_ns=0, prefix=False, kv=kv, pool=pool,
+                           first_token=True))
+    reqs = others + [dict(tokens=toks, arrival_ns=0, prefix=True, first_token=True)]
+    eng.adaptive_serve(reqs, budget, unit, rate)                           # first use: set-up
+    eng.clear_pool()
+    for o in others:
+        o["pool"].zero_()
+    res, per_req, steps = eng.adaptive_serve(reqs, budget, unit, rate)
+    # every request's first token: a logit the oracle cannot tell from its maximum (exactly its argmax when the margin allows)
+    for r, out in zip(reqs, per_req):
+        t = np.asarray(r["tokens"])
+        cache = otf.prefill_chunked(w, shape, t, unit, kv_dtype="f32")
+        want = otf.first_token_logits(w, shape, t, cache)
+        tok = out["first_token"]
+        assert 0 <= tok < shape.vocab
+        assert want[tok] >= want.max() - 2 * TOL["f32"] * np.abs(want).max()
+        if np.sort(want)[-1] - np.sort(want)[-2] > 2 * TOL["f32"] * np.abs(want).max():
+            assert tok == otf.greedy_token(want)
+        assert out["ttft_ns"] > 0
+    # the same tokens as the stand-alone first-token call on the finished cache of the prefix request
+    assert per_req[2]["first_token"] == eng.first_token(toks)[0]
+    assert _errs(eng.pool_images(T), ostore.decode_words(images, "f32")).max() < TOL["f32"]
+    # budget order of every step by the oracle's rule: decode first, then the two others in order, then the prefix request
+    remaining = [300, 700]
+    waiting = 0                                 # requests without a stored prefix whose KV is complete: first token due
+    prefix_decode_steps = []
+    for k, s in enumerate(steps):
+        dec, grants, pref = mp.fill_token_budget(budget, s["decode_tokens"], [r for r in remaining if r > 0], 10 ** 9)
+        assert s["decode_tokens"] == dec and s["decode_tokens"] - waiting in (0, 1), (k, s, waiting)
+        if s["decode_tokens"] - waiting == 1:   # the prefix request's first token rode along
+            prefix_decode_steps.append(k)
+        assert s["nonprefix_tokens"] == sum(grants) and s["prefix_tokens"] <= pref
+        waiting, g = 0, iter(grants)
+        for j in range(2):
+            if remaining[j] > 0:
+                remaining[j] -= next(g)
+                waiting += remaining[j] == 0
+    # three first tokens in all; the prefix request's came once, after its last prefill tokens
+    assert sum(s["decode_tokens"] for s in steps) == 3 and remaining == [0, 0]
+    assert len(prefix_decode_steps) == 1 and all(s["prefix_tokens"] == 0 for s in steps[prefix_decode_steps[0]:])
+    # without the head the request is refused
+    eng2 = cake.Engine(shape, si.make_weights(shape, seed=80), max_tokens=T, max_chunk=budget, page_tokens=pt)
+    eng2.set_store(images)
+    with pytest.raises(cake.CakeError) as ei:
+        eng2.adaptive_serve([dict(tokens=toks, arrival_ns=0, prefix=True, first_token=True)], budget, unit, rate)
+    assert ei.value.code == cake.E_STATE
 
 
 # --------------------------------------------------------------------------- fetch unit finer than the compute step

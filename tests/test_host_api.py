@@ -29,7 +29,7 @@ def test_library_exports_every_declared_symbol():
 def test_struct_sizes_match_the_header_layout():
     assert ctypes.sizeof(cake.ChunkLog) == 48
     assert ctypes.sizeof(cake.DecisionLog) == 96
-    assert ctypes.sizeof(cake.Request) == 56
+    assert ctypes.sizeof(cake.Request) == 64
     assert ctypes.sizeof(cake.StepLog) == 40
     assert ctypes.sizeof(cake.ModelDesc) == 40
     assert ctypes.sizeof(cake.Tuning) == 40
