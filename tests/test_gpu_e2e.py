@@ -17,6 +17,14 @@ pytestmark = pytest.mark.gpu
 TOL = {"f32": 1e-4, "bf16": 2e-2}
 
 
+def _settle():
+    """The oracle's BLAS worker threads spin on every CPU for tens of milliseconds after a matrix
+    product; a race that is timed in microseconds waits that out (its load worker would otherwise
+    not get a CPU before the compute side has finished a short prompt)."""
+    import time
+    time.sleep(0.25)
+
+
 def _errs(got, want):
     """max-abs error over max-abs reference, per (layer, K|V)."""
     num = np.abs(got - want).max(axis=(0, 3))
@@ -312,6 +320,7 @@ def test_load_failure_is_recomputed(tmp_path):
     want = ostore.decode_words(images, "bf16")
     stride = images[0].size * 2
     eng.set_store(images)
+    _settle()
     eng.bidirectional_prefill(toks, C, 4.0, mode="greedy")          # first race of this process: runtime set-up on the loader's thread
     fd, n_pages, stride = _file_store(tmp_path, images, keep_bytes=28 * stride + 1000)   # pages 28..31 (= chunk 7) are cut off
     eng.set_file_store(fd, n_pages, stride)
@@ -491,6 +500,7 @@ def test_adaptive_scheduling_mix():
     images = ostore.pack_store(ref, pt, "bf16")
     want = ostore.decode_words(images, "bf16")
     eng.set_store(images)
+    _settle()
     eng.bidirectional_prefill(toks, C, 4.0, mode="compute_only")          # first-launch costs stay out of the rate
     r_c = eng.bidirectional_prefill(toks, C, 4.0, mode="compute_only")
     kv_bytes = T * otf.kv_bytes_per_token(shape.n_layers, shape.n_kv, shape.head_dim, 2)
@@ -623,6 +633,7 @@ def test_adaptive_mode_serves_first_tokens_at_priority_one():
     ref = otf.prefill_chunked(w, shape, toks, unit, kv_dtype="f32")
     images = ostore.pack_store(ref, pt, "f32")
     eng.set_store(images)
+    _settle()
     eng.bidirectional_prefill(toks, unit, 4.0, mode="compute_only")
     r_c = eng.bidirectional_prefill(toks, unit, 4.0, mode="compute_only")
     rate = T * otf.kv_bytes_per_token(shape.n_layers, shape.n_kv, shape.head_dim, 4) / r_c.ttft_ns
@@ -695,6 +706,7 @@ def test_fetch_unit_smaller_than_compute_step(shape, T, step, unit):
     images = ostore.pack_store(ref, pt, "bf16")
     want = ostore.decode_words(images, "bf16")
     eng.set_store(images)
+    _settle()
     eng.bidirectional_prefill(toks, step, 4.0, mode="compute_only")
     r_c = eng.bidirectional_prefill(toks, step, 4.0, mode="compute_only")
     kv_bytes = T * otf.kv_bytes_per_token(shape.n_layers, shape.n_kv, shape.head_dim, 2)
@@ -727,6 +739,7 @@ def _trace_setup(T=8192, step=1024, unit=256):
     ref = otf.prefill_chunked(w, shape, toks, step, kv_dtype="bf16")
     images = ostore.pack_store(ref, pt, "bf16")
     eng.set_store(images)
+    _settle()
     eng.bidirectional_prefill(toks, step, 4.0, mode="compute_only")
     r_c = eng.bidirectional_prefill(toks, step, 4.0, mode="compute_only")
     rate = T * otf.kv_bytes_per_token(shape.n_layers, shape.n_kv, shape.head_dim, 2) / r_c.ttft_ns
@@ -927,6 +940,7 @@ def test_bidirectional_with_int8_store_moves_the_meet_point_left():
     img8 = ostore.pack_store_int8(ref, pt)
     deq = ostore.pack_store(ostore.unpack_store_int8(img8, T, shape.n_kv, shape.head_dim, pt, "bf16"), pt, "bf16")
     eng.set_store(raw)
+    _settle()
     eng.bidirectional_prefill(toks, C, 4.0, mode="compute_only")
     r_c = eng.bidirectional_prefill(toks, C, 4.0, mode="compute_only")
     # a tier somewhat slower than this GPU computes 16-bit KV: the transfer outweighs the fixed cost of a load
