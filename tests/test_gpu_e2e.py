@@ -927,6 +927,38 @@ def C_byref_model(eng):
     return ctypes.byref(cake.model_desc(eng.shape))
 
 
+def test_adaptive_engine_with_a_file_backed_4bit_store(tmp_path):
+    """Everything at once: the adaptive engine (fetch unit = one page, compute steps of four pages) races a
+    loader that preads 4-bit page images from a file.  Loaded units are the oracle's dequantisation of the stored
+    codes bit for bit, computed units are the compute-only bytes, every decision replays."""
+    import os
+    import paper_2410_03065_amd as cake
+    shape, T, step, unit = BF_NARROW_GQA4, 8192, 1024, 256
+    eng = cake.Engine(shape, None, max_tokens=T, max_chunk=step, page_tokens=unit, seed=6)
+    toks = si.make_tokens(T, shape.vocab, seed=7)
+    eng.bidirectional_prefill(toks, step, 4.0, mode="compute_only")
+    r_c = eng.bidirectional_prefill(toks, step, 4.0, mode="compute_only")
+    full = eng.pool_raw(T).copy()
+    img4 = eng.write_store(T, cake.STORE_INT4).numpy().copy().reshape(T // unit, shape.n_layers, 2, -1)
+    deq = ostore.pack_store(ostore.unpack_store_int4(img4, T, shape.n_kv, shape.head_dim, unit, "bf16"), unit, "bf16")
+    fd, n_pages, stride = _file_store(tmp_path, img4, name="q4.bin")
+    eng.set_file_store(fd, n_pages, stride, cake.STORE_INT4)
+    rate = 0.5 * T * otf.kv_bytes_per_token(shape.n_layers, shape.n_kv, shape.head_dim, 2) / r_c.ttft_ns
+    reqs = [dict(tokens=toks, arrival_ns=0, prefix=True)]
+    eng.adaptive_serve(reqs, step, unit, rate)
+    eng.clear_pool()
+    res, per_req, steps = eng.adaptive_serve(reqs, step, unit, rate)
+    m = res.meet_point
+    assert 0 < m < T // unit and per_req[0]["tokens_computed"] == m * unit and per_req[0]["tokens_loaded"] == T - m * unit
+    raw = eng.pool_raw(T)
+    np.testing.assert_array_equal(raw[:m], full[:m])
+    np.testing.assert_array_equal(raw[m:].view(np.uint16), deq[m:])
+    per_page = ostore.int4_image_bytes(shape.n_layers, shape.n_kv, shape.head_dim, unit)
+    assert res.load_bytes == (T // unit - m) * per_page
+    _check_decisions(res, shape, T, unit, unit, step_tokens=step, page_bytes=per_page)
+    os.close(fd)
+
+
 def test_bidirectional_with_int8_store_moves_the_meet_point_left():
     """Sec. 5.5: the same tier bandwidth with an 8-bit store.  Computed chunks match the oracle's
     bf16 KV as before, loaded chunks are the dequantised store (within half a quantisation step of
