@@ -138,6 +138,9 @@ def main():
     dom_stats = eng.profile_read() if not args.no_profile else {}
     eng.profile_enable(False)
 
+    # yardstick: bf16 MFMAs on register operands only, every CU busy for ~10 ms (median of three)
+    mfma_only = sorted(eng.mfma_rate(2048, 4096) for _ in range(3))[1]
+
     # first-token step on the complete cache (reported beside the headline value, not inside it)
     eng.first_token(toks)
     if not args.no_profile:
@@ -251,6 +254,9 @@ def main():
                                             "(that pass runs ~10 % slower); roofline.achieved is from the timed region",
         "first_token": dict(first_token, ttft_to_first_token_s=round(ttft + ft_wall, 5)),
         "fine_fetch_unit": fine,
+        "mfma_only": {"tflops": round(mfma_only, 1), "frac_of_peak": round(mfma_only / PEAK_BF16_TFLOPS, 4),
+                      "what": "bf16 32x32x16 MFMAs on register operands, no memory traffic: what the matrix pipes of "
+                              "this GPU deliver under its power limit (cake_op_mfma_rate)"},
         "int8_store": int8_store,
         "int4_store": int4_store,
         "roofline": roofline,

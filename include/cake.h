@@ -450,6 +450,11 @@ int32_t cake_op_gemm(cake_ctx* ctx, const void* a, const void* w, float* out,
 /* x[M][N] (float32) += a[M][K] * w[N][K]^T */
 int32_t cake_op_gemm_residual(cake_ctx* ctx, const void* a, const void* w, float* x,
                               int32_t M, int32_t N, int32_t K);
+/* Yardstick, not part of the method: `workgroups` workgroups of eight waves each run `iters` rounds of
+ * eight independent bf16 MFMAs on register operands (no memory traffic); *tflops = what the matrix pipes
+ * of this GPU delivered for that (host).  Blocking; uses the context's activation workspace.
+ * Errors: CAKE_E_INVAL (sizes), CAKE_E_HIP. */
+int32_t cake_op_mfma_rate(cake_ctx* ctx, int32_t workgroups, int32_t iters, double* tflops);
 /* out[M][N] = silu(a*wg^T) .* (a*wu^T), element type out */
 int32_t cake_op_gemm_swiglu(cake_ctx* ctx, const void* a, const void* wg, const void* wu,
                             void* out, int32_t M, int32_t N, int32_t K);

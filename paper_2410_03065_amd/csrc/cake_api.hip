@@ -1099,6 +1099,22 @@ int32_t cake_op_gemm_residual(cake_ctx* c, const void* a, const void* w, float* 
     return CAKE_OK;
 }
 
+int32_t cake_op_mfma_rate(cake_ctx* c, int32_t workgroups, int32_t iters, double* tflops) {
+    if (!c || !tflops || workgroups <= 0 || workgroups > 65536 || iters <= 0 || iters > (1 << 22)) return CAKE_E_INVAL;
+    // one float per wave, written into the float32 qkv workspace (at least max_chunk * 3 * head_dim floats)
+    const size_t room = size_t(c->max_chunk) * size_t(c->m.n_q_heads + 2 * c->m.n_kv_heads) * c->m.head_dim;
+    if (size_t(workgroups) * 8 > room) return fail(c, CAKE_E_INVAL, "mfma_rate: %d workgroups need %zu floats of workspace", workgroups, size_t(workgroups) * 8);
+    HIP_TRY(c, launch_mfma_rate(c->qkv, workgroups, std::max(1, iters / 8), c->cs));   // clocks up
+    HIP_TRY(c, hipEventRecord(c->ev_a, c->cs));
+    HIP_TRY(c, launch_mfma_rate(c->qkv, workgroups, iters, c->cs));
+    HIP_TRY(c, hipEventRecord(c->ev_b, c->cs));
+    HIP_TRY(c, hipStreamSynchronize(c->cs));
+    float ms = 0.f;
+    HIP_TRY(c, hipEventElapsedTime(&ms, c->ev_a, c->ev_b));
+    *tflops = ms > 0.f ? double(workgroups) * 8.0 * iters * 8.0 * 32768.0 / (double(ms) * 1e-3) / 1e12 : 0.0;
+    return CAKE_OK;
+}
+
 int32_t cake_op_gemm_swiglu(cake_ctx* c, const void* a, const void* wg, const void* wu, void* out, int32_t M,
                             int32_t N, int32_t K) {
     if (!c || !a || !wg || !wu || !out || M < 0 || N <= 0 || K <= 0 || (K & 7)) return CAKE_E_INVAL;

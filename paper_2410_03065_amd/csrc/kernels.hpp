@@ -42,6 +42,8 @@ bool gemm_mfma_supported(int epi, int M, int N, int K);
 // cfg_override: -1 = choose the tile configuration from the shape; 0..2 = force one (testing).
 hipError_t launch_gemm_mfma(int epi, const void* a, const void* w, const void* w2, void* out,
                             int M, int N, int K, hipStream_t st, int cfg_override = -1);
+// MFMA-only yardstick kernel: out holds workgroups * 8 floats; see kernels_gemm.hip.
+hipError_t launch_mfma_rate(float* out, int workgroups, int iters, hipStream_t st);
 bool attention_mfma_supported(int head_dim, int page_tokens);
 // variant: 0 = eight-wave kernel, 128 or 64 queries per workgroup by grid size; 1 = four-wave kernel;
 // 2 / 3 = eight-wave kernel with 128 / 64 queries per workgroup (testing).

@@ -203,6 +203,58 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
     }
 }
 
+// =====================================================================================
+// Yardstick: what the matrix pipes deliver with nothing else going on.  Every wave runs `iters`
+// rounds of eight independent 32x32x16 bf16 MFMAs on operands it keeps in registers (no memory
+// traffic, no LDS, no barriers); one value per wave is written so that the work is not dead.
+// `acc[lane & 15]` at the end indexes a vector dynamically; the loop above keeps it in registers.
+// =====================================================================================
+__global__ void __launch_bounds__(512)
+mfma_rate_kernel(float* __restrict__ out, int iters, unsigned seed) {
+    const int lane = threadIdx.x & 63;
+    // operands with the statistics of real data (what the pipes draw depends on how many bits toggle):
+    // hashed values spread over [-2, 2), a different register set for every MFMA of a round, laid out
+    // like one wave's 128x64 tile of the GEMM above (four A fragments, two B fragments)
+    auto rnd = [&](unsigned k) {
+        unsigned h = (k + seed) * 2654435761u; h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
+        return bf16_t(float(int(h & 0xffff) - 32768) * (1.0f / 16384.0f));
+    };
+    bf16x8 a[4], b[2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) a[i][e] = rnd(unsigned((threadIdx.x * 4 + i) * 8 + e));
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) b[j][e] = rnd(0x9e3779b9u + unsigned((threadIdx.x * 2 + j) * 8 + e));
+    f32x16 acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) acc[i][j] = mfma32(a[i], b[j], acc[i][j]);
+    }
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) sum += acc[i][j][lane & 15];
+    if (lane == 0) out[(size_t(blockIdx.x) * blockDim.x + threadIdx.x) >> 6] = sum;
+}
+
+// grid: `workgroups` workgroups of eight waves.  FLOPs = workgroups * 8 * iters * 8 * 32768.
+hipError_t launch_mfma_rate(float* out, int workgroups, int iters, hipStream_t st) {
+    hipLaunchKernelGGL(mfma_rate_kernel, dim3(workgroups), dim3(512), 0, st, out, iters, 12345u);
+    return hipGetLastError();
+}
+
 // Tile configurations.  Chosen per GEMM by gemm_pick() from how well the grid fills 256 CUs.
 struct GemmCfg { int bm, bn; };
 enum { GCFG_256x256 = 0, GCFG_256x128 = 1, GCFG_128x128 = 2, GCFG_128x192 = 3, GCFG_128x64 = 4, GCFG_COUNT = 5 };

@@ -209,3 +209,16 @@ def test_decode_attention(kind, path, shape_kw, T, pt):
     # MFMA path: q and the probabilities are rounded to bf16 (2^-9 each); others are float32 throughout
     tol = 1.2e-2 if (kind == "bf16" and path == 0) else 2e-5
     assert _rel(got, want) < tol, _rel(got, want)
+
+
+def test_mfma_rate_yardstick():
+    """The MFMA-only kernel reports a rate between a quarter of the nominal bf16 peak and the peak itself,
+    and refuses sizes beyond its workspace."""
+    import paper_2410_03065_amd as cake
+    eng = _engine(SHAPE_BF, 256, 256, 128)
+    r = eng.mfma_rate(512, 2048)
+    assert 600.0 < r < 2600.0, r
+    with pytest.raises(cake.CakeError):
+        eng.mfma_rate(60000, 16)
+    with pytest.raises(cake.CakeError):
+        eng.mfma_rate(0, 16)
