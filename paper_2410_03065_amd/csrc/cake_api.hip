@@ -259,14 +259,17 @@ static hipError_t drain_copy_stream(cake_ctx* c) {
     hipError_t e = hipEventRecord(c->ev_load, c->ls);
     if (e != hipSuccess) return e;
     const uint64_t t0 = mono_ns();
+    bool polled_not_ready = false;
     for (;;) {
         e = hipEventQuery(c->ev_load);
-        if (e != hipErrorNotReady) return e;
+        if (e != hipErrorNotReady) break;
+        polled_not_ready = true;
         if (mono_ns() - t0 > 300000) break;
         std::this_thread::yield();
     }
-    (void)hipGetLastError();   // hipErrorNotReady is sticky for hipGetLastError only; clear it
-    return hipEventSynchronize(c->ev_load);
+    // "not ready" is an answer, not a failure: it must not be what a later hipGetLastError() on this thread reports
+    if (polled_not_ready) (void)hipGetLastError();
+    return e == hipErrorNotReady ? hipEventSynchronize(c->ev_load) : e;
 }
 
 // The tier's rate right now: the bandwidth trace if one is running (never below 0.01 GB/s, so a
