@@ -39,7 +39,7 @@ hipError_t launch_attention_generic(int dtype, const void* q, void* out, int n_q
 
 // ---- MFMA kernels (bf16) ----
 bool gemm_mfma_supported(int epi, int M, int N, int K);
-// cfg_override: -1 = choose the tile configuration from the shape; 0..2 = force one (testing).
+// cfg_override: -1 = choose the tile configuration from the shape; 0..4 = force one (testing).
 hipError_t launch_gemm_mfma(int epi, const void* a, const void* w, const void* w2, void* out,
                             int M, int N, int K, hipStream_t st, int cfg_override = -1);
 // MFMA-only yardstick kernel: out holds workgroups * 8 floats; see kernels_gemm.hip.
