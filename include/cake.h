@@ -212,7 +212,8 @@ typedef struct {
     int32_t gemm_config; /* 0: tile shape chosen per GEMM; 1..5: force 256x256 / 256x128 / 128x128 / 128x192 / 128x64 (testing) */
     int32_t attn_variant; /* 0: eight-wave attention kernel, 128 or 64 queries per workgroup by grid size;
                              1: four-wave kernel; 2 / 3: eight-wave with 128 / 64 queries (testing) */
-    int32_t pad_;
+    int32_t gemm_ksplit; /* 0: K of the residual / plain GEMMs split over 2, 4 or 8 workgroups per tile where a cost
+                            model says so (few large tiles); 1: never; 2 / 4 / 8: that many wherever legal (testing) */
 } cake_tuning;
 
 /* ---- life cycle ------------------------------------------------------- */
@@ -450,6 +451,11 @@ int32_t cake_op_gemm(cake_ctx* ctx, const void* a, const void* w, float* out,
 /* x[M][N] (float32) += a[M][K] * w[N][K]^T */
 int32_t cake_op_gemm_residual(cake_ctx* ctx, const void* a, const void* w, float* x,
                               int32_t M, int32_t N, int32_t K);
+/* Which kernel cake_op_gemm (residual = 0) or cake_op_gemm_residual (residual = 1) would launch for this
+ * shape with the context's tuning: tile[0] x tile[1] = workgroup tile (0 x 0: the generic kernel), *ksplit =
+ * K ranges per tile.  Host pointers; pure.  Errors: CAKE_E_INVAL. */
+int32_t cake_op_gemm_plan(cake_ctx* ctx, int32_t residual, int32_t M, int32_t N, int32_t K,
+                          int32_t tile[2], int32_t* ksplit);
 /* Yardstick, not part of the method: `workgroups` workgroups of eight waves each run `iters` rounds of
  * eight independent bf16 MFMAs on register operands (no memory traffic); *tflops = what the matrix pipes
  * of this GPU delivered for that (host).  Blocking; uses the context's activation workspace.

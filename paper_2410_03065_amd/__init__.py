@@ -29,7 +29,7 @@ EXPORTS = [
     "cake_load_chunk", "cake_plan_meet_point", "cake_bidirectional_prefill", "cake_set_bandwidth",
     "cake_schedule_bandwidth_step", "cake_chunk_state", "cake_sync_compute", "cake_sync_load",
     "cake_range_flops", "cake_page_image_bytes", "cake_simulate_race", "cake_op_rmsnorm",
-    "cake_op_gemm", "cake_op_gemm_residual", "cake_op_gemm_swiglu", "cake_op_mfma_rate", "cake_op_rope_kv_write",
+    "cake_op_gemm", "cake_op_gemm_residual", "cake_op_gemm_swiglu", "cake_op_gemm_plan", "cake_op_mfma_rate", "cake_op_rope_kv_write",
     "cake_op_attention", "cake_profile_enable", "cake_profile_read", "cake_adaptive_serve", "cake_first_token",
     "cake_op_decode_attention", "cake_set_traces", "cake_store_image_bytes", "cake_write_store", "cake_prefix_keys", "cake_prefix_lookup",
 ]
@@ -117,7 +117,7 @@ class KernelStats(C.Structure):
 
 class Tuning(C.Structure):
     _fields_ = [("prior_compute_ns", C.c_uint64), ("prior_compute_flops", C.c_uint64), ("piece_bytes", C.c_uint64),
-                ("kernel_path", C.c_int32), ("gemm_config", C.c_int32), ("attn_variant", C.c_int32), ("pad_", C.c_int32)]
+                ("kernel_path", C.c_int32), ("gemm_config", C.c_int32), ("attn_variant", C.c_int32), ("gemm_ksplit", C.c_int32)]
 
 
 def load_library():
@@ -162,6 +162,7 @@ def load_library():
         "cake_op_gemm": (i32, [vp, vp, vp, vp, i32, i32, i32]),
         "cake_op_gemm_residual": (i32, [vp, vp, vp, vp, i32, i32, i32]),
         "cake_op_gemm_swiglu": (i32, [vp, vp, vp, vp, vp, i32, i32, i32]),
+        "cake_op_gemm_plan": (i32, [vp, i32, i32, i32, i32, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
         "cake_op_mfma_rate": (i32, [vp, i32, i32, P(C.c_double)]),
         "cake_op_rope_kv_write": (i32, [vp, vp, vp, i32, i32, i32, P(Kv)]),
         "cake_op_attention": (i32, [vp, vp, vp, i32, i32, i32, P(Kv)]),
@@ -458,8 +459,8 @@ class Engine:
         return rc
 
     def set_tuning(self, prior_compute_ns=0, prior_compute_flops=0, piece_bytes=0, kernel_path=0, gemm_config=0,
-                   attn_variant=0):
-        t = Tuning(prior_compute_ns, prior_compute_flops, piece_bytes, kernel_path, gemm_config, attn_variant, 0)
+                   attn_variant=0, gemm_ksplit=0):
+        t = Tuning(prior_compute_ns, prior_compute_flops, piece_bytes, kernel_path, gemm_config, attn_variant, gemm_ksplit)
         self._check(self.lib.cake_set_tuning(self.ctx, C.byref(t)), "cake_set_tuning")
 
     def _ids(self, tokens):
@@ -650,6 +651,13 @@ class Engine:
                                                    w.shape[0], a.shape[1]), "cake_op_gemm_residual")
         self.sync()
         return x
+
+    def op_gemm_plan(self, M, N, K, residual=True):
+        """(tile rows, tile columns, K ranges per tile) of the GEMM kernel chosen for this shape."""
+        tile = (C.c_int32 * 2)()
+        ks = C.c_int32(0)
+        self._check(self.lib.cake_op_gemm_plan(self.ctx, int(bool(residual)), M, N, K, tile, C.byref(ks)), "cake_op_gemm_plan")
+        return tile[0], tile[1], ks.value
 
     def op_gemm_swiglu(self, a, wg, wu):
         out = self.torch.empty((a.shape[0], wg.shape[0]), dtype=self.tdtype, device=self.dev)

@@ -45,6 +45,7 @@ struct cake_ctx {
     float *t_h = nullptr, *t_q = nullptr, *t_qr = nullptr, *t_ao = nullptr, *t_act = nullptr, *t_logits = nullptr,
           *t_part = nullptr;
     int32_t* t_tok = nullptr;
+    GemmSplitWs split{};       // parts and ticket counters of the split-K GEMMs (bf16 models; compute stream only)
     void* q_stage = nullptr;   // device staging for quantised page images (allocated at the first use)
     size_t q_stage_bytes = 0;
     // second hop of a file-backed store: two pinned buffers of one DMA piece each
@@ -143,7 +144,8 @@ static KvView make_view(const cake_ctx* c, const cake_kv* kv, int layer) {
 // ------------------------------------------------------------------ kernel dispatch
 static hipError_t gemm(cake_ctx* c, int epi, const void* a, const void* w, const void* w2, void* out, int M, int N, int K) {
     if (c->m.dtype == CAKE_BF16 && c->tun.kernel_path == 0 && gemm_mfma_supported(epi, M, N, K))
-        return launch_gemm_mfma(epi, a, w, w2, out, M, N, K, c->cs, c->tun.gemm_config - 1);
+        return launch_gemm_mfma(epi, a, w, w2, out, M, N, K, c->cs, c->tun.gemm_config - 1, c->split.part ? &c->split : nullptr,
+                                c->tun.gemm_ksplit);
     return launch_gemm_generic(c->m.dtype, epi, a, w, w2, out, M, N, K, c->cs);
 }
 
@@ -483,6 +485,15 @@ int32_t cake_create(cake_ctx** out, const cake_model_desc* model, const cake_wei
     ok = ok && hipMalloc(&c->act, R * m.ffn_dim * e) == hipSuccess;
     ok = ok && hipMalloc((void**)&c->rope_cs, R * m.head_dim * 4) == hipSuccess;
     ok = ok && hipMalloc((void**)&c->d_ids, size_t(max_tokens) * 4) == hipSuccess;
+    if (m.dtype == CAKE_BF16) {
+        // room for 256 workgroups' float32 tiles of 256 x 256, less for a small model
+        const size_t rows_up = (R + 255) / 256 * 256;
+        c->split.part_bytes = std::min<size_t>(size_t(64) << 20, 8 * rows_up * std::max<size_t>(m.d_model, nqkv) * 4);
+        c->split.n_counters = 1024;
+        ok = ok && hipMalloc((void**)&c->split.part, c->split.part_bytes) == hipSuccess;
+        ok = ok && hipMalloc((void**)&c->split.counters, size_t(c->split.n_counters) * 4) == hipSuccess;
+        ok = ok && hipMemset(c->split.counters, 0, size_t(c->split.n_counters) * 4) == hipSuccess;
+    }
     ok = ok && hipEventCreate(&c->ev_a) == hipSuccess && hipEventCreate(&c->ev_b) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&c->ev_load, hipEventBlockingSync | hipEventDisableTiming) == hipSuccess;
     if (weights->final_norm && weights->lm_head) {
@@ -519,7 +530,7 @@ int32_t cake_destroy(cake_ctx* c) {
     (void)hipFree(c->ao); (void)hipFree(c->act); (void)hipFree(c->rope_cs); (void)hipFree(c->d_ids);
     (void)hipFree(c->t_h); (void)hipFree(c->t_q); (void)hipFree(c->t_qr); (void)hipFree(c->t_ao);
     (void)hipFree(c->t_act); (void)hipFree(c->t_logits); (void)hipFree(c->t_part); (void)hipFree(c->t_tok);
-    (void)hipFree(c->q_stage);
+    (void)hipFree(c->q_stage); (void)hipFree(c->split.part); (void)hipFree(c->split.counters);
     for (int i = 0; i < 2; ++i)
         if (c->f_stage[i]) (void)hipHostFree(c->f_stage[i]);
     for (hipEvent_t e : c->prof_events) (void)hipEventDestroy(e);
@@ -548,6 +559,9 @@ int32_t cake_set_tuning(cake_ctx* c, const cake_tuning* t) {
     c->tun.gemm_config = t->gemm_config;
     if (t->attn_variant < 0 || t->attn_variant > 3) return fail(c, CAKE_E_INVAL, "attn_variant must be 0..3");
     c->tun.attn_variant = t->attn_variant;
+    if (t->gemm_ksplit != 0 && t->gemm_ksplit != 1 && t->gemm_ksplit != 2 && t->gemm_ksplit != 4 && t->gemm_ksplit != 8)
+        return fail(c, CAKE_E_INVAL, "gemm_ksplit must be 0, 1, 2, 4 or 8");
+    c->tun.gemm_ksplit = t->gemm_ksplit;
     return CAKE_OK;
 }
 
@@ -1099,6 +1113,18 @@ int32_t cake_op_gemm(cake_ctx* c, const void* a, const void* w, float* out, int3
 int32_t cake_op_gemm_residual(cake_ctx* c, const void* a, const void* w, float* x, int32_t M, int32_t N, int32_t K) {
     if (!c || !a || !w || !x || M < 0 || N <= 0 || K <= 0 || (K & 7)) return CAKE_E_INVAL;
     HIP_TRY(c, gemm(c, EPI_RESIDUAL_F32, a, w, nullptr, x, M, N, K));
+    return CAKE_OK;
+}
+
+int32_t cake_op_gemm_plan(cake_ctx* c, int32_t residual, int32_t M, int32_t N, int32_t K, int32_t tile[2], int32_t* ksplit) {
+    if (!c || !tile || !ksplit || M < 0 || N <= 0 || K <= 0) return CAKE_E_INVAL;
+    const int epi = residual ? EPI_RESIDUAL_F32 : EPI_STORE_F32;
+    tile[0] = tile[1] = 0; *ksplit = 1;
+    if (c->m.dtype == CAKE_BF16 && c->tun.kernel_path == 0 && gemm_mfma_supported(epi, M, N, K)) {
+        int bm, bn, ks;
+        gemm_mfma_plan(epi, M, N, K, c->tun.gemm_config - 1, c->split.part ? &c->split : nullptr, c->tun.gemm_ksplit, &bm, &bn, &ks);
+        tile[0] = bm; tile[1] = bn; *ksplit = ks;
+    }
     return CAKE_OK;
 }
 

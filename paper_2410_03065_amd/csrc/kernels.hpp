@@ -39,9 +39,23 @@ hipError_t launch_attention_generic(int dtype, const void* q, void* out, int n_q
 
 // ---- MFMA kernels (bf16) ----
 bool gemm_mfma_supported(int epi, int M, int N, int K);
-// cfg_override: -1 = choose the tile configuration from the shape; 0..4 = force one (testing).
+// Workspace of the split-K GEMMs: float32 parts of the tiles in flight, and one ticket counter per
+// tile (zero between launches: the kernel puts it back).  Launches sharing it must not overlap.
+struct GemmSplitWs {
+    float* part;
+    size_t part_bytes;
+    unsigned* counters;
+    int n_counters;
+};
+// cfg_override: -1 = choose the tile configuration from the shape; 0..4 = force one, unsplit (testing).
+// ws: nullptr = never split K.  ksplit_override: 0 = by the cost model, 1 = never, 2/4/8 = that
+// many K ranges wherever the shape and the workspace allow it.
 hipError_t launch_gemm_mfma(int epi, const void* a, const void* w, const void* w2, void* out,
-                            int M, int N, int K, hipStream_t st, int cfg_override = -1);
+                            int M, int N, int K, hipStream_t st, int cfg_override = -1,
+                            const GemmSplitWs* ws = nullptr, int ksplit_override = 0);
+// What launch_gemm_mfma would launch: tile rows / columns and K ranges per tile.
+void gemm_mfma_plan(int epi, int M, int N, int K, int cfg_override, const GemmSplitWs* ws, int ksplit_override,
+                    int* bm, int* bn, int* ksplit);
 // MFMA-only yardstick kernel: out holds workgroups * 8 floats; see kernels_gemm.hip.
 hipError_t launch_mfma_rate(float* out, int workgroups, int iters, hipStream_t st);
 bool attention_mfma_supported(int head_dim, int page_tokens);

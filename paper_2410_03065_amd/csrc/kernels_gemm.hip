@@ -4,6 +4,8 @@
 // MFMA shape used throughout: v_mfma_f32_32x32x16_bf16.  For D[32x32] += A[32x16] * B[16x32]
 // lane l supplies A[l%32][8*(l/32) .. +7] and B[8*(l/32) .. +7][l%32], and holds
 // D[8*(v/4) + 4*(l/32) + v%4][l%32] in accumulator register v (0..15).
+#include <type_traits>
+
 #include "kernels.hpp"
 
 namespace cake {
@@ -11,6 +13,7 @@ namespace cake {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
@@ -40,6 +43,14 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 // Epilogues: store float32; add into a float32 residual stream; SwiGLU, where each wave's
 // n-tiles alternate gate / up rows of the two weight matrices, so silu(gate) * up of one
 // output column is formed in registers and the tile yields BN/2 output columns.
+//
+// Split K (ksplit > 1, not for SwiGLU): when a GEMM has too few large tiles to fill the chip, each
+// tile is computed by ksplit workgroups, one per K range.  A workgroup writes its accumulators to
+// its slot of a float32 workspace (in accumulator order, so the stores are contiguous), makes them
+// visible device-wide and takes a ticket from the tile's counter; the one that draws the last
+// ticket adds the parts IN K-RANGE ORDER (its own from registers), so the result does not depend on
+// which workgroup came last, runs the ordinary epilogue and puts the counter back to zero.  Nobody
+// waits for anybody.  Launches that share a workspace must not overlap (one stream).
 // =====================================================================================
 #define CAKE_GLOBAL_AS __attribute__((address_space(1)))
 #define CAKE_LDS_AS __attribute__((address_space(3)))
@@ -50,7 +61,8 @@ template <int BK> __device__ __forceinline__ int gemm_swz(int row) { return BK =
 template <int WTM, int WTN, int WAVES_M, int WAVES_N, int BK, int STAGES, int EPI>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
 gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, const bf16_t* __restrict__ W2,
-                 void* __restrict__ outv, int M, int N, int K, int tiles_m, int tiles_n) {
+                 void* __restrict__ outv, int M, int N, int K, int tiles_m, int tiles_n,
+                 float* __restrict__ part, unsigned* __restrict__ counters, int ksplit) {
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int KS = BK / 16;   // 16-deep MFMA steps per slice
     constexpr int BM = WAVES_M * WTM * 32, BN = WAVES_N * WTN * 32;
@@ -69,8 +81,20 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
 
     const int nb = tiles_m * tiles_n;
     const int bid = blockIdx.x;
-    const int t = (nb % 8 == 0) ? (bid % 8) * (nb / 8) + bid / 8 : bid;
+    int t, kpart = 0;
+    if (EPI == EPI_SWIGLU || ksplit == 1) {
+        t = (nb % 8 == 0) ? (bid % 8) * (nb / 8) + bid / 8 : bid;
+    } else if (8 % ksplit == 0 && nb % (8 / ksplit) == 0) {
+        // block b runs on XCD b % 8: an XCD takes one K range of a group of whole weight panels
+        const int xcd = bid & 7, per_group = nb / (8 / ksplit);
+        kpart = xcd % ksplit;
+        t = (xcd / ksplit) * per_group + (bid >> 3);
+    } else {
+        kpart = bid % ksplit;
+        t = bid / ksplit;
+    }
     const int tm = t % tiles_m, tn = t / tiles_m;
+    const int k_begin = kpart * (K / ksplit);
     const int m0 = tm * BM;
     const int n0 = tn * (EPI == EPI_SWIGLU ? BN / 2 : BN);   // first output column of the tile
 
@@ -81,7 +105,7 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
 #pragma unroll
     for (int i = 0; i < A_PER; ++i) {
         int row = (wave + i * NW) * RPL + lr;
-        ag[i] = A + size_t(min(m0 + row, M - 1)) * K + (lpos ^ gemm_swz<BK>(row)) * 8;
+        ag[i] = A + size_t(min(m0 + row, M - 1)) * K + k_begin + (lpos ^ gemm_swz<BK>(row)) * 8;
     }
 #pragma unroll
     for (int i = 0; i < B_PER; ++i) {
@@ -95,7 +119,7 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
         } else {
             grow = n0 + row;
         }
-        bg[i] = src + size_t(grow) * K + (lpos ^ gemm_swz<BK>(row)) * 8;
+        bg[i] = src + size_t(grow) * K + k_begin + (lpos ^ gemm_swz<BK>(row)) * 8;
     }
     auto issue = [&](int stage, int k0) {
         unsigned char* sa = lds + stage * STAGE;
@@ -145,7 +169,7 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
         }
     };
 
-    const int nk = K / BK;
+    const int nk = K / ksplit / BK;
     // prologue: STAGES-1 slices in flight; slice 0 landed; its step-0 operands in registers
 #pragma unroll
     for (int st = 0; st < STAGES - 1; ++st)
@@ -174,6 +198,63 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
         rd(opa[0], opb[0], (kt + 1) % STAGES, koff[0]);
         mm(opa[(KS - 1) & 1], opb[(KS - 1) & 1]);
         interleave();
+    }
+
+    if constexpr (EPI != EPI_SWIGLU) {
+        if (ksplit > 1) {
+            // Parts go through the workspace with device-scope accesses (the sc1 bit: written through to,
+            // and read from, the level every XCD shares), so no cache-wide write-back or invalidate is
+            // needed: a wave waits until its stores are acknowledged, the barrier collects all waves, then
+            // one thread draws the ticket; the loads of the last workgroup are issued after its ticket.
+            constexpr int TILE_B = BM * BN * 4, NT = NW * 64;
+            const __amdgpu_buffer_rsrc_t ws = __builtin_amdgcn_make_buffer_rsrc(part, 0, tiles_m * tiles_n * ksplit * TILE_B, 0x00020000);
+            const unsigned slots = unsigned(t) * ksplit * TILE_B;
+            const unsigned mine = slots + unsigned(kpart) * TILE_B;
+            constexpr int DEVICE_SCOPE = 16;   // sc1
+#pragma unroll
+            for (int i = 0; i < WTM; ++i)
+#pragma unroll
+                for (int j = 0; j < WTN; ++j)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        u32x4 v = {__float_as_uint(acc[i][j][4 * q]), __float_as_uint(acc[i][j][4 * q + 1]),
+                                   __float_as_uint(acc[i][j][4 * q + 2]), __float_as_uint(acc[i][j][4 * q + 3])};
+                        __builtin_amdgcn_raw_buffer_store_b128(v, ws, mine + (((i * WTN + j) * 4 + q) * NT + tid) * 16, 0, DEVICE_SCOPE);
+                    }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            if (tid == 0) *(volatile unsigned*)lds = __hip_atomic_fetch_add(&counters[t], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __syncthreads();
+            if (*(volatile unsigned*)lds != unsigned(ksplit - 1)) return;
+            // every part, this workgroup's too, comes from the workspace, in K-range order
+            auto sum_parts = [&](auto nparts) {
+                constexpr int NP = decltype(nparts)::value;
+#pragma unroll
+                for (int i = 0; i < WTM; ++i)
+#pragma unroll
+                    for (int j = 0; j < WTN; ++j) {
+                        u32x4 p[NP][4];
+#pragma unroll
+                        for (int sp = 0; sp < NP; ++sp)
+#pragma unroll
+                            for (int q = 0; q < 4; ++q)
+                                p[sp][q] = __builtin_amdgcn_raw_buffer_load_b128(ws, slots + sp * TILE_B + (((i * WTN + j) * 4 + q) * NT + tid) * 16, 0, DEVICE_SCOPE);
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                float tot = __uint_as_float(p[0][q][e]);
+#pragma unroll
+                                for (int sp = 1; sp < NP; ++sp) tot += __uint_as_float(p[sp][q][e]);
+                                acc[i][j][4 * q + e] = tot;
+                            }
+                    }
+            };
+            if (ksplit == 2) sum_parts(std::integral_constant<int, 2>{});
+            else if (ksplit == 4) sum_parts(std::integral_constant<int, 4>{});
+            else sum_parts(std::integral_constant<int, 8>{});
+            if (tid == 0) counters[t] = 0;   // every ticket of this tile is drawn: ready for the next launch
+        }
     }
 
     // epilogue
@@ -269,26 +350,45 @@ static bool gemm_cfg_ok(int cfg, int epi, int M, int N, int K) {
 
 bool gemm_mfma_supported(int epi, int M, int N, int K) { return gemm_cfg_ok(GCFG_128x128, epi, M, N, K); }
 
-// Cost model: the busiest CU runs ceil(tiles / 256) tiles one after another, each costing its
-// area divided by a per-shape efficiency (measured: larger tiles feed the MFMAs better because
-// they pull fewer bytes per flop through L2).
-static int gemm_pick(int epi, int M, int N, int K) {
+// Cost model: the busiest CU runs ceil(workgroups / 256) of them one after another, each costing its
+// tile area times its share of K divided by a per-shape efficiency (measured: larger tiles feed the
+// MFMAs better because they pull fewer bytes per flop through L2), plus a fixed part (pipeline fill,
+// epilogue).  With K split `ks` ways every workgroup writes its part and the one that finishes a tile
+// reads ks parts back; that pays only where the unsplit choice is a small tile over a long K (the
+// down projections of the 512-token-chunk and the 8192-wide shapes).  Unit: one 256x256 tile over
+// K = 4096 costs 100 (about a microsecond each).
+struct GemmChoice { int cfg, ksplit; };
+static bool ksplit_ok(int cfg, int ks, int epi, int M, int N, int K, const GemmSplitWs* ws) {
+    if (ks == 1) return true;
+    if (!ws || !ws->part || !ws->counters || epi == EPI_SWIGLU) return false;
+    if (K % ks || (K / ks) % 64 || K / ks < 512) return false;
+    const GemmCfg& c = kGemmCfg[cfg];
+    const long tiles = long((M + c.bm - 1) / c.bm) * (N / c.bn);
+    return tiles <= ws->n_counters && size_t(tiles) * ks * c.bm * c.bn * sizeof(float) <= ws->part_bytes;
+}
+static GemmChoice gemm_pick(int epi, int M, int N, int K, const GemmSplitWs* ws) {
     static const double eff[GCFG_COUNT] = {1.0, 0.77, 0.62, 0.61, 0.45};   // measured TFLOP/s per busy CU, relative to 256x256
-    int best = GCFG_128x128;
+    GemmChoice best{GCFG_128x128, 1};
     double best_cost = 1e30;
     for (int cfg = GCFG_COUNT - 1; cfg >= 0; --cfg) {
         if (!gemm_cfg_ok(cfg, epi, M, N, K)) continue;
         const GemmCfg& c = kGemmCfg[cfg];
-        long tiles = long((M + c.bm - 1) / c.bm) * (N / out_cols_per_tile(cfg, epi));
-        double cost = double((tiles + 255) / 256) * double(c.bm) * c.bn / eff[cfg];
-        if (cost < best_cost) { best_cost = cost; best = cfg; }
+        const long tiles = long((M + c.bm - 1) / c.bm) * (N / out_cols_per_tile(cfg, epi));
+        const double area = double(c.bm) * c.bn / 65536.0;
+        for (int ks = 1; ks <= 8; ks *= 2) {
+            if (!ksplit_ok(cfg, ks, epi, M, N, K, ws)) continue;
+            const double rounds = double((tiles * ks + 255) / 256);
+            double cost = rounds * (100.0 * area * (double(K) / ks / 4096.0) / eff[cfg] + 6.0);
+            if (ks > 1) cost += 8.0 + 16.0 * area * ks;   // measured: the parts cross the chip twice, at device scope
+            if (cost < best_cost) { best_cost = cost; best = GemmChoice{cfg, ks}; }
+        }
     }
     return best;
 }
 
 template <int WTM, int WTN, int WAVES_M, int WAVES_N, int BK, int STAGES, int EPI>
 static hipError_t gemm_launch_t(const bf16_t* A, const bf16_t* W, const bf16_t* W2, void* out, int M, int N, int K,
-                                hipStream_t st) {
+                                hipStream_t st, int ksplit, const GemmSplitWs* ws) {
     constexpr int BM = WAVES_M * WTM * 32, BN = WAVES_N * WTN * 32;
     constexpr int LDS = (BM + BN) * BK * 2 * STAGES;
     auto kern = gemm_mfma_kernel<WTM, WTN, WAVES_M, WAVES_N, BK, STAGES, EPI>;
@@ -299,45 +399,59 @@ static hipError_t gemm_launch_t(const bf16_t* A, const bf16_t* W, const bf16_t* 
         attr_set = true;
     }
     const int tiles_m = (M + BM - 1) / BM, tiles_n = N / (EPI == EPI_SWIGLU ? BN / 2 : BN);
-    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(64 * WAVES_M * WAVES_N), LDS, st, A, W, W2, out, M, N, K,
-                       tiles_m, tiles_n);
+    if (ksplit > 1 && (K / ksplit) % BK) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n * ksplit), dim3(64 * WAVES_M * WAVES_N), LDS, st, A, W, W2, out, M, N, K,
+                       tiles_m, tiles_n, ksplit > 1 ? ws->part : nullptr, ksplit > 1 ? ws->counters : nullptr, ksplit);
     return hipGetLastError();
 }
 
 template <int EPI>
-static hipError_t gemm_launch_cfg(int cfg, const bf16_t* A, const bf16_t* W, const bf16_t* W2, void* out, int M, int N,
-                                  int K, hipStream_t st) {
-    const long tiles128 = long((M + 127) / 128) * (N / (EPI == EPI_SWIGLU ? 64 : 128));
+static hipError_t gemm_launch_cfg(int cfg, int ks, const GemmSplitWs* ws, const bf16_t* A, const bf16_t* W, const bf16_t* W2,
+                                  void* out, int M, int N, int K, hipStream_t st) {
+    const long tiles128 = long((M + 127) / 128) * (N / (EPI == EPI_SWIGLU ? 64 : 128)) * ks;
     switch (cfg) {
-        case GCFG_256x256: return gemm_launch_t<4, 2, 2, 4, 32, 5, EPI>(A, W, W2, out, M, N, K, st);
-        case GCFG_256x128: return gemm_launch_t<4, 2, 2, 2, 32, 4, EPI>(A, W, W2, out, M, N, K, st);
+        case GCFG_256x256: return gemm_launch_t<4, 2, 2, 4, 32, 5, EPI>(A, W, W2, out, M, N, K, st, ks, ws);
+        case GCFG_256x128: return gemm_launch_t<4, 2, 2, 2, 32, 4, EPI>(A, W, W2, out, M, N, K, st, ks, ws);
         case GCFG_128x192:
-            if constexpr (EPI != EPI_SWIGLU) return gemm_launch_t<2, 3, 2, 2, 32, 4, EPI>(A, W, W2, out, M, N, K, st);
+            if constexpr (EPI != EPI_SWIGLU) return gemm_launch_t<2, 3, 2, 2, 32, 4, EPI>(A, W, W2, out, M, N, K, st, ks, ws);
             else return hipErrorInvalidValue;
-        case GCFG_128x64:   // half-size chunks (M = 512): the only shape that still gives N = 4096 GEMMs 256 tiles
+        case GCFG_128x64:   // half-size chunks (M = 512): the only unsplit shape that still gives N = 4096 GEMMs 256 tiles
             if constexpr (EPI != EPI_SWIGLU) {
-                if ((K % 64) == 0) return gemm_launch_t<2, 1, 2, 2, 64, 4, EPI>(A, W, W2, out, M, N, K, st);
-                return gemm_launch_t<2, 1, 2, 2, 32, 4, EPI>(A, W, W2, out, M, N, K, st);
+                if ((K / ks % 64) == 0) return gemm_launch_t<2, 1, 2, 2, 64, 4, EPI>(A, W, W2, out, M, N, K, st, ks, ws);
+                return gemm_launch_t<2, 1, 2, 2, 32, 4, EPI>(A, W, W2, out, M, N, K, st, ks, ws);
             } else {
                 return hipErrorInvalidValue;
             }
         default:
             // one workgroup per CU at most: spend the whole LDS on a deep ring of 64-deep slices
             // (96 KB in flight per CU); more tiles than CUs: 64 KB rings so two workgroups share a CU
-            if (tiles128 <= 256 && (K % 64) == 0) return gemm_launch_t<2, 2, 2, 2, 64, 4, EPI>(A, W, W2, out, M, N, K, st);
-            return gemm_launch_t<2, 2, 2, 2, 32, 4, EPI>(A, W, W2, out, M, N, K, st);
+            if (tiles128 <= 256 && (K / ks % 64) == 0) return gemm_launch_t<2, 2, 2, 2, 64, 4, EPI>(A, W, W2, out, M, N, K, st, ks, ws);
+            return gemm_launch_t<2, 2, 2, 2, 32, 4, EPI>(A, W, W2, out, M, N, K, st, ks, ws);
     }
 }
 
+static GemmChoice gemm_choose(int epi, int M, int N, int K, int cfg_override, const GemmSplitWs* ws, int ksplit_override) {
+    GemmChoice ch = gemm_pick(epi, M, N, K, ksplit_override == 1 ? nullptr : ws);
+    if (cfg_override >= 0 && cfg_override < GCFG_COUNT && gemm_cfg_ok(cfg_override, epi, M, N, K)) ch = GemmChoice{cfg_override, 1};
+    if (ksplit_override > 1 && gemm_cfg_ok(ch.cfg, epi, M, N, K) && ksplit_ok(ch.cfg, ksplit_override, epi, M, N, K, ws))
+        ch.ksplit = ksplit_override;
+    return ch;
+}
+
+void gemm_mfma_plan(int epi, int M, int N, int K, int cfg_override, const GemmSplitWs* ws, int ksplit_override,
+                    int* bm, int* bn, int* ksplit) {
+    const GemmChoice ch = gemm_choose(epi, M, N, K, cfg_override, ws, ksplit_override);
+    *bm = kGemmCfg[ch.cfg].bm; *bn = kGemmCfg[ch.cfg].bn; *ksplit = ch.ksplit;
+}
+
 hipError_t launch_gemm_mfma(int epi, const void* a, const void* w, const void* w2, void* out, int M, int N, int K,
-                            hipStream_t st, int cfg_override) {
+                            hipStream_t st, int cfg_override, const GemmSplitWs* ws, int ksplit_override) {
     const bf16_t *A = (const bf16_t*)a, *W = (const bf16_t*)w, *W2 = (const bf16_t*)w2;
-    int cfg = cfg_override >= 0 && cfg_override < GCFG_COUNT && gemm_cfg_ok(cfg_override, epi, M, N, K)
-                  ? cfg_override : gemm_pick(epi, M, N, K);
-    if (!gemm_cfg_ok(cfg, epi, M, N, K)) return hipErrorInvalidValue;
-    if (epi == EPI_SWIGLU) return gemm_launch_cfg<EPI_SWIGLU>(cfg, A, W, W2, out, M, N, K, st);
-    if (epi == EPI_RESIDUAL_F32) return gemm_launch_cfg<EPI_RESIDUAL_F32>(cfg, A, W, W2, out, M, N, K, st);
-    if (epi == EPI_STORE_F32) return gemm_launch_cfg<EPI_STORE_F32>(cfg, A, W, W2, out, M, N, K, st);
+    const GemmChoice ch = gemm_choose(epi, M, N, K, cfg_override, ws, ksplit_override);
+    if (!gemm_cfg_ok(ch.cfg, epi, M, N, K)) return hipErrorInvalidValue;
+    if (epi == EPI_SWIGLU) return gemm_launch_cfg<EPI_SWIGLU>(ch.cfg, 1, ws, A, W, W2, out, M, N, K, st);
+    if (epi == EPI_RESIDUAL_F32) return gemm_launch_cfg<EPI_RESIDUAL_F32>(ch.cfg, ch.ksplit, ws, A, W, W2, out, M, N, K, st);
+    if (epi == EPI_STORE_F32) return gemm_launch_cfg<EPI_STORE_F32>(ch.cfg, ch.ksplit, ws, A, W, W2, out, M, N, K, st);
     return hipErrorInvalidValue;
 }
 

@@ -77,6 +77,55 @@ def test_gemm_variants(kind, path, M, N, K, cfg):
     assert np.all(np.abs(got - want) <= tol * np.abs(want) + 1e-6 * np.abs(want).max())
 
 
+@pytest.mark.parametrize("M,N,K,cfg,ks,tile", [
+    (1024, 1024, 4096, 1, 2, (256, 256)), (1024, 1024, 4096, 1, 4, (256, 256)), (1024, 1024, 4096, 1, 8, (256, 256)),
+    (700, 512, 2048, 2, 4, (256, 128)),      # ragged M
+    (300, 768, 1024, 3, 2, (128, 128)),
+    (129, 768, 2048, 4, 2, (128, 192)),
+    (200, 512, 1024, 5, 2, (128, 64)),
+    (1024, 4096, 14336, 0, 0, None),         # the shapes of the down projection: whatever the cost model takes
+    (512, 4096, 11008, 0, 0, None),
+])
+def test_gemm_split_k(M, N, K, cfg, ks, tile):
+    """K of one tile spread over several workgroups: same result as the fp64 product, the same bits on
+    every launch (the parts are summed in K order whoever finishes last), counters back at zero."""
+    import torch
+    eng = _engine(SHAPE_BF.with_(d_model=4096), 1024, 1024, 64)
+    eng.set_tuning(gemm_config=cfg, gemm_ksplit=ks)
+    plan = eng.op_gemm_plan(M, N, K, residual=True)
+    if tile is not None:
+        assert plan == (tile[0], tile[1], ks), plan          # the forced split is really what runs
+    else:
+        assert plan[2] > 1, plan                              # these shapes have too few large tiles: the model splits
+    rng = np.random.default_rng(M + N + K + ks)
+    x0 = rng.standard_normal((M, N)).astype(np.float32)
+    tol = 2e-6 * max(1, K / 256)
+    # two different products take turns, so a part left over from the launch before would show
+    ops = []
+    for _ in range(2):
+        a, w = _bf16_vals(rng, (M, K)), _bf16_vals(rng, (N, K), 0.05)
+        A, W = (torch.from_numpy(t).cuda().to(torch.bfloat16) for t in (a, w))
+        ops.append((A, W, a.astype(np.float64) @ w.astype(np.float64).T))
+    first = [None, None]
+    for turn in range(6):
+        A, W, want = ops[turn % 2]
+        if turn < 2:
+            assert _rel(eng.op_gemm(A, W).cpu().numpy(), want) < tol
+        X = torch.from_numpy(x0.copy()).cuda()
+        got = eng.op_gemm_residual(A, W, X).cpu().numpy()
+        if first[turn % 2] is None:
+            assert _rel(got, x0 + want) < tol
+            first[turn % 2] = got
+        else:
+            np.testing.assert_array_equal(got, first[turn % 2])
+    # unsplit, the same kernel agrees to rounding
+    eng.set_tuning(gemm_config=cfg, gemm_ksplit=1)
+    assert eng.op_gemm_plan(M, N, K)[2] == 1
+    A, W, want = ops[0]
+    X = torch.from_numpy(x0.copy()).cuda()
+    assert _rel(eng.op_gemm_residual(A, W, X).cpu().numpy(), first[0]) < tol
+
+
 @pytest.mark.parametrize("kind", ["f32", "bf16"])
 @pytest.mark.parametrize("tok_begin,rows", [(0, 200), (192, 100), (100, 157), (65400, 136)])
 def test_rope_and_page_write(kind, tok_begin, rows):
