@@ -98,6 +98,14 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
     const int m0 = tm * BM;
     const int n0 = tn * (EPI == EPI_SWIGLU ? BN / 2 : BN);   // first output column of the tile
 
+    // first row of weight-tile row `row` (for SwiGLU the tile's rows alternate between the two matrices)
+    auto w_row = [&](int row) -> const bf16_t* {
+        if (EPI == EPI_SWIGLU) {
+            int wcol = row / (WTN * 32), j = (row / 32) % WTN, c = row % 32;
+            return ((j & 1) ? W2 : W) + size_t(n0 + wcol * (WTN / 2) * 32 + (j >> 1) * 32 + c) * K + k_begin;
+        }
+        return W + size_t(n0 + row) * K + k_begin;
+    };
     // global source of this lane for each 1 KB wave-load (16 rows x 64 B)
     const int lr = lane / CPR, lpos = lane % CPR;
     const bf16_t* ag[A_PER];
@@ -110,16 +118,7 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
 #pragma unroll
     for (int i = 0; i < B_PER; ++i) {
         int row = (wave + i * NW) * RPL + lr;
-        const bf16_t* src = W;
-        int grow;
-        if (EPI == EPI_SWIGLU) {
-            int wcol = row / (WTN * 32), j = (row / 32) % WTN, c = row % 32;
-            src = (j & 1) ? W2 : W;
-            grow = n0 + wcol * (WTN / 2) * 32 + (j >> 1) * 32 + c;
-        } else {
-            grow = n0 + row;
-        }
-        bg[i] = src + size_t(grow) * K + k_begin + (lpos ^ gemm_swz<BK>(row)) * 8;
+        bg[i] = w_row(row) + (lpos ^ gemm_swz<BK>(row)) * 8;
     }
     auto issue = [&](int stage, int k0) {
         unsigned char* sa = lds + stage * STAGE;
@@ -411,10 +410,19 @@ static hipError_t gemm_launch_cfg(int cfg, int ks, const GemmSplitWs* ws, const 
     const long tiles128 = long((M + 127) / 128) * (N / (EPI == EPI_SWIGLU ? 64 : 128)) * ks;
     switch (cfg) {
         case GCFG_256x256: return gemm_launch_t<4, 2, 2, 4, 32, 5, EPI>(A, W, W2, out, M, N, K, st, ks, ws);
-        case GCFG_256x128: return gemm_launch_t<4, 2, 2, 2, 32, 4, EPI>(A, W, W2, out, M, N, K, st, ks, ws);
+        case GCFG_256x128:
+            if ((K / ks % 64) == 0) return gemm_launch_t<4, 2, 2, 2, 64, 3, EPI>(A, W, W2, out, M, N, K, st, ks, ws);
+            return gemm_launch_t<4, 2, 2, 2, 32, 4, EPI>(A, W, W2, out, M, N, K, st, ks, ws);
         case GCFG_128x192:
-            if constexpr (EPI != EPI_SWIGLU) return gemm_launch_t<2, 3, 2, 2, 32, 4, EPI>(A, W, W2, out, M, N, K, st, ks, ws);
-            else return hipErrorInvalidValue;
+            if constexpr (EPI != EPI_SWIGLU) {
+                // at most one workgroup per CU: the whole 160 KB of LDS as a ring of 64-deep slices (120 KB in
+                // flight hide the latency of weights that come from HBM: 64 against 75 us for N = 6144)
+                if (long((M + 127) / 128) * (N / 192) * ks <= 256 && (K / ks % 64) == 0)
+                    return gemm_launch_t<2, 3, 2, 2, 64, 4, EPI>(A, W, W2, out, M, N, K, st, ks, ws);
+                return gemm_launch_t<2, 3, 2, 2, 32, 4, EPI>(A, W, W2, out, M, N, K, st, ks, ws);
+            } else {
+                return hipErrorInvalidValue;
+            }
         case GCFG_128x64:   // half-size chunks (M = 512): the only unsplit shape that still gives N = 4096 GEMMs 256 tiles
             if constexpr (EPI != EPI_SWIGLU) {
                 if ((K / ks % 64) == 0) return gemm_launch_t<2, 1, 2, 2, 64, 4, EPI>(A, W, W2, out, M, N, K, st, ks, ws);
