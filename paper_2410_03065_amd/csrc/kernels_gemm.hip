@@ -366,7 +366,7 @@ static bool ksplit_ok(int cfg, int ks, int epi, int M, int N, int K, const GemmS
     return tiles <= ws->n_counters && size_t(tiles) * ks * c.bm * c.bn * sizeof(float) <= ws->part_bytes;
 }
 static GemmChoice gemm_pick(int epi, int M, int N, int K, const GemmSplitWs* ws) {
-    static const double eff[GCFG_COUNT] = {1.0, 0.77, 0.62, 0.61, 0.45};   // measured TFLOP/s per busy CU, relative to 256x256
+    static const double eff[GCFG_COUNT] = {1.0, 0.77, 0.62, 0.61, 0.40};   // measured TFLOP/s per busy CU, relative to 256x256
     GemmChoice best{GCFG_128x128, 1};
     double best_cost = 1e30;
     for (int cfg = GCFG_COUNT - 1; cfg >= 0; --cfg) {
@@ -378,7 +378,8 @@ static GemmChoice gemm_pick(int epi, int M, int N, int K, const GemmSplitWs* ws)
             if (!ksplit_ok(cfg, ks, epi, M, N, K, ws)) continue;
             const double rounds = double((tiles * ks + 255) / 256);
             double cost = rounds * (100.0 * area * (double(K) / ks / 4096.0) / eff[cfg] + 6.0);
-            if (ks > 1) cost += 8.0 + 16.0 * area * ks;   // measured: the parts cross the chip twice, at device scope
+            // measured: the parts cross the chip twice, at device scope; and a split must promise 8 % to be taken
+            if (ks > 1) cost = (cost + 10.0 + 20.0 * area * ks) * 1.08;
             if (cost < best_cost) { best_cost = cost; best = GemmChoice{cfg, ks}; }
         }
     }

@@ -83,8 +83,7 @@ def test_gemm_variants(kind, path, M, N, K, cfg):
     (300, 768, 1024, 3, 2, (128, 128)),
     (129, 768, 2048, 4, 2, (128, 192)),
     (200, 512, 1024, 5, 2, (128, 64)),
-    (1024, 4096, 14336, 0, 0, None),         # the shapes of the down projection: whatever the cost model takes
-    (512, 4096, 11008, 0, 0, None),
+    (512, 4096, 11008, 0, 0, None),          # down projection with 512-token chunks: the cost model splits it
 ])
 def test_gemm_split_k(M, N, K, cfg, ks, tile):
     """K of one tile spread over several workgroups: same result as the fp64 product, the same bits on
@@ -96,7 +95,10 @@ def test_gemm_split_k(M, N, K, cfg, ks, tile):
     if tile is not None:
         assert plan == (tile[0], tile[1], ks), plan          # the forced split is really what runs
     else:
-        assert plan[2] > 1, plan                              # these shapes have too few large tiles: the model splits
+        assert plan[2] > 1, plan                              # too few large tiles: the model splits
+        assert eng.op_gemm_plan(1024, 8192, 28672) == (256, 256, 2)      # the widest model's down projection
+        assert eng.op_gemm_plan(1024, 4096, 14336) == (128, 128, 1)      # 256 tiles of 128 x 128 fill the chip: unsplit
+        assert eng.op_gemm_plan(1024, 6144, 4096, residual=False) == (128, 192, 1)
     rng = np.random.default_rng(M + N + K + ks)
     x0 = rng.standard_normal((M, N)).astype(np.float32)
     tol = 2e-6 * max(1, K / 256)
