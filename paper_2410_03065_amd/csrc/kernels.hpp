@@ -47,7 +47,7 @@ struct GemmSplitWs {
     unsigned* counters;
     int n_counters;
 };
-// cfg_override: -1 = choose the tile configuration from the shape; 0..4 = force one, unsplit (testing).
+// cfg_override: -1 = choose the tile configuration from the shape; 0..5 = force one, unsplit (testing).
 // ws: nullptr = never split K.  ksplit_override: 0 = by the cost model, 1 = never, 2/4/8 = that
 // many K ranges wherever the shape and the workspace allow it.
 hipError_t launch_gemm_mfma(int epi, const void* a, const void* w, const void* w2, void* out,

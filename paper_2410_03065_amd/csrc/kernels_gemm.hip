@@ -58,13 +58,16 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 // 16 consecutive rows must fall into 16 different 16-byte slots of a 256-byte bank window
 template <int BK> __device__ __forceinline__ int gemm_swz(int row) { return BK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3); }
 
-template <int WTM, int WTN, int WAVES_M, int WAVES_N, int BK, int STAGES, int EPI>
-__global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
+template <int WTM, int WTN, int WAVES_M, int WAVES_N, int BK, int STAGES, int EPI, int KW>
+__global__ void __launch_bounds__(64 * WAVES_M * WAVES_N * KW)
 gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, const bf16_t* __restrict__ W2,
                  void* __restrict__ outv, int M, int N, int K, int tiles_m, int tiles_n,
                  float* __restrict__ part, unsigned* __restrict__ counters, int ksplit) {
-    constexpr int NW = WAVES_M * WAVES_N;
-    constexpr int KS = BK / 16;   // 16-deep MFMA steps per slice
+    constexpr int NWS = WAVES_M * WAVES_N;   // waves that divide the tile in space
+    constexpr int NW = NWS * KW;             // times the waves that divide each slice along K
+    constexpr int KS = BK / 16 / KW;         // 16-deep MFMA steps per slice and wave
+    static_assert(KW == 1 || (KW == 2 && BK == 64), "K is divided between two waves at most, two steps each");
+    static_assert(KW == 1 || STAGES * (WAVES_M * WTM + WAVES_N * WTN) * 32 * BK * 2 >= NWS * WTM * WTN * 4096, "the ring holds the exchange");
     constexpr int BM = WAVES_M * WTM * 32, BN = WAVES_N * WTN * 32;
     constexpr int ROWB = BK * 2, CPR = BK / 8, RPL = 64 / CPR;
     constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB, STAGE = A_BYTES + B_BYTES;
@@ -76,7 +79,8 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+    const int kw = wave / NWS, wsp = wave % NWS;
+    const int wm = wsp / WAVES_N, wn = wsp % WAVES_N;
     const int lrow = lane & 31, lhalf = lane >> 5;
 
     const int nb = tiles_m * tiles_n;
@@ -143,7 +147,7 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
     const int sw = gemm_swz<BK>(lrow);  // tile rows start at multiples of 32, so the swizzle depends on lrow only
     int koff[KS];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) koff[ks] = ((2 * ks + lhalf) ^ sw) << 4;
+    for (int ks = 0; ks < KS; ++ks) koff[ks] = ((2 * (kw * KS + ks) + lhalf) ^ sw) << 4;
     const int a_row_off = (wm * WTM * 32 + lrow) * ROWB;
     const int b_row_off = A_BYTES + (wn * WTN * 32 + lrow) * ROWB;
     auto rd = [&](bf16x8* a, bf16x8* bb, int stage, int koffv) {
@@ -199,13 +203,42 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
         interleave();
     }
 
+    if constexpr (KW > 1) {
+        // The two waves that shared a tile along K add up: the second hands its accumulators over through
+        // the ring (idle by now) and leaves; the first carries on with the sum.
+        __syncthreads();
+        float4* spot = (float4*)(lds + wsp * (WTM * WTN * 4096));
+        if (kw == 1) {
+#pragma unroll
+            for (int i = 0; i < WTM; ++i)
+#pragma unroll
+                for (int j = 0; j < WTN; ++j)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        spot[((i * WTN + j) * 4 + q) * 64 + lane] =
+                            make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+        }
+        __syncthreads();
+        if (kw == 1) return;
+#pragma unroll
+        for (int i = 0; i < WTM; ++i)
+#pragma unroll
+            for (int j = 0; j < WTN; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float4 p = spot[((i * WTN + j) * 4 + q) * 64 + lane];
+                    acc[i][j][4 * q] += p.x; acc[i][j][4 * q + 1] += p.y; acc[i][j][4 * q + 2] += p.z; acc[i][j][4 * q + 3] += p.w;
+                }
+    }
+    const int tid_s = wsp * 64 + lane;   // thread index among the waves that hold a result
+
     if constexpr (EPI != EPI_SWIGLU) {
         if (ksplit > 1) {
             // Parts go through the workspace with device-scope accesses (the sc1 bit: written through to,
             // and read from, the level every XCD shares), so no cache-wide write-back or invalidate is
             // needed: a wave waits until its stores are acknowledged, the barrier collects all waves, then
             // one thread draws the ticket; the loads of the last workgroup are issued after its ticket.
-            constexpr int TILE_B = BM * BN * 4, NT = NW * 64;
+            constexpr int TILE_B = BM * BN * 4, NT = NWS * 64;
             const __amdgpu_buffer_rsrc_t ws = __builtin_amdgcn_make_buffer_rsrc(part, 0, tiles_m * tiles_n * ksplit * TILE_B, 0x00020000);
             const unsigned slots = unsigned(t) * ksplit * TILE_B;
             const unsigned mine = slots + unsigned(kpart) * TILE_B;
@@ -218,11 +251,11 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
                     for (int q = 0; q < 4; ++q) {
                         u32x4 v = {__float_as_uint(acc[i][j][4 * q]), __float_as_uint(acc[i][j][4 * q + 1]),
                                    __float_as_uint(acc[i][j][4 * q + 2]), __float_as_uint(acc[i][j][4 * q + 3])};
-                        __builtin_amdgcn_raw_buffer_store_b128(v, ws, mine + (((i * WTN + j) * 4 + q) * NT + tid) * 16, 0, DEVICE_SCOPE);
+                        __builtin_amdgcn_raw_buffer_store_b128(v, ws, mine + (((i * WTN + j) * 4 + q) * NT + tid_s) * 16, 0, DEVICE_SCOPE);
                     }
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
-            if (tid == 0) *(volatile unsigned*)lds = __hip_atomic_fetch_add(&counters[t], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (tid_s == 0) *(volatile unsigned*)lds = __hip_atomic_fetch_add(&counters[t], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __syncthreads();
             if (*(volatile unsigned*)lds != unsigned(ksplit - 1)) return;
             // every part, this workgroup's too, comes from the workspace, in K-range order
@@ -237,7 +270,7 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
                         for (int sp = 0; sp < NP; ++sp)
 #pragma unroll
                             for (int q = 0; q < 4; ++q)
-                                p[sp][q] = __builtin_amdgcn_raw_buffer_load_b128(ws, slots + sp * TILE_B + (((i * WTN + j) * 4 + q) * NT + tid) * 16, 0, DEVICE_SCOPE);
+                                p[sp][q] = __builtin_amdgcn_raw_buffer_load_b128(ws, slots + sp * TILE_B + (((i * WTN + j) * 4 + q) * NT + tid_s) * 16, 0, DEVICE_SCOPE);
 #pragma unroll
                         for (int q = 0; q < 4; ++q)
 #pragma unroll
@@ -252,7 +285,7 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
             if (ksplit == 2) sum_parts(std::integral_constant<int, 2>{});
             else if (ksplit == 4) sum_parts(std::integral_constant<int, 4>{});
             else sum_parts(std::integral_constant<int, 8>{});
-            if (tid == 0) counters[t] = 0;   // every ticket of this tile is drawn: ready for the next launch
+            if (tid_s == 0) counters[t] = 0;   // every ticket of this tile is drawn: ready for the next launch
         }
     }
 
@@ -337,13 +370,15 @@ hipError_t launch_mfma_rate(float* out, int workgroups, int iters, hipStream_t s
 
 // Tile configurations.  Chosen per GEMM by gemm_pick() from how well the grid fills 256 CUs.
 struct GemmCfg { int bm, bn; };
-enum { GCFG_256x256 = 0, GCFG_256x128 = 1, GCFG_128x128 = 2, GCFG_128x192 = 3, GCFG_128x64 = 4, GCFG_COUNT = 5 };
-static const GemmCfg kGemmCfg[GCFG_COUNT] = {{256, 256}, {256, 128}, {128, 128}, {128, 192}, {128, 64}};
+// GCFG_128x128K: the 128x128 tile as two 128x64 halves, each shared by two waves that divide K (KW = 2)
+enum { GCFG_256x256 = 0, GCFG_256x128 = 1, GCFG_128x128 = 2, GCFG_128x192 = 3, GCFG_128x64 = 4, GCFG_128x128K = 5, GCFG_COUNT = 6 };
+static const GemmCfg kGemmCfg[GCFG_COUNT] = {{256, 256}, {256, 128}, {128, 128}, {128, 192}, {128, 64}, {128, 128}};
 
 static int out_cols_per_tile(int cfg, int epi) { return epi == EPI_SWIGLU ? kGemmCfg[cfg].bn / 2 : kGemmCfg[cfg].bn; }
 
 static bool gemm_cfg_ok(int cfg, int epi, int M, int N, int K) {
     if ((cfg == GCFG_128x192 || cfg == GCFG_128x64) && epi == EPI_SWIGLU) return false;   // odd n-tiles per wave: no gate/up pairs
+    if (cfg == GCFG_128x128K && (epi == EPI_SWIGLU || (K % 64) != 0)) return false;
     return M > 0 && N > 0 && K >= 32 && (K % 32) == 0 && (N % out_cols_per_tile(cfg, epi)) == 0;
 }
 
@@ -366,7 +401,7 @@ static bool ksplit_ok(int cfg, int ks, int epi, int M, int N, int K, const GemmS
     return tiles <= ws->n_counters && size_t(tiles) * ks * c.bm * c.bn * sizeof(float) <= ws->part_bytes;
 }
 static GemmChoice gemm_pick(int epi, int M, int N, int K, const GemmSplitWs* ws) {
-    static const double eff[GCFG_COUNT] = {1.0, 0.77, 0.62, 0.61, 0.40};   // measured TFLOP/s per busy CU, relative to 256x256
+    static const double eff[GCFG_COUNT] = {1.0, 0.77, 0.62, 0.61, 0.40, 0.65};   // measured TFLOP/s per busy CU, relative to 256x256
     GemmChoice best{GCFG_128x128, 1};
     double best_cost = 1e30;
     for (int cfg = GCFG_COUNT - 1; cfg >= 0; --cfg) {
@@ -386,12 +421,12 @@ static GemmChoice gemm_pick(int epi, int M, int N, int K, const GemmSplitWs* ws)
     return best;
 }
 
-template <int WTM, int WTN, int WAVES_M, int WAVES_N, int BK, int STAGES, int EPI>
+template <int WTM, int WTN, int WAVES_M, int WAVES_N, int BK, int STAGES, int EPI, int KW = 1>
 static hipError_t gemm_launch_t(const bf16_t* A, const bf16_t* W, const bf16_t* W2, void* out, int M, int N, int K,
                                 hipStream_t st, int ksplit, const GemmSplitWs* ws) {
     constexpr int BM = WAVES_M * WTM * 32, BN = WAVES_N * WTN * 32;
     constexpr int LDS = (BM + BN) * BK * 2 * STAGES;
-    auto kern = gemm_mfma_kernel<WTM, WTN, WAVES_M, WAVES_N, BK, STAGES, EPI>;
+    auto kern = gemm_mfma_kernel<WTM, WTN, WAVES_M, WAVES_N, BK, STAGES, EPI, KW>;
     static bool attr_set = false;   // one flag per instantiation
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
@@ -400,7 +435,7 @@ static hipError_t gemm_launch_t(const bf16_t* A, const bf16_t* W, const bf16_t* 
     }
     const int tiles_m = (M + BM - 1) / BM, tiles_n = N / (EPI == EPI_SWIGLU ? BN / 2 : BN);
     if (ksplit > 1 && (K / ksplit) % BK) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n * ksplit), dim3(64 * WAVES_M * WAVES_N), LDS, st, A, W, W2, out, M, N, K,
+    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n * ksplit), dim3(64 * WAVES_M * WAVES_N * KW), LDS, st, A, W, W2, out, M, N, K,
                        tiles_m, tiles_n, ksplit > 1 ? ws->part : nullptr, ksplit > 1 ? ws->counters : nullptr, ksplit);
     return hipGetLastError();
 }
@@ -424,6 +459,9 @@ static hipError_t gemm_launch_cfg(int cfg, int ks, const GemmSplitWs* ws, const 
             } else {
                 return hipErrorInvalidValue;
             }
+        case GCFG_128x128K:
+            if constexpr (EPI != EPI_SWIGLU) return gemm_launch_t<2, 2, 2, 2, 64, 5, EPI, 2>(A, W, W2, out, M, N, K, st, ks, ws);
+            else return hipErrorInvalidValue;
         case GCFG_128x64:   // half-size chunks (M = 512): the only unsplit shape that still gives N = 4096 GEMMs 256 tiles
             if constexpr (EPI != EPI_SWIGLU) {
                 if ((K / ks % 64) == 0) return gemm_launch_t<2, 1, 2, 2, 64, 4, EPI>(A, W, W2, out, M, N, K, st, ks, ws);
