@@ -454,7 +454,7 @@ static hipError_t gemm_launch_cfg(int cfg, int ks, const GemmSplitWs* ws, const 
                 // at most one workgroup per CU: the whole 160 KB of LDS as a ring of 64-deep slices (120 KB in
                 // flight hide the latency of weights that come from HBM: 64 against 75 us for N = 6144)
                 if (long((M + 127) / 128) * (N / 192) * ks <= 256 && (K / ks % 64) == 0)
-                    return gemm_launch_t<2, 3, 2, 2, 64, 4, EPI>(A, W, W2, out, M, N, K, st, ks, ws);
+                    return gemm_launch_t<2, 3, 2, 2, 64, 4, EPI, 2>(A, W, W2, out, M, N, K, st, ks, ws);
                 return gemm_launch_t<2, 3, 2, 2, 32, 4, EPI>(A, W, W2, out, M, N, K, st, ks, ws);
             } else {
                 return hipErrorInvalidValue;
