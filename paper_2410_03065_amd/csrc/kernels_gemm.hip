@@ -203,32 +203,37 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
         interleave();
     }
 
+    // With K divided between two waves, wave kw finishes the 32-row bands i with (i & 1) == kw.
+    auto band_is_mine = [&](int i) { return KW == 1 || (i & 1) == kw; };
     if constexpr (KW > 1) {
-        // The two waves that shared a tile along K add up: the second hands its accumulators over through
-        // the ring (idle by now) and leaves; the first carries on with the sum.
+        // The two waves that shared a tile along K add up: each hands the other, through the ring (idle
+        // by now), the bands it does not finish, and adds what it is handed (a + b = b + a exactly, so
+        // the sum does not depend on which of the two holds it).
+        static_assert(WTM % 2 == 0, "bands are dealt alternately");
         __syncthreads();
         float4* spot = (float4*)(lds + wsp * (WTM * WTN * 4096));
-        if (kw == 1) {
 #pragma unroll
-            for (int i = 0; i < WTM; ++i)
+        for (int i = 0; i < WTM; ++i)
+            if (!band_is_mine(i)) {
 #pragma unroll
                 for (int j = 0; j < WTN; ++j)
 #pragma unroll
                     for (int q = 0; q < 4; ++q)
                         spot[((i * WTN + j) * 4 + q) * 64 + lane] =
                             make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
-        }
+            }
         __syncthreads();
-        if (kw == 1) return;
 #pragma unroll
         for (int i = 0; i < WTM; ++i)
+            if (band_is_mine(i)) {
 #pragma unroll
-            for (int j = 0; j < WTN; ++j)
+                for (int j = 0; j < WTN; ++j)
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const float4 p = spot[((i * WTN + j) * 4 + q) * 64 + lane];
-                    acc[i][j][4 * q] += p.x; acc[i][j][4 * q + 1] += p.y; acc[i][j][4 * q + 2] += p.z; acc[i][j][4 * q + 3] += p.w;
-                }
+                    for (int q = 0; q < 4; ++q) {
+                        const float4 p = spot[((i * WTN + j) * 4 + q) * 64 + lane];
+                        acc[i][j][4 * q] += p.x; acc[i][j][4 * q + 1] += p.y; acc[i][j][4 * q + 2] += p.z; acc[i][j][4 * q + 3] += p.w;
+                    }
+            }
     }
     const int tid_s = wsp * 64 + lane;   // thread index among the waves that hold a result
 
@@ -249,13 +254,14 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
                 for (int j = 0; j < WTN; ++j)
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
+                        if (!band_is_mine(i)) continue;
                         u32x4 v = {__float_as_uint(acc[i][j][4 * q]), __float_as_uint(acc[i][j][4 * q + 1]),
                                    __float_as_uint(acc[i][j][4 * q + 2]), __float_as_uint(acc[i][j][4 * q + 3])};
                         __builtin_amdgcn_raw_buffer_store_b128(v, ws, mine + (((i * WTN + j) * 4 + q) * NT + tid_s) * 16, 0, DEVICE_SCOPE);
                     }
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
-            if (tid_s == 0) *(volatile unsigned*)lds = __hip_atomic_fetch_add(&counters[t], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (tid == 0) *(volatile unsigned*)lds = __hip_atomic_fetch_add(&counters[t], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __syncthreads();
             if (*(volatile unsigned*)lds != unsigned(ksplit - 1)) return;
             // every part, this workgroup's too, comes from the workspace, in K-range order
@@ -265,6 +271,7 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
                 for (int i = 0; i < WTM; ++i)
 #pragma unroll
                     for (int j = 0; j < WTN; ++j) {
+                        if (!band_is_mine(i)) continue;
                         u32x4 p[NP][4];
 #pragma unroll
                         for (int sp = 0; sp < NP; ++sp)
@@ -285,13 +292,14 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
             if (ksplit == 2) sum_parts(std::integral_constant<int, 2>{});
             else if (ksplit == 4) sum_parts(std::integral_constant<int, 4>{});
             else sum_parts(std::integral_constant<int, 8>{});
-            if (tid_s == 0) counters[t] = 0;   // every ticket of this tile is drawn: ready for the next launch
+            if (tid == 0) counters[t] = 0;   // every ticket of this tile is drawn: ready for the next launch
         }
     }
 
     // epilogue
 #pragma unroll
     for (int i = 0; i < WTM; ++i) {
+        if (!band_is_mine(i)) continue;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             int row = m0 + (wm * WTM + i) * 32 + 8 * (v >> 2) + 4 * lhalf + (v & 3);
