@@ -309,7 +309,8 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
                 for (int j = 0; j < WTN; j += 2) {
                     int col = n0 + wn * (WTN / 2) * 32 + (j >> 1) * 32 + lrow;
                     float g = acc[i][j][v], u = acc[i][j + 1][v];
-                    ((bf16_t*)outv)[size_t(row) * N + col] = bf16_t(g / (1.0f + __expf(-g)) * u);
+                    // silu(g) * u; the hardware reciprocal (1 ulp) instead of an IEEE division: the result is rounded to bf16
+                    ((bf16_t*)outv)[size_t(row) * N + col] = bf16_t(g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u);
                 }
             } else {
 #pragma unroll
