@@ -48,9 +48,16 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 // tile is computed by ksplit workgroups, one per K range.  A workgroup writes its accumulators to
 // its slot of a float32 workspace (in accumulator order, so the stores are contiguous), makes them
 // visible device-wide and takes a ticket from the tile's counter; the one that draws the last
-// ticket adds the parts IN K-RANGE ORDER (its own from registers), so the result does not depend on
+// ticket reads all parts back and adds them IN K-RANGE ORDER, so the result does not depend on
 // which workgroup came last, runs the ordinary epilogue and puts the counter back to zero.  Nobody
 // waits for anybody.  Launches that share a workspace must not overlap (one stream).
+//
+// Waves dividing K (KW = 2, 64-deep slices): every spatial part of the tile belongs to two waves,
+// one taking the first two 16-deep steps of each slice, the other the last two.  The LDS traffic
+// per MFMA is unchanged; what it buys is two waves per SIMD for a small tile (one CU's 128 x 128),
+// so that one wave's waits (LDS, barrier) hide behind the other's MFMAs.  After the last slice the
+// pair exchanges, through the idle ring, the 32-row bands each does not finish, and each runs the
+// epilogue for its own bands.
 // =====================================================================================
 #define CAKE_GLOBAL_AS __attribute__((address_space(1)))
 #define CAKE_LDS_AS __attribute__((address_space(3)))
