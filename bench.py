@@ -75,8 +75,8 @@ def recorded_traffic(kernel_class, default_workload):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3)
-    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--shape", default="llama3-8b-shape")
     ap.add_argument("--tokens", type=int, default=32768)
     ap.add_argument("--chunk", type=int, default=1024)
@@ -238,7 +238,9 @@ def main():
                                % (shape.name, T, C, pt, args.gbps),
                    "global_batch": 1, "seq_len": T, "parallelism": "single-gpu"},
         "ttft_s": {"bidirectional": round(ttft, 5), "compute_only": round(r_c.ttft_ns / 1e9, 5),
-                   "load_only": round(r_l.ttft_ns / 1e9, 5)},
+                   "load_only": round(r_l.ttft_ns / 1e9, 5),
+                   "bidirectional_median": round(float(np.median([r.ttft_ns for r in runs])) / 1e9, 5),
+                   "bidirectional_min": round(min(r.ttft_ns for r in runs) / 1e9, 5)},
         "speedup": {"over_load_only": round(r_l.ttft_ns / 1e9 / ttft, 3),
                     "over_compute_only": round(r_c.ttft_ns / 1e9 / ttft, 3)},
         "sum_ttft_over_baselines": round(ttft / (r_c.ttft_ns / 1e9) + ttft / (r_l.ttft_ns / 1e9), 4),
