@@ -473,11 +473,6 @@ int32_t cake_op_rope_kv_write(cake_ctx* ctx, const float* qkv, void* q, int32_t 
  * against layer `layer` of kv's pages, keys 0 .. tok_begin+rows-1. */
 int32_t cake_op_attention(cake_ctx* ctx, const void* q, void* out, int32_t layer,
                           int32_t tok_begin, int32_t rows, const cake_kv* kv);
-/* The same attention with the queries taken from qkv[rows][(n_q+2n_kv)*hd] (float32, not rotated): the kernel
- * rotates them at positions tok_begin+row itself (what the prefill does; Sec. 3).  K and V must already be in
- * the pages.  bf16 contexts with head_dim 128 only.  Errors: CAKE_E_INVAL. */
-int32_t cake_op_attention_qkv(cake_ctx* ctx, const float* qkv, void* out, int32_t layer,
-                              int32_t tok_begin, int32_t rows, const cake_kv* kv);
 /* out[n_q][hd] (float32) = attention of ONE query per head, q[n_q][hd] (float32, already rotated),
  * against keys 0 .. n_keys-1 of layer `layer` (the first-token step's attention).  Needs a
  * context created with head weights (it owns the split workspace). */

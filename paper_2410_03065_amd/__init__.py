@@ -30,7 +30,7 @@ EXPORTS = [
     "cake_schedule_bandwidth_step", "cake_chunk_state", "cake_sync_compute", "cake_sync_load",
     "cake_range_flops", "cake_page_image_bytes", "cake_simulate_race", "cake_op_rmsnorm",
     "cake_op_gemm", "cake_op_gemm_residual", "cake_op_gemm_swiglu", "cake_op_gemm_plan", "cake_op_mfma_rate", "cake_op_rope_kv_write",
-    "cake_op_attention", "cake_op_attention_qkv", "cake_profile_enable", "cake_profile_read", "cake_adaptive_serve", "cake_first_token",
+    "cake_op_attention", "cake_profile_enable", "cake_profile_read", "cake_adaptive_serve", "cake_first_token",
     "cake_op_decode_attention", "cake_set_traces", "cake_store_image_bytes", "cake_write_store", "cake_prefix_keys", "cake_prefix_lookup",
 ]
 STORE_RAW, STORE_INT8, STORE_INT4 = 0, 1, 2
@@ -166,7 +166,6 @@ def load_library():
         "cake_op_mfma_rate": (i32, [vp, i32, i32, P(C.c_double)]),
         "cake_op_rope_kv_write": (i32, [vp, vp, vp, i32, i32, i32, P(Kv)]),
         "cake_op_attention": (i32, [vp, vp, vp, i32, i32, i32, P(Kv)]),
-        "cake_op_attention_qkv": (i32, [vp, vp, vp, i32, i32, i32, P(Kv)]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -680,15 +679,6 @@ class Engine:
         out = self.torch.empty((rows, self.shape.n_q * self.shape.head_dim), dtype=self.tdtype, device=self.dev)
         self._check(self.lib.cake_op_attention(self.ctx, q.data_ptr(), out.data_ptr(), layer, tok_begin, rows,
                                                C.byref(self.kv)), "cake_op_attention")
-        self.sync()
-        return out
-
-    def op_attention_qkv(self, qkv, layer, tok_begin):
-        """Attention with the queries taken, unrotated, from the float32 QKV product [rows][(n_q+2n_kv)*hd]."""
-        rows = qkv.shape[0]
-        out = self.torch.empty((rows, self.shape.n_q * self.shape.head_dim), dtype=self.tdtype, device=self.dev)
-        self._check(self.lib.cake_op_attention_qkv(self.ctx, qkv.data_ptr(), out.data_ptr(), layer, tok_begin, rows,
-                                                   C.byref(self.kv)), "cake_op_attention_qkv")
         self.sync()
         return out
 

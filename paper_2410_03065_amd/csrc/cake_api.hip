@@ -149,16 +149,9 @@ static hipError_t gemm(cake_ctx* c, int epi, const void* a, const void* w, const
     return launch_gemm_generic(c->m.dtype, epi, a, w, w2, out, M, N, K, c->cs);
 }
 
-static bool attention_uses_mfma(const cake_ctx* c, const KvView& kv) {
-    return c->m.dtype == CAKE_BF16 && c->tun.kernel_path == 0 && attention_mfma_supported(kv.head_dim, kv.page_tokens);
-}
-
-// qs.qkv != nullptr (MFMA kernels only): the kernel takes the queries from the QKV product and rotates them itself
-static hipError_t attention(cake_ctx* c, const void* q, void* out, int tok_begin, int rows, const KvView& kv,
-                            QSource qs = QSource{nullptr, nullptr, 0}) {
-    if (attention_uses_mfma(c, kv))
-        return launch_attention_mfma(q, out, c->m.n_q_heads, tok_begin, rows, kv, c->cs, c->tun.attn_variant, qs);
-    if (!q) return hipErrorInvalidValue;
+static hipError_t attention(cake_ctx* c, const void* q, void* out, int tok_begin, int rows, const KvView& kv) {
+    if (c->m.dtype == CAKE_BF16 && c->tun.kernel_path == 0 && attention_mfma_supported(kv.head_dim, kv.page_tokens))
+        return launch_attention_mfma(q, out, c->m.n_q_heads, tok_begin, rows, kv, c->cs, c->tun.attn_variant);
     return launch_attention_generic(c->m.dtype, q, out, c->m.n_q_heads, tok_begin, rows, kv, c->cs);
 }
 
@@ -194,11 +187,7 @@ static int enqueue_prefill(cake_ctx* c, int tok_begin, int rows, const cake_kv* 
     const uint64_t t0 = tok_begin;
     // algorithmic work per launch: flops of the contraction; bytes = operands once + result once
     const uint64_t attn_flops = 4 * hq * (t0 * R + R * (R + 1) / 2);
-    // the MFMA attention kernels rotate the queries themselves (from the float32 QKV product): the rotary kernel
-    // then only has the keys and values to do, and Q is rounded to bf16 once instead of twice
-    const bool fused_q = attention_uses_mfma(c, make_view(c, kv, 0));
-    const uint64_t attn_bytes = (2 * R * hq + 2 * hkv * (t0 + R)) * e + (fused_q ? R * hq * (4 - e) : 0);
-    const uint64_t rope_cols = fused_q ? 2 * hkv : nqkv;
+    const uint64_t attn_bytes = (2 * R * hq + 2 * hkv * (t0 + R)) * e;
     KLAUNCH(c, CAKE_K_EMBED, 0, R * d * (e + 4), launch_embed(m.dtype, c->embed, c->d_ids + tok_begin, c->x, rows, d, m.vocab, c->cs));
     HIP_TRY(c, launch_rope_table(c->rope_cs, tok_begin, rows, m.head_dim, m.rope_theta, c->cs));
     for (int l = 0; l < m.n_layers; ++l) {
@@ -207,11 +196,9 @@ static int enqueue_prefill(cake_ctx* c, int tok_begin, int rows, const cake_kv* 
         KLAUNCH(c, CAKE_K_RMSNORM, 0, R * d * (4 + e), launch_rmsnorm(m.dtype, c->x, w.attn_norm, c->h, rows, d, m.rms_eps, c->cs));
         KLAUNCH(c, CAKE_K_GEMM_QKV, 2 * R * nqkv * d, (R * d + nqkv * d) * e + R * nqkv * 4,
                 gemm(c, EPI_STORE_F32, c->h, w.wqkv, nullptr, c->qkv, rows, nqkv, d));
-        KLAUNCH(c, CAKE_K_ROPE_KV, 0, R * rope_cols * (4 + e),
-                launch_rope_kv_write(m.dtype, c->qkv, c->rope_cs, c->q, m.n_q_heads, tok_begin, rows, view, c->cs, fused_q));
-        KLAUNCH(c, CAKE_K_ATTENTION, attn_flops, attn_bytes,
-                attention(c, c->q, c->ao, tok_begin, rows, view,
-                          fused_q ? QSource{c->qkv, (const float2*)c->rope_cs, int(nqkv)} : QSource{nullptr, nullptr, 0}));
+        KLAUNCH(c, CAKE_K_ROPE_KV, 0, R * nqkv * (4 + e),
+                launch_rope_kv_write(m.dtype, c->qkv, c->rope_cs, c->q, m.n_q_heads, tok_begin, rows, view, c->cs));
+        KLAUNCH(c, CAKE_K_ATTENTION, attn_flops, attn_bytes, attention(c, c->q, c->ao, tok_begin, rows, view));
         KLAUNCH(c, CAKE_K_GEMM_O, 2 * R * d * hq, (R * hq + d * hq) * e + 2 * R * d * 4,
                 gemm(c, EPI_RESIDUAL_F32, c->ao, w.wo, nullptr, c->x, rows, d, hq));
         KLAUNCH(c, CAKE_K_RMSNORM, 0, R * d * (4 + e), launch_rmsnorm(m.dtype, c->x, w.ffn_norm, c->h, rows, d, m.rms_eps, c->cs));
@@ -1181,20 +1168,6 @@ int32_t cake_op_attention(cake_ctx* c, const void* q, void* out, int32_t layer, 
     int rc = check_kv(c, kv, tok_begin + rows);
     if (rc != CAKE_OK) return rc;
     HIP_TRY(c, attention(c, q, out, tok_begin, rows, make_view(c, kv, layer)));
-    return CAKE_OK;
-}
-
-int32_t cake_op_attention_qkv(cake_ctx* c, const float* qkv, void* out, int32_t layer, int32_t tok_begin, int32_t rows,
-                              const cake_kv* kv) {
-    if (!c || !qkv || !out || layer < 0 || layer >= c->m.n_layers || tok_begin < 0 || rows < 0 || rows > c->max_chunk)
-        return CAKE_E_INVAL;
-    int rc = check_kv(c, kv, tok_begin + rows);
-    if (rc != CAKE_OK) return rc;
-    const KvView view = make_view(c, kv, layer);
-    if (!attention_uses_mfma(c, view)) return fail(c, CAKE_E_INVAL, "op_attention_qkv: only the bf16 MFMA attention kernels rotate Q themselves");
-    const int ldq = (c->m.n_q_heads + 2 * c->m.n_kv_heads) * c->m.head_dim;
-    HIP_TRY(c, launch_rope_table(c->rope_cs, tok_begin, rows, c->m.head_dim, c->m.rope_theta, c->cs));
-    HIP_TRY(c, attention(c, nullptr, out, tok_begin, rows, view, QSource{qkv, (const float2*)c->rope_cs, ldq}));
     return CAKE_OK;
 }
 

@@ -30,9 +30,8 @@ hipError_t launch_rmsnorm(int dtype, const float* x, const float* gain, void* ou
                           float eps, hipStream_t st);
 hipError_t launch_rope_table(float* cs, int tok_begin, int rows, int head_dim, float theta,
                              hipStream_t st);
-// kv_only: leave the query heads alone (the attention kernel rotates them itself); q may then be null.
 hipError_t launch_rope_kv_write(int dtype, const float* qkv, const float* cs, void* q, int n_q,
-                                int tok_begin, int rows, const KvView& kv, hipStream_t st, bool kv_only = false);
+                                int tok_begin, int rows, const KvView& kv, hipStream_t st);
 hipError_t launch_gemm_generic(int dtype, int epi, const void* a, const void* w, const void* w2,
                                void* out, int M, int N, int K, hipStream_t st);
 hipError_t launch_attention_generic(int dtype, const void* q, void* out, int n_q, int tok_begin,
@@ -62,16 +61,8 @@ hipError_t launch_mfma_rate(float* out, int workgroups, int iters, hipStream_t s
 bool attention_mfma_supported(int head_dim, int page_tokens);
 // variant: 0 = eight-wave kernel, 128 or 64 queries per workgroup by grid size; 1 = four-wave kernel;
 // 2 / 3 = eight-wave kernel with 128 / 64 queries per workgroup (testing).
-// Where the MFMA attention kernels may take their queries from instead of a rotated bf16 copy: the float32
-// QKV product (row stride ldq elements, query head h at column h * head_dim) and the (cos, sin) table of the
-// rows' positions; the kernels then rotate Q themselves.  qkv == nullptr: use the rotated copy `q`.
-struct QSource {
-    const float* qkv;
-    const float2* cs;
-    int ldq;
-};
 hipError_t launch_attention_mfma(const void* q, void* out, int n_q, int tok_begin, int rows,
-                                 const KvView& kv, hipStream_t st, int variant = 0, QSource qs = QSource{nullptr, nullptr, 0});
+                                 const KvView& kv, hipStream_t st, int variant = 0);
 
 bool decode_attention_mfma_supported(int dtype, int head_dim, int page_tokens, int r);
 hipError_t launch_decode_attention_mfma(const float* q, float* part, int n_q, int n_keys, int tiles_per_split,

@@ -23,23 +23,6 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 #define CAKE_GLOBAL_AS __attribute__((address_space(1)))
 #define CAKE_LDS_AS __attribute__((address_space(3)))
 
-// Q operand of one lane, taken straight from the QKV product: elements 16*ks + 8*lhalf .. +7 of row
-// `src_row` (float32), rotated by that row's position (Sec. 3: rotary embedding of queries; pairs
-// (2i, 2i+1), the table holds (cos, sin) per pair), times `scale`, rounded to bf16 once.
-__device__ __forceinline__ void load_rotated_q(bf16x8* qreg, const float* src_row, const float2* cs_row, int lhalf, float scale) {
-    const float* src = src_row + 8 * lhalf;
-    const float2* cs = cs_row + 4 * lhalf;
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-        const float4 v0 = *(const float4*)(src + 16 * ks), v1 = *(const float4*)(src + 16 * ks + 4);
-        const float4 c0 = *(const float4*)(cs + 8 * ks), c1 = *(const float4*)(cs + 8 * ks + 2);
-        qreg[ks][0] = bf16_t((v0.x * c0.x - v0.y * c0.y) * scale); qreg[ks][1] = bf16_t((v0.x * c0.y + v0.y * c0.x) * scale);
-        qreg[ks][2] = bf16_t((v0.z * c0.z - v0.w * c0.w) * scale); qreg[ks][3] = bf16_t((v0.z * c0.w + v0.w * c0.z) * scale);
-        qreg[ks][4] = bf16_t((v1.x * c1.x - v1.y * c1.y) * scale); qreg[ks][5] = bf16_t((v1.x * c1.y + v1.y * c1.x) * scale);
-        qreg[ks][6] = bf16_t((v1.z * c1.z - v1.w * c1.w) * scale); qreg[ks][7] = bf16_t((v1.z * c1.w + v1.w * c1.z) * scale);
-    }
-}
-
 // =====================================================================================
 // Attention: out[row][h*128 + :] = softmax_s(q_row . k_s / sqrt(128)) v_s over keys s <= tok_begin+row.
 //
@@ -73,7 +56,7 @@ __device__ __forceinline__ int sigma16(int x) { return (x & 3) | ((x & 4) << 1) 
 
 __global__ void __launch_bounds__(256)
 attention_mfma_kernel(const bf16_t* __restrict__ q, bf16_t* __restrict__ out, int n_q, int tok_begin, int rows,
-                      KvView kv, int q_tiles, QSource qs) {
+                      KvView kv, int q_tiles) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -101,9 +84,7 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, bf16_t* __restrict__ out, in
 
     // Q^T operand: lane supplies q[my_row][16*ks + 8*lhalf .. +7]
     bf16x8 qreg[AHD / 16];
-    if (qs.qkv) {
-        load_rotated_q(qreg, qs.qkv + size_t(my_row) * qs.ldq + h * AHD, qs.cs + size_t(my_row) * (AHD / 2), lhalf, 1.0f);
-    } else {
+    {
         const bf16_t* qp = q + (size_t(h) * rows + my_row) * AHD + 8 * lhalf;
 #pragma unroll
         for (int ks = 0; ks < AHD / 16; ++ks) qreg[ks] = *(const bf16x8*)(qp + 16 * ks);
@@ -383,7 +364,7 @@ constexpr int A8_TABLE = 4 * A8_RING;        // page offsets after both rings
 template <int QW>
 __global__ void __launch_bounds__(128 * QW)
 attention_mfma8_kernel(const bf16_t* __restrict__ q, bf16_t* __restrict__ out, int n_q, int tok_begin, int rows,
-                       KvView kv, int q_tiles, QSource qs) {
+                       KvView kv, int q_tiles) {
     constexpr int AQW = 32 * QW;        // queries per workgroup
     constexpr int PER = 16 / QW;        // wave-loads per wave per K (or V^T) tile
     constexpr int KP = QW >= 4 ? 1 : 4 / QW;   // period after which the K swizzle term of a wave's loads repeats
@@ -416,19 +397,15 @@ attention_mfma8_kernel(const bf16_t* __restrict__ q, bf16_t* __restrict__ out, i
 
     bf16x8 qreg[AHD / 16];
     {
+        const bf16_t* qp = q + (size_t(h) * rows + my_row) * AHD + 8 * lhalf;
+#pragma unroll
+        for (int ks = 0; ks < AHD / 16; ++ks) qreg[ks] = *(const bf16x8*)(qp + 16 * ks);
         // softmax scale and log2(e) go into Q once, so a score leaves the MFMA in the exponent's units
         const float sl2q = 0.08838834764831845f * 1.4426950408889634f;
-        if (qs.qkv) {
-            load_rotated_q(qreg, qs.qkv + size_t(my_row) * qs.ldq + h * AHD, qs.cs + size_t(my_row) * (AHD / 2), lhalf, sl2q);
-        } else {
-            const bf16_t* qp = q + (size_t(h) * rows + my_row) * AHD + 8 * lhalf;
 #pragma unroll
-            for (int ks = 0; ks < AHD / 16; ++ks) qreg[ks] = *(const bf16x8*)(qp + 16 * ks);
+        for (int ks = 0; ks < AHD / 16; ++ks)
 #pragma unroll
-            for (int ks = 0; ks < AHD / 16; ++ks)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) qreg[ks][e] = bf16_t(float(qreg[ks][e]) * sl2q);
-        }
+            for (int e = 0; e < 8; ++e) qreg[ks][e] = bf16_t(float(qreg[ks][e]) * sl2q);
     }
     // lane offsets of this wave's K / V^T wave-loads of a tile: load i covers 1 KB = key rows
     // 4j .. 4j+3 (V^T: head-dim rows 8j .. 8j+7) with j = wave + QW*i.  The swizzle term of the K
@@ -869,8 +846,7 @@ bool attention_mfma_supported(int head_dim, int page_tokens) {
 }
 
 hipError_t launch_attention_mfma(const void* q, void* out, int n_q, int tok_begin, int rows, const KvView& kv,
-                                 hipStream_t st, int variant, QSource qs) {
-    if (!q && !qs.qkv) return hipErrorInvalidValue;
+                                 hipStream_t st, int variant) {
     if (rows <= 0) return hipSuccess;
     static bool attr_set = false;
     constexpr int LDS_MAX = 160 * 1024;
@@ -887,7 +863,7 @@ hipError_t launch_attention_mfma(const void* q, void* out, int n_q, int tok_begi
         const int LDS = A_STAGES * A_STAGE + table;
         if (LDS > LDS_MAX) return hipErrorInvalidValue;
         hipLaunchKernelGGL(attention_mfma_kernel, dim3(q_tiles * n_q), dim3(256), LDS, st, (const bf16_t*)q, (bf16_t*)out, n_q,
-                           tok_begin, rows, kv, q_tiles, qs);
+                           tok_begin, rows, kv, q_tiles);
     } else {
         const int LDS = A8_TABLE + table;
         if (LDS > LDS_MAX) return hipErrorInvalidValue;
@@ -898,10 +874,10 @@ hipError_t launch_attention_mfma(const void* q, void* out, int n_q, int tok_begi
         const bool small_wins = q_tiles64 > q_tiles && double(rounds64) * 64 / 0.85 < double(rounds128) * 128;
         if (variant == 3 || (variant == 0 && small_wins))
             hipLaunchKernelGGL(attention_mfma8_kernel<2>, dim3(q_tiles64 * n_q), dim3(256), LDS, st, (const bf16_t*)q, (bf16_t*)out,
-                               n_q, tok_begin, rows, kv, q_tiles64, qs);
+                               n_q, tok_begin, rows, kv, q_tiles64);
         else
             hipLaunchKernelGGL(attention_mfma8_kernel<4>, dim3(q_tiles * n_q), dim3(512), LDS, st, (const bf16_t*)q, (bf16_t*)out,
-                               n_q, tok_begin, rows, kv, q_tiles, qs);
+                               n_q, tok_begin, rows, kv, q_tiles);
     }
     return hipGetLastError();
 }

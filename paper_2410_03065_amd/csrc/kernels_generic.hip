@@ -155,12 +155,12 @@ hipError_t launch_rope_table(float* cs, int tok_begin, int rows, int head_dim, f
 template <typename T, int HD>
 __global__ void __launch_bounds__(256)
 rope_kv_write_kernel(const float* __restrict__ qkv, const float2* __restrict__ cs, T* __restrict__ q, int n_q,
-                     int tok_begin, int rows, KvView kv, int first_head) {
+                     int tok_begin, int rows, KvView kv) {
     constexpr int HALF = HD / 2;
     __shared__ T vt[64][HD + 2];
     const int n_kv = kv.n_kv;
     const int ldq = (n_q + 2 * n_kv) * HD;
-    const int head = blockIdx.y + first_head;   // first_head = n_q: the key and value heads only
+    const int head = blockIdx.y;
     const int tile_tok0 = (tok_begin / 64 + blockIdx.x) * 64;  // absolute
     const int lo = max(tile_tok0, tok_begin), hi = min(tile_tok0 + 64, tok_begin + rows);
     if (lo >= hi) return;
@@ -212,14 +212,14 @@ rope_kv_write_kernel(const float* __restrict__ qkv, const float2* __restrict__ c
 // transpose as 16-byte pieces of 8 consecutive tokens.
 __global__ void __launch_bounds__(256)
 rope_kv_write_bf16_hd128_kernel(const float* __restrict__ qkv, const float2* __restrict__ cs, bf16_t* __restrict__ q,
-                                int n_q, int tok_begin, int rows, KvView kv, int first_head) {
+                                int n_q, int tok_begin, int rows, KvView kv) {
     constexpr int HD = 128, HALF = 64;
     typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4_t;
     typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
     __shared__ bf16_t vt[64][HD + 2];
     const int n_kv = kv.n_kv;
     const int ldq = (n_q + 2 * n_kv) * HD;
-    const int head = blockIdx.y + first_head;   // first_head = n_q: the key and value heads only
+    const int head = blockIdx.y;
     const int tile_tok0 = (tok_begin / 64 + blockIdx.x) * 64;  // absolute
     const int lo = max(tile_tok0, tok_begin), hi = min(tile_tok0 + 64, tok_begin + rows);
     if (lo >= hi) return;
@@ -280,26 +280,24 @@ rope_kv_write_bf16_hd128_kernel(const float* __restrict__ qkv, const float2* __r
 }
 
 hipError_t launch_rope_kv_write(int dtype, const float* qkv, const float* cs, void* q, int n_q, int tok_begin,
-                                int rows, const KvView& kv, hipStream_t st, bool kv_only) {
+                                int rows, const KvView& kv, hipStream_t st) {
     if (rows <= 0) return hipSuccess;
-    if (!kv_only && !q) return hipErrorInvalidValue;
     int tiles = (tok_begin + rows - 1) / 64 - tok_begin / 64 + 1;
-    const int first_head = kv_only ? n_q : 0;
-    dim3 grid(tiles, n_q + 2 * kv.n_kv - first_head), block(256);
+    dim3 grid(tiles, n_q + 2 * kv.n_kv), block(256);
     const float2* c2 = (const float2*)cs;
     const bool aligned = ((uintptr_t(qkv) | uintptr_t(cs) | uintptr_t(q) | uintptr_t(kv.pool)) & 15) == 0;
     if (dtype == 1 && kv.head_dim == 128 && aligned) {
-        hipLaunchKernelGGL(rope_kv_write_bf16_hd128_kernel, grid, block, 0, st, qkv, c2, (bf16_t*)q, n_q, tok_begin, rows, kv, first_head);
+        hipLaunchKernelGGL(rope_kv_write_bf16_hd128_kernel, grid, block, 0, st, qkv, c2, (bf16_t*)q, n_q, tok_begin, rows, kv);
         return hipGetLastError();
     }
     if (dtype == 0 && kv.head_dim == 64)
-        hipLaunchKernelGGL((rope_kv_write_kernel<float, 64>), grid, block, 0, st, qkv, c2, (float*)q, n_q, tok_begin, rows, kv, first_head);
+        hipLaunchKernelGGL((rope_kv_write_kernel<float, 64>), grid, block, 0, st, qkv, c2, (float*)q, n_q, tok_begin, rows, kv);
     else if (dtype == 0 && kv.head_dim == 128)
-        hipLaunchKernelGGL((rope_kv_write_kernel<float, 128>), grid, block, 0, st, qkv, c2, (float*)q, n_q, tok_begin, rows, kv, first_head);
+        hipLaunchKernelGGL((rope_kv_write_kernel<float, 128>), grid, block, 0, st, qkv, c2, (float*)q, n_q, tok_begin, rows, kv);
     else if (dtype == 1 && kv.head_dim == 64)
-        hipLaunchKernelGGL((rope_kv_write_kernel<bf16_t, 64>), grid, block, 0, st, qkv, c2, (bf16_t*)q, n_q, tok_begin, rows, kv, first_head);
+        hipLaunchKernelGGL((rope_kv_write_kernel<bf16_t, 64>), grid, block, 0, st, qkv, c2, (bf16_t*)q, n_q, tok_begin, rows, kv);
     else if (dtype == 1 && kv.head_dim == 128)
-        hipLaunchKernelGGL((rope_kv_write_kernel<bf16_t, 128>), grid, block, 0, st, qkv, c2, (bf16_t*)q, n_q, tok_begin, rows, kv, first_head);
+        hipLaunchKernelGGL((rope_kv_write_kernel<bf16_t, 128>), grid, block, 0, st, qkv, c2, (bf16_t*)q, n_q, tok_begin, rows, kv);
     else
         return hipErrorInvalidValue;
     return hipGetLastError();

@@ -198,39 +198,6 @@ def test_attention(kind, path, variant, tok_begin, rows):
     assert _rel(got, want) < tol, _rel(got, want)
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 3])
-@pytest.mark.parametrize("tok_begin,rows", [(0, 130), (256, 256), (448, 77), (64, 1), (960, 200)])
-def test_attention_rotating_q_itself(variant, tok_begin, rows):
-    """The prefill's attention takes Q from the float32 QKV product and rotates it in the kernel (Sec. 3):
-    against the oracle's rotary embedding + attention, and against the two-kernel path of the same library."""
-    import torch
-    shape = SHAPE_BF
-    pt, T = 128, tok_begin + rows
-    n_log = (T + pt - 1) // pt
-    bt = np.random.default_rng(5).permutation(n_log).astype(np.int32)
-    eng = _engine(shape, n_log * pt, 256, pt, block_table=bt)
-    eng.set_tuning(attn_variant=variant)
-    rng = np.random.default_rng(40 + rows)
-    nq, nkv, hd = shape.n_q, shape.n_kv, shape.head_dim
-    cache = otf.KVCache(1, T, nkv, hd)
-    cache.k[0] = rng.standard_normal((T, nkv, hd)) * 1.5
-    cache.v[0] = rng.standard_normal((T, nkv, hd))
-    cache = _rounded(cache, "bf16")
-    eng.set_store(ostore.pack_store(cache, pt, "bf16"))
-    eng.load_chunk(0, T)
-    qkv = rng.standard_normal((rows, (nq + 2 * nkv) * hd)).astype(np.float32)   # the K and V columns are not read
-    pos = np.arange(tok_begin, T)
-    q_rot = otf.rope(qkv[:, :nq * hd].astype(np.float64).reshape(rows, nq, hd), pos, shape.rope_theta)
-    want = otf.attention(q_rot, cache.k[0], cache.v[0], pos, np.arange(T))
-    got = eng.op_attention_qkv(torch.from_numpy(qkv).cuda(), 0, tok_begin).float().cpu().numpy().reshape(rows, nq, hd)
-    assert _rel(got, want) < 1.2e-2, _rel(got, want)
-    # the separate rotary kernel (into scratch pages of another engine, so that this cache stays) + attention
-    other = _engine(shape, n_log * pt, 256, pt, block_table=bt)
-    q_dev = other.op_rope_kv_write(torch.from_numpy(qkv).cuda(), 0, tok_begin)
-    two = eng.op_attention(q_dev, 0, tok_begin).float().cpu().numpy().reshape(rows, nq, hd)
-    assert _rel(got, two) < 1.2e-2, _rel(got, two)
-
-
 def test_attention_and_page_write_above_2_and_4_gib():
     """Physical pages whose byte offset in the pool has bit 31 / bit 32 set (a 4 GiB pool is what
     the 32K-token benchmark uses): offsets must be formed in unsigned 64-bit arithmetic."""
