@@ -158,10 +158,13 @@ def _block_forward(x: np.ndarray, pos: np.ndarray, lw: Dict[str, np.ndarray], sh
 def prefill_chunked(weights, shape, tokens: np.ndarray, chunk: int,
                     kv_dtype: Optional[str] = None, cache: Optional[KVCache] = None,
                     tok_begin: int = 0, tok_end: Optional[int] = None,
-                    return_hidden: bool = False):
+                    return_hidden: bool = False,
+                    layer_inputs: Optional[Dict[int, List[np.ndarray]]] = None):
     """Chunk prefill (Sec. 3): tokens [tok_begin, tok_end) in pieces of ``chunk``
     tokens (the last may be shorter), each attending to everything cached before it.
-    ``cache`` must already hold [0, tok_begin)."""
+    ``cache`` must already hold [0, tok_begin).  ``layer_inputs``, if given, maps a layer
+    index to a list that receives a copy of that layer's input rows for every chunk, in
+    order (index ``n_layers`` = the output of the last layer); nothing is computed for it."""
     tokens = np.asarray(tokens)
     T = len(tokens)
     tok_end = T if tok_end is None else tok_end
@@ -175,7 +178,11 @@ def prefill_chunked(weights, shape, tokens: np.ndarray, chunk: int,
         pos = np.arange(t0, t1)
         x = np.asarray(embed[tokens[t0:t1]], dtype=F64)
         for l, lw in enumerate(layers):
+            if layer_inputs is not None and l in layer_inputs:
+                layer_inputs[l].append(x.copy())
             x = _block_forward(x, pos, lw, shape, cache, l, kv_dtype)
+        if layer_inputs is not None and len(layers) in layer_inputs:
+            layer_inputs[len(layers)].append(x.copy())
         cache.filled = t1
         hidden = x
     return (cache, hidden) if return_hidden else cache
