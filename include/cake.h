@@ -479,6 +479,19 @@ int32_t cake_op_attention(cake_ctx* ctx, const void* q, void* out, int32_t layer
 int32_t cake_op_decode_attention(cake_ctx* ctx, const float* q, float* out, int32_t layer,
                                  int32_t n_keys, const cake_kv* kv);
 
+/* cake_op_decode_attention for callers that cannot allocate device memory (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): same arguments, same kernels and
+ * the same result, but the per-key-range partial results go to a buffer that is part of the
+ * library's image on each GPU (4 259 840 bytes, held until the process ends) instead of one that
+ * cake_create allocated, so the call makes no hipMalloc / hipFree and works on a context created
+ * without head weights.  Limit: n_q_heads * (head_dim + 2) <= 64 * 130, i.e. up to 64 query heads
+ * of head dimension 128; a larger model is refused with CAKE_E_INVAL.  Every call on a GPU shares
+ * that GPU's one buffer (each launch writes every entry it later reads, so nothing is cleared
+ * between calls): calls that overlap on one GPU, from different streams or contexts, race.
+ * Asynchronous on the compute stream.  Errors: CAKE_E_INVAL, CAKE_E_STATE, CAKE_E_HIP. */
+int32_t cake_op_decode_attention_static(cake_ctx* ctx, const float* q, float* out, int32_t layer,
+                                        int32_t n_keys, const cake_kv* kv);
+
 #ifdef __cplusplus
 }
 #endif

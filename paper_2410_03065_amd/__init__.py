@@ -31,7 +31,7 @@ EXPORTS = [
     "cake_range_flops", "cake_page_image_bytes", "cake_simulate_race", "cake_op_rmsnorm",
     "cake_op_gemm", "cake_op_gemm_residual", "cake_op_gemm_swiglu", "cake_op_gemm_plan", "cake_op_mfma_rate", "cake_op_rope_kv_write",
     "cake_op_attention", "cake_profile_enable", "cake_profile_read", "cake_adaptive_serve", "cake_first_token",
-    "cake_op_decode_attention", "cake_set_traces", "cake_store_image_bytes", "cake_write_store", "cake_prefix_keys", "cake_prefix_lookup",
+    "cake_op_decode_attention", "cake_op_decode_attention_static", "cake_set_traces", "cake_store_image_bytes", "cake_write_store", "cake_prefix_keys", "cake_prefix_lookup",
 ]
 STORE_RAW, STORE_INT8, STORE_INT4 = 0, 1, 2
 STORE_PINNED, STORE_FILE = 0, 1
@@ -146,6 +146,7 @@ def load_library():
         "cake_prefix_lookup": (i32, [vp, i32, vp, i32]),
         "cake_write_store": (i32, [vp, P(Kv), i32, P(KvStore)]),
         "cake_op_decode_attention": (i32, [vp, vp, vp, i32, i32, P(Kv)]),
+        "cake_op_decode_attention_static": (i32, [vp, vp, vp, i32, i32, P(Kv)]),
         "cake_set_bandwidth": (i32, [vp, dbl]),
         "cake_schedule_bandwidth_step": (i32, [vp, i32, dbl]),
         "cake_chunk_state": (i32, [vp, i32]),
@@ -502,11 +503,15 @@ class Engine:
             out.decisions = _decisions_to_list(dec, res.n_decisions)
         return out
 
-    def op_decode_attention(self, q, layer, n_keys):
-        """q: float32 device tensor [n_q][hd] -> float32 [n_q][hd]."""
-        out = self.torch.empty_like(q)
-        self._check(self.lib.cake_op_decode_attention(self.ctx, q.data_ptr(), out.data_ptr(), layer, n_keys,
-                                                      C.byref(self.kv)), "cake_op_decode_attention")
+    def op_decode_attention(self, q, layer, n_keys, out=None, static=False):
+        """q: float32 device tensor [n_q][hd] -> float32 [n_q][hd].  static: the entry point that
+        allocates nothing (its partial results live in the library's own static buffer); `out` may be
+        a tensor made beforehand so that nothing is allocated around the call either."""
+        if out is None:
+            out = self.torch.empty_like(q)
+        fn = self.lib.cake_op_decode_attention_static if static else self.lib.cake_op_decode_attention
+        self._check(fn(self.ctx, q.data_ptr(), out.data_ptr(), layer, n_keys, C.byref(self.kv)),
+                    "cake_op_decode_attention_static" if static else "cake_op_decode_attention")
         self.sync()
         return out
 

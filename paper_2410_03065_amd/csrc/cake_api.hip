@@ -45,6 +45,7 @@ struct cake_ctx {
     float *t_h = nullptr, *t_q = nullptr, *t_qr = nullptr, *t_ao = nullptr, *t_act = nullptr, *t_logits = nullptr,
           *t_part = nullptr;
     int32_t* t_tok = nullptr;
+    void* static_scratch = nullptr;   // this device's copy of the file-scope scratch array (set by cake_create)
     GemmSplitWs split{};       // parts and ticket counters of the split-K GEMMs (bf16 models; compute stream only)
     void* q_stage = nullptr;   // device staging for quantised page images (allocated at the first use)
     size_t q_stage_bytes = 0;
@@ -79,6 +80,32 @@ struct cake_ctx {
     // the load worker of every race of this context (bound to the context's device when it starts)
     WorkerThread load_thread;
 };
+
+// Partial results of the one-token attention for callers that may not allocate device memory
+// (cake_op_decode_attention_static): one array per GPU the library runs on, held until the process
+// ends.  Sized for 64 query heads of head dimension 128 over the largest number of key ranges the
+// kernels use (128): 64 * 128 * 130 floats.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; kernels get the address that call returned for the current device.
+constexpr size_t STATIC_SCRATCH_BYTES = size_t(64) * 128 * (128 + 2) * sizeof(float);
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+constexpr int STATIC_SCRATCH_MAX_DEVICES = 64;
+static std::mutex g_scratch_mu;
+static void* g_scratch_ptr[STATIC_SCRATCH_MAX_DEVICES] = {};
+
+// Address of `scratch` on `device`, which must be the current device; looked up once per device.
+static hipError_t static_scratch_for_device(int device, void** out) {
+    if (device < 0 || device >= STATIC_SCRATCH_MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> g(g_scratch_mu);
+    if (!g_scratch_ptr[device]) {
+        void* p = nullptr;
+        hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[device] = p;
+    }
+    *out = g_scratch_ptr[device];
+    return hipSuccess;
+}
 
 static int fail(cake_ctx* ctx, int code, const char* fmt, ...) {
     char buf[512];
@@ -477,6 +504,7 @@ int32_t cake_create(cake_ctx** out, const cake_model_desc* model, const cake_wei
     const size_t e = esize(c), R = size_t(max_chunk);
     const size_t hq = size_t(m.n_q_heads) * m.head_dim, nqkv = size_t(m.n_q_heads + 2 * m.n_kv_heads) * m.head_dim;
     bool ok = hipGetDevice(&c->device) == hipSuccess;
+    ok = ok && static_scratch_for_device(c->device, &c->static_scratch) == hipSuccess;
     ok = ok && hipMalloc((void**)&c->x, R * m.d_model * 4) == hipSuccess;
     ok = ok && hipMalloc(&c->h, R * m.d_model * e) == hipSuccess;
     ok = ok && hipMalloc((void**)&c->qkv, R * nqkv * 4) == hipSuccess;
@@ -1179,6 +1207,24 @@ int32_t cake_op_decode_attention(cake_ctx* c, const float* q, float* out, int32_
     if (rc != CAKE_OK) return rc;
     HIP_TRY(c, launch_decode_attention(c->m.dtype, q, out, c->t_part, c->m.n_q_heads, n_keys, make_view(c, kv, layer), c->cs,
                                        c->tun.kernel_path == 1));
+    return CAKE_OK;
+}
+
+int32_t cake_op_decode_attention_static(cake_ctx* c, const float* q, float* out, int32_t layer, int32_t n_keys,
+                                        const cake_kv* kv) {
+    if (!c || !q || !out || layer < 0 || layer >= c->m.n_layers || n_keys <= 0 || n_keys > c->max_tokens)
+        return fail(c, CAKE_E_INVAL, "op_decode_attention_static: bad argument");
+    const size_t need = decode_attention_workspace_bytes(c->m.n_q_heads, c->m.head_dim);
+    if (need > STATIC_SCRATCH_BYTES)
+        return fail(c, CAKE_E_INVAL, "op_decode_attention_static: %d query heads of head dimension %d need %zu bytes of "
+                    "partial results, the static buffer holds %zu (64 heads of 128)", c->m.n_q_heads, c->m.head_dim, need,
+                    STATIC_SCRATCH_BYTES);
+    if (!c->static_scratch) return fail(c, CAKE_E_STATE, "op_decode_attention_static: no static buffer on this device");
+    int rc = check_kv(c, kv, n_keys);
+    if (rc != CAKE_OK) return rc;
+    // every key range that the combine kernel reads is written by this launch first: nothing needs clearing
+    HIP_TRY(c, launch_decode_attention(c->m.dtype, q, out, (float*)c->static_scratch, c->m.n_q_heads, n_keys,
+                                       make_view(c, kv, layer), c->cs, c->tun.kernel_path == 1));
     return CAKE_OK;
 }
 
