@@ -176,7 +176,10 @@ typedef struct {
                                fetch units smaller than the step, starting at token f_off of chunk `claimed` */
     int32_t pad_;
     uint64_t now_ns;
-    uint64_t o_c, o_l;                            /* predicted remaining ns of the work in flight on each side */
+    uint64_t o_c, o_l;                            /* predicted remaining ns of the work in flight on each side; o_c in the
+                                                     adaptive mode while higher priorities leave the request none of the step
+                                                     budget: the ns it has gone without tokens so far (expected to last as
+                                                     long again) */
     uint64_t est_compute_ns, est_compute_flops;   /* throughput sample: last <= 4 computed chunks, or the prior */
     uint64_t est_load_ns, est_load_bytes;         /* last loaded chunk, or the prior */
     uint64_t partial_ns;                          /* estimate of the unclaimed rest of chunk f when f_off > 0, else 0 */
@@ -220,8 +223,11 @@ typedef struct {
 /* ---- life cycle ------------------------------------------------------- */
 
 /* Creates a context on the current device: copies the layer table, allocates the
- * activation workspace for chunks of up to max_chunk tokens and a device buffer for
- * max_tokens token ids.  compute_stream / copy_stream: hipStream_t, default priority.
+ * activation workspace for chunks of up to max_chunk tokens, a device buffer for
+ * max_tokens token ids and the staging of the load path (device room for the 8-bit page
+ * images of max_chunk tokens; two pinned buffers of one DMA piece for file-backed stores),
+ * and starts the load worker.  Loads allocate nothing; a page of more than max_chunk tokens
+ * cannot be loaded from a quantised store.  compute_stream / copy_stream: hipStream_t, default priority.
  * Errors: CAKE_E_INVAL (shape not supported), CAKE_E_NOMEM, CAKE_E_HIP. */
 int32_t cake_create(cake_ctx** out, const cake_model_desc* model, const cake_weights* weights,
                     int32_t max_tokens, int32_t max_chunk, void* compute_stream, void* copy_stream);
@@ -244,10 +250,16 @@ int32_t cake_prefill_chunk(cake_ctx* ctx, const int32_t* token_ids, int32_t tok_
 /* Sec. 5.1 "I/O Bandwidth Control"; App. A step 5.  Copies the stored images of the logical
  * pages covering [tok_begin, tok_begin+tok_count) into their physical pages on the copy
  * stream, in pieces, releasing a piece only once the tier would have delivered it at `gbps`
- * (cumulative bytes issued <= gbps * elapsed).  Blocks the calling thread while pacing and
- * returns when the last piece is enqueued; the chunk is resident once the copy stream has
- * drained (cake_sync_load or an event of the caller's).  tok_begin must be page aligned.
- * gbps <= 0 means unthrottled.  Errors: CAKE_E_INVAL, CAKE_E_STORE_MISS, CAKE_E_HIP. */
+ * (cumulative bytes issued <= gbps * elapsed).  Asynchronous: the arguments are checked, the
+ * range is handed to the context's load worker (a thread that lives with the context) and the
+ * call returns; the worker paces the pieces onto the copy stream.  Ranges queued by several
+ * calls are loaded in call order.  The chunk is resident once cake_sync_load has returned
+ * CAKE_OK; a failure that only shows while loading (a short read from a file-backed store) is
+ * returned by that cake_sync_load.  The two descriptor structs are copied; the store's bytes,
+ * the pool and the host block table stay borrowed until cake_sync_load returns.
+ * tok_begin must be page aligned.  gbps <= 0 means unthrottled.  Nothing is allocated.
+ * Errors (all before anything is queued): CAKE_E_INVAL, CAKE_E_STORE_MISS (the store holds
+ * fewer pages than the range needs). */
 int32_t cake_load_chunk(cake_ctx* ctx, const cake_kv_store* store, int32_t tok_begin,
                         int32_t tok_count, const cake_kv* kv, double gbps);
 
@@ -398,8 +410,11 @@ int32_t cake_schedule_bandwidth_step(cake_ctx* ctx, int32_t after_loaded_chunks,
 /* The paper's is_resident (App. B.2 step 4): cake_chunk_status of a chunk of the running or
  * last cake_bidirectional_prefill; negative cake_status on a bad index. */
 int32_t cake_chunk_state(const cake_ctx* ctx, int32_t chunk);
-/* Blocks until the compute / copy stream has drained. */
+/* Blocks until the compute stream has drained. */
 int32_t cake_sync_compute(cake_ctx* ctx);
+/* Blocks until every range queued by cake_load_chunk has been issued and the copy stream has
+ * drained.  Returns the first failure of such a load since the previous call (CAKE_E_STORE_MISS,
+ * CAKE_E_HIP; text in cake_last_error), else CAKE_OK. */
 int32_t cake_sync_load(cake_ctx* ctx);
 
 /* Algorithmic FLOPs of prefilling tokens [tok_begin, tok_begin+tok_count): projections
@@ -478,7 +493,6 @@ int32_t cake_op_attention(cake_ctx* ctx, const void* q, void* out, int32_t layer
  * context created with head weights (it owns the split workspace). */
 int32_t cake_op_decode_attention(cake_ctx* ctx, const float* q, float* out, int32_t layer,
                                  int32_t n_keys, const cake_kv* kv);
-
 /* cake_op_decode_attention for callers that cannot allocate device memory (code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc): same arguments, same kernels and
  * the same result, but the per-key-range partial results go to a buffer that is part of the

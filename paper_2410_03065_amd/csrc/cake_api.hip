@@ -47,7 +47,7 @@ struct cake_ctx {
     int32_t* t_tok = nullptr;
     void* static_scratch = nullptr;   // this device's copy of the file-scope scratch array (set by cake_create)
     GemmSplitWs split{};       // parts and ticket counters of the split-K GEMMs (bf16 models; compute stream only)
-    void* q_stage = nullptr;   // device staging for quantised page images (allocated at the first use)
+    void* q_stage = nullptr;   // device staging for quantised page images: a ring of image slots (cake_create)
     size_t q_stage_bytes = 0;
     // second hop of a file-backed store: two pinned buffers of one DMA piece each
     void* f_stage[2] = {nullptr, nullptr};
@@ -56,6 +56,7 @@ struct cake_ctx {
     hipEvent_t ev_a = nullptr, ev_b = nullptr;
     hipEvent_t ev_load = nullptr;   // blocking-sync event: the load worker sleeps until the copy stream has drained
     std::atomic<double> gbps{0.0};
+    std::atomic<int> async_load_rc{0};   // first failure of a load queued by cake_load_chunk since the last cake_sync_load
     int step_after = -1;
     double step_gbps = 0.0;
     // traces for the next cake_adaptive_serve (copied by cake_set_traces)
@@ -375,14 +376,14 @@ static int enqueue_load(cake_ctx* c, const cake_kv_store* st, int tok_begin, int
     if (p1 > st->n_pages) return fail(c, CAKE_E_STORE_MISS, "store holds %d pages, page %d requested", st->n_pages, p1 - 1);
     const uint64_t piece_max = c->tun.piece_bytes ? c->tun.piece_bytes : (4ull << 20);
     const int bits = store_code_bits(st->format);
-    if (bits) {
-        int rc = ensure_stage(c, uint64_t(p1 - p0) * image_bytes);
-        if (rc != CAKE_OK) return rc;
-    }
-    if (from_file) {
-        int rc = ensure_file_stage(c, piece_max);
-        if (rc != CAKE_OK) return rc;
-    }
+    // Nothing is allocated on a load: both staging areas belong to the context (cake_create, cake_set_tuning).
+    // Quantised images go through a ring of image slots; a slot is written again only after the dequantise
+    // kernel that read it, because copies and kernels of a load share the one copy stream.
+    const uint64_t n_slots = bits ? c->q_stage_bytes / image_bytes : 0;
+    if (bits && n_slots == 0)
+        return fail(c, CAKE_E_INVAL, "a quantised page image of %llu bytes exceeds the context's staging buffer (%llu): "
+                    "page_tokens above max_chunk", (unsigned long long)image_bytes, (unsigned long long)c->q_stage_bytes);
+    if (from_file && c->f_stage_bytes < piece_max) return fail(c, CAKE_E_STATE, "file staging smaller than a DMA piece");
     const uint64_t start = mono_ns();
     c->load_bytes_done.store(0);
     c->load_start_ns.store(start);
@@ -421,7 +422,7 @@ static int enqueue_load(cake_ctx* c, const cake_kv_store* st, int tok_begin, int
         if (bits) {
             // the whole image lands in the staging buffer, then one kernel on the copy stream
             // dequantises it into the page of every layer; stream order keeps the two apart
-            char* stage = (char*)c->q_stage + uint64_t(p - p0) * image_bytes;
+            char* stage = (char*)c->q_stage + (uint64_t(p - p0) % n_slots) * image_bytes;
             int rc = paced_copy(stage, img, image_bytes);
             if (rc != CAKE_OK) return rc;
             HIP_TRY(c, launch_dequant_page(m.dtype, stage, make_view(c, kv, 0), pp, m.n_layers, bits, c->ls));
@@ -458,7 +459,12 @@ struct HipBackend : Backend {
     }
     int load_chunk(int i) override {
         int rc = enqueue_load(c, store, tb[i], tc[i], kv, -1.0);
-        if (rc != CAKE_OK) return rc;
+        if (rc != CAKE_OK) {
+            // pieces (and dequantise kernels) of this chunk that were already issued must have landed before
+            // the chunk goes back to the range: the compute side may rewrite the same pages at once
+            (void)hipStreamSynchronize(c->ls);
+            return rc;
+        }
         if (drain_copy_stream(c) != hipSuccess) return fail(c, CAKE_E_HIP, "copy stream failed in chunk %d", i);
         return CAKE_OK;
     }
@@ -522,6 +528,13 @@ int32_t cake_create(cake_ctx** out, const cake_model_desc* model, const cake_wei
         ok = ok && hipMalloc((void**)&c->split.counters, size_t(c->split.n_counters) * 4) == hipSuccess;
         ok = ok && hipMemset(c->split.counters, 0, size_t(c->split.n_counters) * 4) == hipSuccess;
     }
+    {
+        // staging of the load path, so that no load allocates: device room for the 8-bit images (the largest
+        // quantised format) of max_chunk tokens, and two pinned buffers of one DMA piece for file-backed stores
+        const uint64_t per_token = cake::store_image_bytes(m, 64, CAKE_STORE_INT8) / 64;
+        ok = ok && ensure_stage(c, per_token * uint64_t(max_chunk)) == CAKE_OK;
+        ok = ok && ensure_file_stage(c, c->tun.piece_bytes) == CAKE_OK;
+    }
     ok = ok && hipEventCreate(&c->ev_a) == hipSuccess && hipEventCreate(&c->ev_b) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&c->ev_load, hipEventBlockingSync | hipEventDisableTiming) == hipSuccess;
     if (weights->final_norm && weights->lm_head) {
@@ -580,6 +593,9 @@ int32_t cake_set_tuning(cake_ctx* c, const cake_tuning* t) {
     if (t->piece_bytes) {
         if (t->piece_bytes < 4096) return fail(c, CAKE_E_INVAL, "piece_bytes below 4096");
         c->tun.piece_bytes = t->piece_bytes;
+        c->load_thread.wait();   // a queued load may be using the staging buffers this resizes
+        int rc = ensure_file_stage(c, t->piece_bytes);
+        if (rc != CAKE_OK) return rc;
     }
     if (t->kernel_path < 0 || t->kernel_path > 1) return fail(c, CAKE_E_INVAL, "kernel_path must be 0 or 1");
     c->tun.kernel_path = t->kernel_path;
@@ -616,7 +632,24 @@ int32_t cake_load_chunk(cake_ctx* c, const cake_kv_store* store, int32_t tok_beg
     if (tok_begin < 0 || tok_count < 0) return fail(c, CAKE_E_INVAL, "negative token range");
     int rc = check_kv(c, kv, tok_begin + tok_count);
     if (rc != CAKE_OK) return rc;
-    return enqueue_load(c, store, tok_begin, tok_count, kv, gbps > 0 ? gbps : 0.0);
+    rc = check_store(c, store, kv);
+    if (rc != CAKE_OK) return rc;
+    if (tok_begin % kv->page_tokens) return fail(c, CAKE_E_INVAL, "load range must start on a page boundary");
+    if ((tok_begin + tok_count + kv->page_tokens - 1) / kv->page_tokens > store->n_pages)
+        return fail(c, CAKE_E_STORE_MISS, "store holds %d pages, the range needs more", store->n_pages);
+    // The range goes to the context's load worker, which paces the pieces onto the copy stream; this call
+    // returns at once.  The two descriptors are copied, what they point to stays borrowed until cake_sync_load.
+    const cake_kv_store st = *store;
+    const cake_kv k = *kv;
+    const double rate = gbps > 0 ? gbps : 0.0;
+    c->load_thread.submit([c, st, k, tok_begin, tok_count, rate] {
+        int r = enqueue_load(c, &st, tok_begin, tok_count, &k, rate);
+        if (r != CAKE_OK) {
+            int expected = CAKE_OK;
+            c->async_load_rc.compare_exchange_strong(expected, r);   // the first failure is the one reported
+        }
+    });
+    return CAKE_OK;
 }
 
 int32_t cake_bidirectional_prefill(cake_ctx* c, const int32_t* token_ids, int32_t n_tokens,
@@ -912,6 +945,19 @@ int32_t cake_adaptive_serve(cake_ctx* c, cake_request* reqs, int32_t n_reqs, int
             c->load_thread.submit([&] { ex.worker(W_LOAD, be); });
             loader_started = true;
         }
+        // The prefix-cached request's KV is complete as soon as nothing is left to claim and the loader's
+        // last chunk has landed.  Looked at before every step, not only when the engine is idle: its
+        // first-token step is priority 1 and must go into this very step even while other requests keep
+        // the budget busy.
+        if (P >= 0 && loader_started && !kv_complete[P]) {
+            std::lock_guard<std::mutex> g(ex.mu);
+            if (ex.core.range_empty() && !ex.core.w[W_LOAD].busy && ex.first_error == CAKE_OK) {
+                uint64_t end = prefix_compute_end;
+                for (int i = 0; i < nc; ++i) if (ex.chunk_log[i].source == CAKE_SRC_LOAD) end = std::max(end, ex.chunk_log[i].end_ns);
+                finish_kv(P, end, &n_done);
+                if (n_done >= n_reqs) break;
+            }
+        }
         // ---- deal the budget out: (1) decoding requests, one token each: here the first-token step
         // of a request whose KV is complete; (2) prefill of requests without a stored prefix, oldest
         // first; (3) the rest to the prefix-cached request, as far as the plan gives it to the compute side
@@ -938,11 +984,16 @@ int32_t cake_adaptive_serve(cake_ctx* c, cake_request* reqs, int32_t n_reqs, int
         }
         int got = 0, first = -1;
         const bool prefix_live = P >= 0 && !kv_complete[P] && reqs[P].arrival_ns <= now;
-        if (prefix_live && left > 0) {
+        if (prefix_live) {
             std::lock_guard<std::mutex> g(ex.mu);
-            ex.refresh_load_progress(be);
-            got = ex.core.claim_front(now, left, &first);
-            if (got > 0) { ++ex.gen; ex.cv.notify_all(); }
+            // no budget left for the request: the plan must know that its compute side is not coming soon
+            if (left <= 0 && !ex.core.starved) { ex.core.starved = true; ex.core.starved_since = now; }
+            if (left > 0) ex.core.starved = false;
+            if (left > 0) {
+                ex.refresh_load_progress(be);
+                got = ex.core.claim_front(now, left, &first);
+                if (got > 0) { ++ex.gen; ex.cv.notify_all(); }
+            }
         }
         if (got > 0) parts.push_back({P, first, got, false});
 
@@ -1095,8 +1146,9 @@ int32_t cake_sync_compute(cake_ctx* c) {
 
 int32_t cake_sync_load(cake_ctx* c) {
     if (!c) return CAKE_E_INVAL;
-    HIP_TRY(c, hipStreamSynchronize(c->ls));
-    return CAKE_OK;
+    c->load_thread.wait();                      // every queued load has issued its last piece
+    HIP_TRY(c, hipStreamSynchronize(c->ls));    // ... and the pieces have landed
+    return c->async_load_rc.exchange(CAKE_OK);  // first failure of a queued load since the last call (text in cake_last_error)
 }
 
 int32_t cake_profile_enable(cake_ctx* c, int32_t on) {

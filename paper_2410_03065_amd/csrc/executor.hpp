@@ -6,6 +6,7 @@
 #include <atomic>
 #include <chrono>
 #include <condition_variable>
+#include <deque>
 #include <functional>
 #include <mutex>
 #include <thread>
@@ -31,8 +32,9 @@ inline uint64_t mono_ns() {
                         std::chrono::steady_clock::now().time_since_epoch()).count());
 }
 
-// A thread that lives as long as its owner and runs one job at a time: the load worker of every
-// race of a context runs here, so that no thread is created on the path whose latency is measured.
+// A thread that lives as long as its owner and runs the jobs handed to it one at a time, in the order
+// they were handed over: the load worker of every race of a context runs here, and so do the loads
+// queued by cake_load_chunk, so that no thread is created on the path whose latency is measured.
 class WorkerThread {
 public:
     WorkerThread() = default;
@@ -46,10 +48,11 @@ public:
             if (on_start) on_start();
             std::unique_lock<std::mutex> lk(mu_);
             for (;;) {
-                cv_.wait(lk, [&] { return quit_ || job_; });
-                if (quit_) return;
-                std::function<void()> j = std::move(job_);
-                job_ = nullptr;
+                cv_.wait(lk, [&] { return quit_ || !jobs_.empty(); });
+                if (jobs_.empty()) return;   // quit, and nothing left to run
+                std::function<void()> j = std::move(jobs_.front());
+                jobs_.pop_front();
+                busy_ = true;
                 lk.unlock();
                 j();
                 lk.lock();
@@ -59,23 +62,22 @@ public:
         });
     }
     bool running() const { return th_.joinable(); }
-    // one job at a time: the caller waits for the previous one first
+    // never blocks: the job runs after those handed over before it
     void submit(std::function<void()> job) {
-        std::unique_lock<std::mutex> lk(mu_);
-        cv_.wait(lk, [&] { return !busy_; });
-        busy_ = true;
-        job_ = std::move(job);
+        std::lock_guard<std::mutex> lk(mu_);
+        jobs_.push_back(std::move(job));
         cv_.notify_all();
     }
+    // until every job handed over so far has finished
     void wait() {
         std::unique_lock<std::mutex> lk(mu_);
-        cv_.wait(lk, [&] { return !busy_; });
+        cv_.wait(lk, [&] { return !busy_ && jobs_.empty(); });
     }
     void stop() {
         if (!th_.joinable()) return;
         {
             std::unique_lock<std::mutex> lk(mu_);
-            cv_.wait(lk, [&] { return !busy_; });
+            cv_.wait(lk, [&] { return !busy_ && jobs_.empty(); });
             quit_ = true;
             cv_.notify_all();
         }
@@ -86,7 +88,7 @@ private:
     std::thread th_;
     std::mutex mu_;
     std::condition_variable cv_;
-    std::function<void()> job_;
+    std::deque<std::function<void()>> jobs_;
     bool busy_ = false, quit_ = false;
 };
 

@@ -138,6 +138,12 @@ struct RaceCore {
     // progress of the load in flight, if the executor can observe it (bytes the tier has delivered
     // so far and the time that took); 0 bytes = unknown
     uint64_t load_prog_ns = 0, load_prog_bytes = 0;
+    // Adaptive mode: the compute side is free but gets no tokens of the step budget (higher priorities
+    // take all of it) since `starved_since`.  Its offset in the plan is then the time it has gone without
+    // tokens so far -- a starvation is expected to last about as long again as it already has -- so that
+    // the loader takes over chunks the compute side would only reach much later.
+    bool starved = false;
+    uint64_t starved_since = 0;
     cake_decision_log* log = nullptr;
     int log_cap = 0, log_n = 0;
     bool log_overflow = false;
@@ -145,7 +151,7 @@ struct RaceCore {
 
     void init(int n_chunks, const uint64_t* fl, const uint64_t* by, int md, int fm) {
         n = n_chunks; f = 0; b = n_chunks - 1; flops = fl; bytes = by; mode = md; forced_m = fm; f_off = 0;
-        w[0] = Worker(); w[1] = Worker(); log_n = 0; log_overflow = false;
+        w[0] = Worker(); w[1] = Worker(); log_n = 0; log_overflow = false; starved = false; starved_since = 0;
         if (mode == CAKE_COMPUTE_ONLY) w[W_LOAD].retired = true;
         if (mode == CAKE_LOAD_ONLY) w[W_COMPUTE].retired = true;
     }
@@ -162,6 +168,7 @@ struct RaceCore {
         est.compute_state(&p.D, &p.F);
         est.load_state(&p.LN, &p.LB);
         p.oc = (w[W_COMPUTE].busy && w[W_COMPUTE].pred_end > now) ? w[W_COMPUTE].pred_end - now : 0;
+        if (!w[W_COMPUTE].busy && starved && now > starved_since) p.oc = now - starved_since;
         p.ol = (w[W_LOAD].busy && w[W_LOAD].pred_end > now) ? w[W_LOAD].pred_end - now : 0;
         if (w[W_LOAD].busy && load_prog_bytes > 0 && w[W_LOAD].inflight >= 0) {
             // the chunk in flight tells the tier's current rate sooner than its completion would

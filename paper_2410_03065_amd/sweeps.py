@@ -89,7 +89,7 @@ def main():
                 t = res.ttft_ns / 1e9
                 cells.append("%.3f (%.2f \\\\ %.2f) m=%d" % (t, load_only[gb] / t, t_c / t, per_req[0]["tokens_computed"]))
             print("| %.1f %% | %.3f | %s |" % (share * 100, t_c, " | ".join(cells)))
-        print("\nload-only s: " + ", ".join("%g Gbps %.3f" % (g, load_only[g]) for g in args.gbit))
+        print("\nload-only s: " + ", ".join("%g Gbps %.5f" % (g, load_only[g]) for g in args.gbit))
     if args.compression:
         r_c = eng.bidirectional_prefill(toks, B, 4.0, mode="compute_only", log=False)     # also refills the pool for the writers
         t_c = r_c.ttft_ns / 1e9
@@ -111,6 +111,10 @@ def main():
         print("|---|---|---|---|")
         for gb in args.gbit:
             print("| %g Gbps | %s |" % (gb, " | ".join(rows[gb])))
+    if args.compression and (args.chunks or args.lengths):
+        # the compression table left its last (4-bit) store in place: the tables below are about 16-bit KV
+        eng.bidirectional_prefill(toks, B, 4.0, mode="compute_only", log=False)
+        eng.store_from_pool(T)
     if args.chunks:
         gb = args.gbit[0]
         r_c = eng.bidirectional_prefill(toks, B, gb / 8.0, mode="compute_only")

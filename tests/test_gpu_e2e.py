@@ -88,6 +88,24 @@ def _check_decisions(res, shape, T, C, pt, step_tokens=None, page_bytes=None):
         assert c["work"] == (fl if c["source"] == 0 else by)
 
 
+def _virtual_meet(r_c, byts, rate, slow=1.0, split=1):
+    """Where the library's claim protocol ends in VIRTUAL time (cake_simulate_race: the decision code of the
+    threaded executor, no clock, no threads) when computing chunk i costs what the GPU measured for it in
+    the compute-only run `r_c` (times `slow`) and loading it costs bytes / rate.  split > 1: every chunk of
+    `r_c` stands for that many equal units (one entry of `byts` each).  Trends between stores or budget
+    shares are asserted on this number, which depends on the method and the GPU's kernel times only; the
+    threaded runs are then held to it with an explicit margin."""
+    import paper_2410_03065_amd as cake
+    flops = [c["work"] // split for c in r_c.chunks for _ in range(split)]
+    comp = [max(1, int((c["end_ns"] - c["start_ns"]) * slow / split)) for c in r_c.chunks for _ in range(split)]
+    assert len(flops) == len(byts)
+    load = [max(1, int(b / rate)) for b in byts]
+    _, src, _ = cake.simulate_race(flops, byts, comp, load, prior_compute=(10 ** 9, 5 * 10 ** 14),
+                                   prior_load=(10 ** 9, max(1, int(rate * 1e9))))
+    assert src == sorted(src)                      # computed prefix, loaded suffix
+    return src.count(0)
+
+
 def test_config1_tiny_fp32_all_splits():
     """Tiny decoder, fp32, 2048 tokens, chunk 256, stored KV from the oracle's full prefill,
     1 GB/s: every forced split, the two baselines and the planned race."""
@@ -680,6 +698,85 @@ def test_first_token_needs_head_weights():
     assert e.value.code == cake.E_STATE
 
 
+def test_adaptive_first_token_does_not_wait_for_other_requests_to_drain():
+    """Sec. 4 Part 3: a decode token is priority 1.  A long request without a stored prefix keeps every
+    step's budget full (priority 2), so the prefix-cached request gets no compute tokens and its KV is
+    completed by the loader alone, in the middle of the other request's prefill.  Its first-token step
+    must ride in the very next engine step, not after the other request has finished."""
+    import paper_2410_03065_amd as cake
+    shape = si.TINY.with_(vocab=1000)
+    T, T_other, unit, budget, pt = 512, 16384, 256, 256, 128
+    w = si.make_weights(shape, seed=82, with_head=True)
+    eng = cake.Engine(shape, w, max_tokens=T_other, max_chunk=budget, page_tokens=pt)
+    toks = si.make_tokens(T, shape.vocab, seed=83)
+    ref = otf.prefill_chunked(w, shape, toks, unit, kv_dtype="f32")
+    eng.set_store(ostore.pack_store(ref, pt, "f32"))
+    kv, pool = eng.new_kv(T_other)
+    other = dict(tokens=si.make_tokens(T_other, shape.vocab, seed=84), arrival_ns=0, prefix=False, kv=kv, pool=pool)
+    reqs = [other, dict(tokens=toks, arrival_ns=0, prefix=True, first_token=True)]
+    _settle()
+    eng.adaptive_serve(reqs, budget, unit, 4.0)                           # first use: set-up
+    eng.clear_pool()
+    res, per_req, steps = eng.adaptive_serve(reqs, budget, unit, 4.0)     # 2 MiB at 4 GB/s: ~0.5 ms of 64 steps
+    assert res.meet_point == 0 and per_req[1]["tokens_loaded"] == T       # the loader produced all of it
+    # ... because the plan counts the time the request has gone without tokens as the compute side's offset
+    # (with the prior's compute rate alone it would wait for the GPU that the other request holds)
+    looks = [d for d in res.decisions if d["who"] == 1]
+    assert looks and all(d["o_c"] == d["now_ns"] - steps[0]["start_ns"] for d in looks[1:]), looks
+    _check_decisions(res, shape, T, unit, pt)
+    kv_done = max(c["end_ns"] for c in res.chunks)
+    dec = [k for k, s in enumerate(steps) if s["decode_tokens"] == 1]
+    assert len(dec) == 1
+    d = dec[0]
+    nxt = next(k for k, s in enumerate(steps) if s["start_ns"] >= kv_done)     # the first step dealt after the KV was complete
+    assert d <= nxt, (d, nxt, kv_done, steps[d])
+    assert steps[d]["nonprefix_tokens"] == budget - 1                          # the other request was still mid-prefill
+    assert d < len(steps) - 8                                                  # ... with most of its steps still to come
+    assert per_req[1]["ttft_ns"] == steps[d]["end_ns"]
+    want = otf.first_token_logits(w, shape, toks, ref)
+    tok = per_req[1]["first_token"]
+    assert want[tok] >= want.max() - 2 * TOL["f32"] * np.abs(want).max()
+
+
+def test_load_chunk_returns_at_once_and_overlaps_prefill_chunk():
+    """cake_load_chunk hands its range to the load worker and returns; the paced copy then runs beside
+    cake_prefill_chunk calls on the compute stream (App. A steps 4 and 5 side by side, driven by the
+    caller instead of the planner).  Result against the oracle; the stored half byte for byte."""
+    import time
+    shape, T, C, pt = si.TINY.with_(vocab=1000), 2048, 256, 128
+    w, toks, eng = _setup(shape, T, C, pt, seed=21, scramble=True)
+    ref = otf.prefill_chunked(w, shape, toks, C, kv_dtype="f32")
+    images = ostore.pack_store(ref, pt, "f32")
+    want = ostore.decode_words(images, "f32")
+    eng.set_store(images)
+    eng.load_chunk(1024, 1024)                      # warm-up of both paths
+    eng.prefill_chunk(toks, 0, C)
+    eng.clear_pool()
+    half_bytes = 1024 * otf.kv_bytes_per_token(shape.n_layers, shape.n_kv, shape.head_dim, 4)     # 4 MiB
+    gbps = 0.02                                     # ... paced over 0.21 s
+    t0 = time.perf_counter()
+    eng.load_chunk(1024, 512, gbps=gbps, sync=False)
+    eng.load_chunk(1536, 512, gbps=gbps, sync=False)            # queued behind the first
+    t_call = time.perf_counter() - t0
+    for i in range(4):                                          # the front half, computed meanwhile
+        eng.prefill_chunk(toks, i * C, C)
+    t_compute = time.perf_counter() - t0
+    eng.sync()
+    t_all = time.perf_counter() - t0
+    paced = half_bytes / (gbps * 1e9)
+    assert t_call < 0.25 * paced, (t_call, paced)               # the calls did not wait for the pacing
+    assert t_compute < 0.5 * paced, (t_compute, paced)          # nor did the compute calls queue behind it
+    assert t_all >= 0.98 * paced                                # and the tier's rate was kept
+    assert _errs(eng.pool_images(T), want).max() < TOL["f32"]
+    np.testing.assert_array_equal(eng.pool_raw(T)[1024 // pt:].view(np.uint32), images[1024 // pt:])
+    # a range beyond the stored pages is refused before anything is queued
+    import paper_2410_03065_amd as cake
+    eng.store.n_pages = 12
+    with pytest.raises(cake.CakeError) as ei:
+        eng.load_chunk(1536, 512)
+    assert ei.value.code == cake.E_STORE_MISS
+
+
 def test_adaptive_mode_serves_first_tokens_at_priority_one():
     """Sec. 4 Part 3: decode tokens come first in every engine step.  Here the decode step of a
     request is its first-token step, taken in the engine step after its KV is complete.  Tokens and
@@ -840,8 +937,15 @@ def test_gpu_utilisation_levels():
         computed[share] = per_req[0]["tokens_computed"]
         timeline[share] = ([(s["start_ns"] // 1000, s["end_ns"] // 1000, s["prefix_tokens"]) for s in steps],
                            [(c["start_ns"] // 1000, c["end_ns"] // 1000) for c in res.chunks if c["source"] == 1])
-    # tier as fast as the whole GPU: about 1/2, 1/3 and 1/9 of the prompt computed
-    assert computed[1.0] > computed[0.5] > computed[0.125] > 0, (computed, timeline)
+    # Tier as fast as the whole GPU: about 1/2, 1/3 and 1/9 of the prompt computed.  The trend is asserted in
+    # virtual time on the GPU's own per-unit compute times (a share s of every step makes a unit cost 1/s as
+    # much); each threaded run must end within one compute step (4 units) + 1 unit of its virtual twin.
+    r_s = eng.bidirectional_prefill(toks, step, 4.0, mode="compute_only")
+    byts = [unit * otf.kv_bytes_per_token(shape.n_layers, shape.n_kv, shape.head_dim, 2)] * (len(toks) // unit)
+    virt = {share: _virtual_meet(r_s, byts, rate, slow=1.0 / share, split=step // unit) for share in computed}
+    assert virt[1.0] > virt[0.5] > virt[0.125] > 0, virt
+    for share in computed:
+        assert abs(computed[share] // unit - virt[share]) <= step // unit + 1, (share, computed, virt, timeline)
     # the trace applied to one run only
     eng.clear_pool()
     _, _, steps = eng.adaptive_serve(reqs, step, unit, rate)
@@ -960,7 +1064,7 @@ def test_bidirectional_with_int4_store_moves_the_meet_point_further_left():
     full = eng.pool_raw(T).copy()
     # a tier half as fast as this GPU computes 16-bit KV: the transfer then outweighs the fixed cost of a load
     rate = 0.5 * T * otf.kv_bytes_per_token(shape.n_layers, shape.n_kv, shape.head_dim, 2) / r_c.ttft_ns
-    meet, ppc = {}, C // pt
+    meet, virt, ppc = {}, {}, C // pt
     for fmt in (cake.STORE_INT8, cake.STORE_INT4):
         eng.bidirectional_prefill(toks, C, 4.0, mode="compute_only", log=False)
         t = eng.write_store(T, fmt).numpy().copy()
@@ -971,6 +1075,7 @@ def test_bidirectional_with_int4_store_moves_the_meet_point_further_left():
         raw = eng.pool_raw(T)
         np.testing.assert_array_equal(raw[:m * ppc], full[:m * ppc])         # computed chunks: the compute-only bytes
         per_page = int(eng.lib.cake_store_image_bytes(C_byref_model(eng), pt, fmt))
+        virt[fmt] = _virtual_meet(r_c, [ppc * per_page] * (T // C), rate)
         assert r.load_bytes == (T // C - m) * ppc * per_page
         _check_decisions(r, shape, T, C, pt, page_bytes=per_page)
         # loaded pages: the oracle's dequantisation of the very codes the store holds
@@ -978,7 +1083,11 @@ def test_bidirectional_with_int4_store_moves_the_meet_point_further_left():
             img = t.reshape(T // pt, shape.n_layers, 2, -1)
             deq = ostore.pack_store(ostore.unpack_store_int4(img, T, shape.n_kv, shape.head_dim, pt, "bf16"), pt, "bf16")
             np.testing.assert_array_equal(raw[m * ppc:].view(np.uint16), deq[m * ppc:])
-    assert 0 < meet[cake.STORE_INT4] < meet[cake.STORE_INT8] < T // C
+    # the trend, in virtual time on the measured compute times (no clock involved); the threaded runs within
+    # two chunks of it (dequantising on arrival and the host's wake-ups are not in the virtual model)
+    assert 0 < virt[cake.STORE_INT4] < virt[cake.STORE_INT8] < T // C, virt
+    for fmt in meet:
+        assert 0 < meet[fmt] < T // C and abs(meet[fmt] - virt[fmt]) <= 2, (meet, virt)
 
 
 def C_byref_model(eng):
@@ -1052,5 +1161,11 @@ def test_bidirectional_with_int8_store_moves_the_meet_point_left():
     assert all(c["work"] == ppc * per_page8 for c in r8.chunks if c["source"] == 1)
     assert r8.load_bytes == (T // C - m) * ppc * per_page8
     _check_decisions(r8, shape, T, C, pt, page_bytes=per_page8)
-    # about 6 of 16 chunks loaded with 16-bit KV, about 9 with 8-bit KV
-    assert 0 < r8.meet_point < r16.meet_point
+    # about 6 of 16 chunks loaded with 16-bit KV, about 9 with 8-bit KV: the trend in virtual time on the
+    # measured compute times, the threaded runs within two chunks of it
+    per_page16 = pt * otf.kv_bytes_per_token(shape.n_layers, shape.n_kv, shape.head_dim, 2)
+    v16 = _virtual_meet(r_c, [ppc * per_page16] * (T // C), rate)
+    v8 = _virtual_meet(r_c, [ppc * per_page8] * (T // C), rate)
+    assert 0 < v8 < v16 < T // C, (v8, v16)
+    assert 0 < r8.meet_point < T // C and abs(r8.meet_point - v8) <= 2 and abs(r16.meet_point - v16) <= 2, \
+        (r8.meet_point, v8, r16.meet_point, v16)
