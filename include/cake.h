@@ -212,8 +212,8 @@ typedef struct {
     uint64_t prior_compute_ns, prior_compute_flops; /* default 1e9 ns per 5e14 FLOP */
     uint64_t piece_bytes;                           /* largest single DMA; default 4 MiB */
     int32_t kernel_path; /* 0: MFMA kernels where the shape allows (bf16); 1: generic kernels only */
-    int32_t gemm_config; /* 0: tile shape chosen per GEMM; 1..6: force 256x256 / 256x128 / 128x128 / 128x192 / 128x64 /
-                            128x128 with the waves dividing K (testing) */
+    int32_t gemm_config; /* 0: tile shape chosen per GEMM; 1..7: force 256x256 / 256x128 / 128x128 / 128x192 / 128x64 /
+                            128x128 with the waves dividing K / the persistent four-wave 256x256 kernel (testing) */
     int32_t attn_variant; /* 0: eight-wave attention kernel, 128 or 64 queries per workgroup by grid size;
                              1: four-wave kernel; 2 / 3: eight-wave with 128 / 64 queries (testing) */
     int32_t gemm_ksplit; /* 0: K of the residual / plain GEMMs split over 2, 4 or 8 workgroups per tile where a cost

@@ -599,7 +599,7 @@ int32_t cake_set_tuning(cake_ctx* c, const cake_tuning* t) {
     }
     if (t->kernel_path < 0 || t->kernel_path > 1) return fail(c, CAKE_E_INVAL, "kernel_path must be 0 or 1");
     c->tun.kernel_path = t->kernel_path;
-    if (t->gemm_config < 0 || t->gemm_config > 6) return fail(c, CAKE_E_INVAL, "gemm_config must be 0..6");
+    if (t->gemm_config < 0 || t->gemm_config > 7) return fail(c, CAKE_E_INVAL, "gemm_config must be 0..7");
     c->tun.gemm_config = t->gemm_config;
     if (t->attn_variant < 0 || t->attn_variant > 3) return fail(c, CAKE_E_INVAL, "attn_variant must be 0..3");
     c->tun.attn_variant = t->attn_variant;

@@ -333,6 +333,226 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
 }
 
 // =====================================================================================
+// Persistent GEMM for shapes with many 256 x 256 tiles (the gate/up product): out = a * w^T as above.
+//
+// What bounds a 256 x 256 tile on this chip is the LDS port, then the texture addresser: with eight
+// waves of 128 x 64 the operand reads plus the incoming tile data keep the LDS busy for as long as the
+// MFMAs take, and a burst of loads after the slice barrier fills the addresser's FIFO, which blocks the
+// issuing wave (and its MFMAs) until it drains.  So here:
+//  * four waves of 128 x 128 (8 x 8 tiles of v_mfma_f32_16x16x32_bf16, 256 accumulator registers each):
+//    16 operand reads per 64 MFMAs instead of 24, two thirds of the LDS read traffic;
+//  * K in 64-deep slices (whole 128-byte lines from L2, half the requests of 32-deep slices), each slice
+//    two 32 KB items (the A rows, the W rows) in a ring of five LDS slots filled by buffer loads to LDS;
+//    row r of an item stores its 16-byte chunk c at c ^ ((r >> 1) & 7), so the sixteen rows a
+//    quarter-wave reads hit all 64 banks once;
+//  * a slice is two phases of 64 MFMAs: phase A computes k-step 0 while the operands of k-step 1 are read
+//    and the A item of slice g+2 is loaded; then one barrier (this slice's slots are free, the next slice
+//    has landed); phase B computes k-step 1 while the first operands of slice g+1 are read and the W item
+//    of slice g+2 is loaded into a slot just freed.  Inside a phase the source interleaves two operand
+//    reads with one load, eight times, and sched_group_barrier pins 2 MFMAs between any two of them: no
+//    burst anywhere (a load to LDS and an LDS read may not pass each other, so source order is issue
+//    order);
+//  * workgroups are persistent: each takes its tiles one after another, the loads of the next tile's first
+//    slices are already in flight during the epilogue, and the grid is a whole number of rounds
+//    (448 tiles -> 224 workgroups of two tiles).  Past the end of its tiles a workgroup's loads use an
+//    empty buffer descriptor: they return zeros into slots nobody reads again, which keeps the load count
+//    per phase, and with it the s_waitcnt arithmetic, the same in every iteration.
+// Rows past M are read as zeros and their stores dropped by the buffer bounds checks.
+// SwiGLU: the 256 W rows of a tile alternate between the two matrices in groups of sixteen (even MFMA
+// tiles of a wave hold gate columns, odd ones the same columns of up), so the tile yields 128 output
+// columns and silu(gate) * up is formed in registers.
+// =====================================================================================
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+constexpr int P_ITEM = 256 * 128, P_SLOTS = 5, P_LDS = P_ITEM * P_SLOTS;
+
+template <int EPI>
+__global__ void __launch_bounds__(256)
+gemm_p256_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, const bf16_t* __restrict__ W2,
+                 void* __restrict__ outv, int M, int N, int K, int tiles_m, int tiles_n, int tiles_per_wg) {
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+    constexpr int OUT_COLS = EPI == EPI_SWIGLU ? 128 : 256;   // output columns per tile
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l16 = lane & 15, lq = lane >> 4;
+    const int nb = tiles_m * tiles_n, G = gridDim.x;
+    // tile u of this workgroup.  Workgroup b runs on XCD b % 8: where the counts divide, an XCD owns
+    // nb / 8 consecutive tiles (whole weight panels, shared through its L2 by workgroups in step).
+    const bool by_xcd = (nb & 7) == 0 && (G & 7) == 0;
+    const int xcd = blockIdx.x & 7, jw = blockIdx.x >> 3, per_xcd = nb >> 3, wg_per_xcd = G >> 3;
+    auto tile_of = [&](int u) { return by_xcd ? xcd * per_xcd + jw + u * wg_per_xcd : int(blockIdx.x) + u * G; };
+    int n_mine = 0;
+    for (int u = 0; u < tiles_per_wg; ++u)
+        if (by_xcd ? jw + u * wg_per_xcd < per_xcd : int(blockIdx.x) + u * G < nb) ++n_mine;
+    if (n_mine == 0) return;
+    const int nk = K / 64;
+
+    // ---- loads.  Wave-load wl = wave + 4 i of an item covers its rows 8 wl .. 8 wl + 7 (128 B each).
+    const int lr = lane >> 3, lpos = lane & 7;
+    const unsigned chunk = unsigned((lpos ^ (((wave & 1) << 2) + (lr >> 1))) << 4);
+    const unsigned voff_a = unsigned((8 * wave + lr) * K * 2) + chunk, step_a = unsigned(32 * K * 2);
+    // W rows: plain, item row = matrix row; SwiGLU, waves 0 and 1 fetch gate rows, waves 2 and 3 up rows
+    const unsigned voff_w = EPI == EPI_SWIGLU ? unsigned((8 * (wave & 1) + lr) * K * 2) + chunk : voff_a;
+    const unsigned step_w = EPI == EPI_SWIGLU ? unsigned(16 * K * 2) : step_a;
+    __amdgpu_buffer_rsrc_t ra, rw;
+    int ka = 0, ua = 0, kw = 0, uw = 0, slot_a = 0, slot_w = 1;
+    auto set_a = [&]() {
+        const int m0 = (tile_of(ua) % tiles_m) * 256;
+        ra = __builtin_amdgcn_make_buffer_rsrc((void*)(A + size_t(m0) * K), 0, min(256, M - m0) * K * 2, 0x00020000);
+    };
+    auto set_w = [&]() {
+        const int tn = tile_of(uw) / tiles_m;
+        const bf16_t* base = EPI == EPI_SWIGLU ? ((wave >> 1) ? W2 : W) + size_t(tn) * 128 * K : W + size_t(tn) * 256 * K;
+        rw = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, OUT_COLS * K * 2, 0x00020000);
+    };
+    auto next_a = [&]() {
+        slot_a = slot_a >= P_SLOTS - 2 ? slot_a + 2 - P_SLOTS : slot_a + 2;
+        if (++ka == nk) {
+            ka = 0; ++ua;
+            if (ua < n_mine) set_a();
+            else ra = __builtin_amdgcn_make_buffer_rsrc((void*)A, 0, 0, 0x00020000);
+        }
+    };
+    auto next_w = [&]() {
+        slot_w = slot_w >= P_SLOTS - 2 ? slot_w + 2 - P_SLOTS : slot_w + 2;
+        if (++kw == nk) {
+            kw = 0; ++uw;
+            if (uw < n_mine) set_w();
+            else rw = __builtin_amdgcn_make_buffer_rsrc((void*)W, 0, 0, 0x00020000);
+        }
+    };
+    auto load_item = [&](__amdgpu_buffer_rsrc_t rs, int slot, unsigned voff, int kk, unsigned step) {
+        unsigned char* dst = lds + slot * P_ITEM + wave * 1024;
+#pragma unroll
+        for (int r = 0; r < 8; ++r)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (CAKE_LDS_AS void*)(dst + r * 4096), 16, voff, kk * 128 + r * step, 0, 0);
+    };
+
+    // ---- operand reads: MFMA tile i of this wave = rows 16 i .. 16 i + 15 of its 128; k-step ks = chunks 4 ks .. 4 ks + 3
+    const int sw = (l16 >> 1) & 7;
+    const int a_lane = (wm * 128 + l16) * 128, b_lane = (wn * 128 + l16) * 128;
+    int kch[2];
+    kch[0] = (lq ^ sw) << 4;
+    kch[1] = ((4 + lq) ^ sw) << 4;
+    f32x4 acc[8][8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.f;
+    bf16x8 a0[8], b0[8], a1[8], b1[8];
+    auto rd = [&](bf16x8* a, bf16x8* b, int sa, int sb, int ks) {
+        const unsigned char* pa = lds + sa * P_ITEM + a_lane + kch[ks];
+        const unsigned char* pb = lds + sb * P_ITEM + b_lane + kch[ks];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) b[j] = *(const bf16x8*)(pb + j * 2048);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) a[i] = *(const bf16x8*)(pa + i * 2048);
+    };
+    // the same reads with the eight wave-loads of one item dealt between them
+    auto rd_ld = [&](bf16x8* a, bf16x8* b, int sa, int sb, int ks, __amdgpu_buffer_rsrc_t rs, int slot, unsigned voff, int kk,
+                     unsigned step) {
+        const unsigned char* pa = lds + sa * P_ITEM + a_lane + kch[ks];
+        const unsigned char* pb = lds + sb * P_ITEM + b_lane + kch[ks];
+        unsigned char* dst = lds + slot * P_ITEM + wave * 1024;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            if (r < 4) { b[2 * r] = *(const bf16x8*)(pb + (2 * r) * 2048); b[2 * r + 1] = *(const bf16x8*)(pb + (2 * r + 1) * 2048); }
+            else { a[2 * r - 8] = *(const bf16x8*)(pa + (2 * r - 8) * 2048); a[2 * r - 7] = *(const bf16x8*)(pa + (2 * r - 7) * 2048); }
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (CAKE_LDS_AS void*)(dst + r * 4096), 16, voff, kk * 128 + r * step, 0, 0);
+        }
+    };
+    auto mm = [&](const bf16x8* a, const bf16x8* b) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    };
+    auto mix = [&]() {   // 64 MFMAs, 16 operand reads, 8 loads
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
+    };
+
+    // prologue: items A0 W0 A1 W1 in flight (dummies past the end of the streams)
+    set_a(); set_w();
+    load_item(ra, slot_a, voff_a, ka, step_a); next_a();
+    load_item(rw, slot_w, voff_w, kw, step_w); next_w();
+    load_item(ra, slot_a, voff_a, ka, step_a); next_a();
+    load_item(rw, slot_w, voff_w, kw, step_w); next_w();
+    asm volatile("s_waitcnt vmcnt(16)");
+    __builtin_amdgcn_s_barrier();
+    int sa = 0, sb = 1;   // slots of the slice being consumed
+    rd(a0, b0, sa, sb, 0);
+    constexpr int OUT_ELT = EPI == EPI_SWIGLU ? 2 : 4;
+    const __amdgpu_buffer_rsrc_t obuf = __builtin_amdgcn_make_buffer_rsrc(outv, 0, int(size_t(M) * N * OUT_ELT), 0x00020000);
+    for (int u = 0; u < n_mine; ++u) {
+        for (int kt = 0; kt < nk; ++kt) {
+            // phase A: k-step 0; operands of k-step 1; the A item of the slice after next
+            rd_ld(a1, b1, sa, sb, 1, ra, slot_a, voff_a, ka, step_a);
+            mm(a0, b0);
+            mix();
+            next_a();
+            // this wave has read all of this slice; the next slice must have landed: only the item just issued may be out
+            asm volatile("s_waitcnt vmcnt(8)");
+            __builtin_amdgcn_s_barrier();
+            sa = sa >= P_SLOTS - 2 ? sa + 2 - P_SLOTS : sa + 2;
+            sb = sb >= P_SLOTS - 2 ? sb + 2 - P_SLOTS : sb + 2;
+            // phase B: k-step 1; first operands of the next slice; the W item of the slice after next into a freed slot
+            rd_ld(a0, b0, sa, sb, 0, rw, slot_w, voff_w, kw, step_w);
+            mm(a1, b1);
+            mix();
+            next_w();
+        }
+        // epilogue of tile u (the next tile's first slices are in flight); accumulator (i, j)[v] is row 16 i + 4 lq + v, column 16 j + l16
+        const int t = tile_of(u);
+        const int m0 = (t % tiles_m) * 256, c0 = (t / tiles_m) * OUT_COLS;
+        const int row0 = m0 + wm * 128 + 4 * lq;
+        if constexpr (EPI == EPI_SWIGLU) {
+            const unsigned base = unsigned(row0 * N + c0 + wn * 64 + l16) * 2u;
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+#pragma unroll
+                for (int j = 0; j < 8; j += 2)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const float g = acc[i][j][v], up = acc[i][j + 1][v];
+                        // silu(g) * up; the hardware reciprocal (1 ulp) instead of an IEEE division: the result is rounded to bf16
+                        const bf16_t o = bf16_t(g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * up);
+                        unsigned short bits;
+                        __builtin_memcpy(&bits, &o, 2);
+                        __builtin_amdgcn_raw_buffer_store_b16(bits, obuf, base + unsigned((i * 16 + v) * N + (j >> 1) * 16) * 2u, 0, 0);
+                        acc[i][j][v] = 0.f; acc[i][j + 1][v] = 0.f;
+                    }
+        } else {
+            const unsigned base = unsigned(row0 * N + c0 + wn * 128 + l16) * 4u;
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const unsigned off = base + unsigned((i * 16 + v) * N + j * 16) * 4u;
+                        float x = acc[i][j][v];
+                        if constexpr (EPI == EPI_RESIDUAL_F32) x += __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(obuf, off, 0, 0));
+                        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(x), obuf, off, 0, 0);
+                        acc[i][j][v] = 0.f;
+                    }
+        }
+        // loads and stores complete out of order with respect to each other: nothing is counted across them
+        asm volatile("s_waitcnt vmcnt(0)");
+    }
+}
+
+// =====================================================================================
 // Yardstick: what the matrix pipes deliver with nothing else going on.  Every wave runs `iters`
 // rounds of eight independent 32x32x16 bf16 MFMAs on operands it keeps in registers (no memory
 // traffic, no LDS, no barriers); one value per wave is written so that the work is not dead.
@@ -387,14 +607,18 @@ hipError_t launch_mfma_rate(float* out, int workgroups, int iters, hipStream_t s
 // Tile configurations.  Chosen per GEMM by gemm_pick() from how well the grid fills 256 CUs.
 struct GemmCfg { int bm, bn; };
 // GCFG_128x128K: the 128x128 tile as two 128x64 halves, each shared by two waves that divide K (KW = 2)
-enum { GCFG_256x256 = 0, GCFG_256x128 = 1, GCFG_128x128 = 2, GCFG_128x192 = 3, GCFG_128x64 = 4, GCFG_128x128K = 5, GCFG_COUNT = 6 };
-static const GemmCfg kGemmCfg[GCFG_COUNT] = {{256, 256}, {256, 128}, {128, 128}, {128, 192}, {128, 64}, {128, 128}};
+// GCFG_P256: the persistent four-wave kernel (256x256 tiles, several per workgroup)
+enum { GCFG_256x256 = 0, GCFG_256x128 = 1, GCFG_128x128 = 2, GCFG_128x192 = 3, GCFG_128x64 = 4, GCFG_128x128K = 5, GCFG_P256 = 6,
+       GCFG_COUNT = 7 };
+static const GemmCfg kGemmCfg[GCFG_COUNT] = {{256, 256}, {256, 128}, {128, 128}, {128, 192}, {128, 64}, {128, 128}, {256, 256}};
 
 static int out_cols_per_tile(int cfg, int epi) { return epi == EPI_SWIGLU ? kGemmCfg[cfg].bn / 2 : kGemmCfg[cfg].bn; }
 
 static bool gemm_cfg_ok(int cfg, int epi, int M, int N, int K) {
     if ((cfg == GCFG_128x192 || cfg == GCFG_128x64) && epi == EPI_SWIGLU) return false;   // odd n-tiles per wave: no gate/up pairs
     if (cfg == GCFG_128x128K && (epi == EPI_SWIGLU || (K % 64) != 0)) return false;
+    // the persistent kernel addresses everything through 32-bit buffer offsets
+    if (cfg == GCFG_P256 && ((K % 64) != 0 || double(M) * N * 4 >= 2147483648.0 || double(K) * 512 >= 2147483648.0)) return false;
     return M > 0 && N > 0 && K >= 32 && (K % 32) == 0 && (N % out_cols_per_tile(cfg, epi)) == 0;
 }
 
@@ -417,7 +641,7 @@ static bool ksplit_ok(int cfg, int ks, int epi, int M, int N, int K, const GemmS
     return tiles <= ws->n_counters && size_t(tiles) * ks * c.bm * c.bn * sizeof(float) <= ws->part_bytes;
 }
 static GemmChoice gemm_pick(int epi, int M, int N, int K, const GemmSplitWs* ws) {
-    static const double eff[GCFG_COUNT] = {1.0, 0.77, 0.62, 0.61, 0.40, 0.65};   // measured TFLOP/s per busy CU, relative to 256x256
+    static const double eff[GCFG_COUNT] = {1.0, 0.77, 0.62, 0.61, 0.40, 0.65, 1.25};   // measured TFLOP/s per busy CU, relative to 256x256
     GemmChoice best{GCFG_128x128, 1};
     double best_cost = 1e30;
     for (int cfg = GCFG_COUNT - 1; cfg >= 0; --cfg) {
@@ -427,6 +651,7 @@ static GemmChoice gemm_pick(int epi, int M, int N, int K, const GemmSplitWs* ws)
         const double area = double(c.bm) * c.bn / 65536.0;
         for (int ks = 1; ks <= 8; ks *= 2) {
             if (!ksplit_ok(cfg, ks, epi, M, N, K, ws)) continue;
+            if (cfg == GCFG_P256 && ks > 1) continue;
             const double rounds = double((tiles * ks + 255) / 256);
             double cost = rounds * (100.0 * area * (double(K) / ks / 4096.0) / eff[cfg] + 6.0);
             // measured: the parts cross the chip twice, at device scope; and a split must promise 8 % to be taken
@@ -460,6 +685,20 @@ template <int EPI>
 static hipError_t gemm_launch_cfg(int cfg, int ks, const GemmSplitWs* ws, const bf16_t* A, const bf16_t* W, const bf16_t* W2,
                                   void* out, int M, int N, int K, hipStream_t st) {
     const long tiles128 = long((M + 127) / 128) * (N / (EPI == EPI_SWIGLU ? 64 : 128)) * ks;
+    if (cfg == GCFG_P256) {
+        // a whole number of rounds: every workgroup takes `rounds` tiles (the last may take one less)
+        const int tiles_m = (M + 255) / 256, tiles_n = N / (EPI == EPI_SWIGLU ? 128 : 256), nb = tiles_m * tiles_n;
+        const int rounds = (nb + 255) / 256, wgs = (nb + rounds - 1) / rounds;
+        auto kern = gemm_p256_kernel<EPI>;
+        static bool attr_set = false;
+        if (!attr_set) {
+            hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS);
+            if (e != hipSuccess) return e;
+            attr_set = true;
+        }
+        hipLaunchKernelGGL(kern, dim3(wgs), dim3(256), P_LDS, st, A, W, W2, out, M, N, K, tiles_m, tiles_n, rounds);
+        return hipGetLastError();
+    }
     switch (cfg) {
         case GCFG_256x256: return gemm_launch_t<4, 2, 2, 4, 32, 5, EPI>(A, W, W2, out, M, N, K, st, ks, ws);
         case GCFG_256x128:
