@@ -346,8 +346,8 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
 //    row r of an item stores its 16-byte chunk c at c ^ ((r >> 1) & 7), so the sixteen rows a
 //    quarter-wave reads hit all 64 banks once;
 //  * a slice is two phases of 64 MFMAs: phase A computes k-step 0 while the operands of k-step 1 are read
-//    and the A item of slice g+2 is loaded; then one barrier (this slice's slots are free, the next slice
-//    has landed); phase B computes k-step 1 while the first operands of slice g+1 are read and the W item
+//    and the W item of slice g+2 is loaded; then one barrier (this slice's slots are free, the next slice
+//    has landed); phase B computes k-step 1 while the first operands of slice g+1 are read and the A item
 //    of slice g+2 is loaded into a slot just freed.  Inside a phase the source interleaves two operand
 //    reads with one load, eight times, and sched_group_barrier pins 2 MFMAs between any two of them: no
 //    burst anywhere (a load to LDS and an LDS read may not pass each other, so source order is issue
@@ -368,16 +368,20 @@ constexpr int P_ITEM = 256 * 128, P_SLOTS = 5, P_LDS = P_ITEM * P_SLOTS;
 template <int EPI>
 __global__ void __launch_bounds__(256)
 gemm_p256_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, const bf16_t* __restrict__ W2,
-                 void* __restrict__ outv, int M, int N, int K, int tiles_m, int tiles_n, int tiles_per_wg) {
+                 void* __restrict__ outv, int M, int N, int K, int tiles_m, int tiles_n, int tiles_per_wg,
+                 float* __restrict__ part, int ksplit) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     constexpr int OUT_COLS = EPI == EPI_SWIGLU ? 128 : 256;   // output columns per tile
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
     const int l16 = lane & 15, lq = lane >> 4;
-    const int nb = tiles_m * tiles_n, G = gridDim.x;
-    // tile u of this workgroup.  Workgroup b runs on XCD b % 8: where the counts divide, an XCD owns
-    // nb / 8 consecutive tiles (whole weight panels, shared through its L2 by workgroups in step).
+    // A work item is one tile over one of `ksplit` K ranges, numbered range-major (item = range * tiles + tile),
+    // so that consecutive items share a K range of the same weight panels.
+    const int n_tiles = tiles_m * tiles_n;
+    const int nb = n_tiles * ksplit, G = gridDim.x;
+    // item u of this workgroup.  Workgroup b runs on XCD b % 8: where the counts divide, an XCD owns
+    // nb / 8 consecutive items (whole weight panels, shared through its L2 by workgroups in step).
     const bool by_xcd = (nb & 7) == 0 && (G & 7) == 0;
     const int xcd = blockIdx.x & 7, jw = blockIdx.x >> 3, per_xcd = nb >> 3, wg_per_xcd = G >> 3;
     auto tile_of = [&](int u) { return by_xcd ? xcd * per_xcd + jw + u * wg_per_xcd : int(blockIdx.x) + u * G; };
@@ -385,7 +389,7 @@ gemm_p256_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
     for (int u = 0; u < tiles_per_wg; ++u)
         if (by_xcd ? jw + u * wg_per_xcd < per_xcd : int(blockIdx.x) + u * G < nb) ++n_mine;
     if (n_mine == 0) return;
-    const int nk = K / 64;
+    const int nk = K / ksplit / 64;   // slices per item
 
     // ---- loads.  Wave-load wl = wave + 4 i of an item covers its rows 8 wl .. 8 wl + 7 (128 B each).
     const int lr = lane >> 3, lpos = lane & 7;
@@ -395,15 +399,18 @@ gemm_p256_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
     const unsigned voff_w = EPI == EPI_SWIGLU ? unsigned((8 * (wave & 1) + lr) * K * 2) + chunk : voff_a;
     const unsigned step_w = EPI == EPI_SWIGLU ? unsigned(16 * K * 2) : step_a;
     __amdgpu_buffer_rsrc_t ra, rw;
-    int ka = 0, ua = 0, kw = 0, uw = 0, slot_a = 0, slot_w = 1;
+    int ka = 0, ua = 0, kw = 0, uw = 0, slot_a = 1, slot_w = 0;
+    // descriptors start at the item's first row and first K element
     auto set_a = [&]() {
-        const int m0 = (tile_of(ua) % tiles_m) * 256;
-        ra = __builtin_amdgcn_make_buffer_rsrc((void*)(A + size_t(m0) * K), 0, min(256, M - m0) * K * 2, 0x00020000);
+        const int q = tile_of(ua), t = q % n_tiles, kbeg = (q / n_tiles) * nk * 64;
+        const int m0 = (t % tiles_m) * 256;
+        ra = __builtin_amdgcn_make_buffer_rsrc((void*)(A + size_t(m0) * K + kbeg), 0, min(256, M - m0) * K * 2 - kbeg * 2, 0x00020000);
     };
     auto set_w = [&]() {
-        const int tn = tile_of(uw) / tiles_m;
+        const int q = tile_of(uw), t = q % n_tiles, kbeg = (q / n_tiles) * nk * 64;
+        const int tn = t / tiles_m;
         const bf16_t* base = EPI == EPI_SWIGLU ? ((wave >> 1) ? W2 : W) + size_t(tn) * 128 * K : W + size_t(tn) * 256 * K;
-        rw = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, OUT_COLS * K * 2, 0x00020000);
+        rw = __builtin_amdgcn_make_buffer_rsrc((void*)(base + kbeg), 0, OUT_COLS * K * 2 - kbeg * 2, 0x00020000);
     };
     auto next_a = [&]() {
         slot_a = slot_a >= P_SLOTS - 2 ? slot_a + 2 - P_SLOTS : slot_a + 2;
@@ -482,40 +489,61 @@ gemm_p256_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
         __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
     };
 
-    // prologue: items A0 W0 A1 W1 in flight (dummies past the end of the streams)
+    // prologue: items W0 A0 W1 A1 in flight (dummies past the end of the streams)
     set_a(); set_w();
-    load_item(ra, slot_a, voff_a, ka, step_a); next_a();
     load_item(rw, slot_w, voff_w, kw, step_w); next_w();
     load_item(ra, slot_a, voff_a, ka, step_a); next_a();
     load_item(rw, slot_w, voff_w, kw, step_w); next_w();
+    load_item(ra, slot_a, voff_a, ka, step_a); next_a();
     asm volatile("s_waitcnt vmcnt(16)");
     __builtin_amdgcn_s_barrier();
-    int sa = 0, sb = 1;   // slots of the slice being consumed
+    int sa = 1, sb = 0;   // slots of the slice being consumed
     rd(a0, b0, sa, sb, 0);
     constexpr int OUT_ELT = EPI == EPI_SWIGLU ? 2 : 4;
     const __amdgpu_buffer_rsrc_t obuf = __builtin_amdgcn_make_buffer_rsrc(outv, 0, int(size_t(M) * N * OUT_ELT), 0x00020000);
     for (int u = 0; u < n_mine; ++u) {
         for (int kt = 0; kt < nk; ++kt) {
-            // phase A: k-step 0; operands of k-step 1; the A item of the slice after next
-            rd_ld(a1, b1, sa, sb, 1, ra, slot_a, voff_a, ka, step_a);
+            // phase A: k-step 0; operands of k-step 1; the W item of the slice after next (the weights come from HBM
+            // and get the longer run-up: a slice and a half; the activations are L2 hits)
+            rd_ld(a1, b1, sa, sb, 1, rw, slot_w, voff_w, kw, step_w);
             mm(a0, b0);
             mix();
-            next_a();
+            next_w();
             // this wave has read all of this slice; the next slice must have landed: only the item just issued may be out
             asm volatile("s_waitcnt vmcnt(8)");
             __builtin_amdgcn_s_barrier();
             sa = sa >= P_SLOTS - 2 ? sa + 2 - P_SLOTS : sa + 2;
             sb = sb >= P_SLOTS - 2 ? sb + 2 - P_SLOTS : sb + 2;
-            // phase B: k-step 1; first operands of the next slice; the W item of the slice after next into a freed slot
-            rd_ld(a0, b0, sa, sb, 0, rw, slot_w, voff_w, kw, step_w);
+            // phase B: k-step 1; first operands of the next slice; the A item of the slice after next into a freed slot
+            rd_ld(a0, b0, sa, sb, 0, ra, slot_a, voff_a, ka, step_a);
             mm(a1, b1);
             mix();
-            next_w();
+            next_a();
         }
-        // epilogue of tile u (the next tile's first slices are in flight); accumulator (i, j)[v] is row 16 i + 4 lq + v, column 16 j + l16
-        const int t = tile_of(u);
+        // epilogue of item u (the next item's first slices are in flight); accumulator (i, j)[v] is row 16 i + 4 lq + v, column 16 j + l16
+        const int q = tile_of(u), t = q % n_tiles;
         const int m0 = (t % tiles_m) * 256, c0 = (t / tiles_m) * OUT_COLS;
         const int row0 = m0 + wm * 128 + 4 * lq;
+        bool finish = true;
+        if constexpr (EPI != EPI_SWIGLU) {
+            if (ksplit > 1) {
+                // This K range's accumulators go to the item's slot of the workspace, in accumulator order (each store
+                // is 4 KB contiguous over the workgroup); a second kernel adds the ranges up and runs the epilogue:
+                // a single workgroup reading a tile's parts back would take longer than the whole K loop.
+                constexpr int TILE_B = 256 * 256 * 4;
+                const __amdgpu_buffer_rsrc_t ws = __builtin_amdgcn_make_buffer_rsrc(part, 0, n_tiles * ksplit * TILE_B, 0x00020000);
+                const unsigned mine = (unsigned(t) * ksplit + unsigned(q / n_tiles)) * TILE_B + unsigned(tid) * 16;
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        u32x4 v = {__float_as_uint(acc[i][j][0]), __float_as_uint(acc[i][j][1]), __float_as_uint(acc[i][j][2]),
+                                   __float_as_uint(acc[i][j][3])};
+                        __builtin_amdgcn_raw_buffer_store_b128(v, ws, mine + (i * 8 + j) * 4096, 0, 0);
+                    }
+                finish = false;
+            }
+        }
         if constexpr (EPI == EPI_SWIGLU) {
             const unsigned base = unsigned(row0 * N + c0 + wn * 64 + l16) * 2u;
 #pragma unroll
@@ -532,23 +560,74 @@ gemm_p256_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
                         __builtin_amdgcn_raw_buffer_store_b16(bits, obuf, base + unsigned((i * 16 + v) * N + (j >> 1) * 16) * 2u, 0, 0);
                         acc[i][j][v] = 0.f; acc[i][j + 1][v] = 0.f;
                     }
-        } else {
+        } else if (finish) {
             const unsigned base = unsigned(row0 * N + c0 + wn * 128 + l16) * 4u;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                float old[8][4];
+                if constexpr (EPI == EPI_RESIDUAL_F32) {   // all 32 loads of a band of 16 rows in flight before the first add
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v)
+                            old[j][v] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(obuf, base + unsigned((i * 16 + v) * N + j * 16) * 4u, 0, 0));
+                }
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        float x = acc[i][j][v];
+                        if constexpr (EPI == EPI_RESIDUAL_F32) x += old[j][v];
+                        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(x), obuf, base + unsigned((i * 16 + v) * N + j * 16) * 4u, 0, 0);
+                        acc[i][j][v] = 0.f;
+                    }
+            }
+        } else {
 #pragma unroll
             for (int i = 0; i < 8; ++i)
 #pragma unroll
                 for (int j = 0; j < 8; ++j)
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const unsigned off = base + unsigned((i * 16 + v) * N + j * 16) * 4u;
-                        float x = acc[i][j][v];
-                        if constexpr (EPI == EPI_RESIDUAL_F32) x += __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(obuf, off, 0, 0));
-                        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(x), obuf, off, 0, 0);
-                        acc[i][j][v] = 0.f;
-                    }
+                    for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.f;
         }
         // loads and stores complete out of order with respect to each other: nothing is counted across them
         asm volatile("s_waitcnt vmcnt(0)");
+    }
+}
+
+// Second pass of the persistent kernel with K split: workgroup (tile t, band i) adds up, in range order, the
+// `ksplit` parts of the tile's i-th bands of sixteen rows per wave (so the result is the same bits on every
+// launch) and stores them or adds them into the float32 residual stream.  Thread and accumulator layout are
+// the producing kernel's: thread tid = wave (wm, wn) x lane (lq, l16), accumulator (i, j)[e] = row
+// 128 wm + 16 i + 4 lq + e, column 128 wn + 16 j + l16 of the tile.
+template <int EPI>
+__global__ void __launch_bounds__(256)
+gemm_p256_finish_kernel(const float* __restrict__ part, float* __restrict__ out, int M, int N, int tiles_m, int ksplit) {
+    const int t = blockIdx.x >> 3, i = blockIdx.x & 7, tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63, wm = wave >> 1, wn = wave & 1, l16 = lane & 15, lq = lane >> 4;
+    const int m0 = (t % tiles_m) * 256, c0 = (t / tiles_m) * 256;
+    const float4* src = (const float4*)part + (size_t(t) * ksplit * 64 + i * 8) * 256 + tid;
+    float4 tot[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) tot[j] = src[j * 256];
+    for (int sp = 1; sp < ksplit; ++sp) {
+        float4 p[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) p[j] = src[(size_t(sp) * 64 + j) * 256];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { tot[j].x += p[j].x; tot[j].y += p[j].y; tot[j].z += p[j].z; tot[j].w += p[j].w; }
+    }
+    const int row = m0 + wm * 128 + 16 * i + 4 * lq, col = c0 + wn * 128 + l16;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        if (row + e >= M) break;
+        float* o = out + size_t(row + e) * N + col;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float x = e == 0 ? tot[j].x : e == 1 ? tot[j].y : e == 2 ? tot[j].z : tot[j].w;
+            if (EPI == EPI_RESIDUAL_F32) o[16 * j] += x;
+            else o[16 * j] = x;
+        }
     }
 }
 
@@ -641,7 +720,7 @@ static bool ksplit_ok(int cfg, int ks, int epi, int M, int N, int K, const GemmS
     return tiles <= ws->n_counters && size_t(tiles) * ks * c.bm * c.bn * sizeof(float) <= ws->part_bytes;
 }
 static GemmChoice gemm_pick(int epi, int M, int N, int K, const GemmSplitWs* ws) {
-    static const double eff[GCFG_COUNT] = {1.0, 0.77, 0.62, 0.61, 0.40, 0.65, 1.25};   // measured TFLOP/s per busy CU, relative to 256x256
+    static const double eff[GCFG_COUNT] = {1.0, 0.77, 0.62, 0.61, 0.40, 0.65, 1.11};   // measured TFLOP/s per busy CU, relative to 256x256
     GemmChoice best{GCFG_128x128, 1};
     double best_cost = 1e30;
     for (int cfg = GCFG_COUNT - 1; cfg >= 0; --cfg) {
@@ -651,11 +730,15 @@ static GemmChoice gemm_pick(int epi, int M, int N, int K, const GemmSplitWs* ws)
         const double area = double(c.bm) * c.bn / 65536.0;
         for (int ks = 1; ks <= 8; ks *= 2) {
             if (!ksplit_ok(cfg, ks, epi, M, N, K, ws)) continue;
-            if (cfg == GCFG_P256 && ks > 1) continue;
+            // The persistent kernel needs a grid that fills the chip; split, its parts (256 KB per workgroup) go through
+            // memory to a second kernel, about 45 us for 256 of them, which only a long K range per workgroup repays
+            // (measured: 487 against 515-579 us on 1024 x 8192 x 28672 in two ranges, 155 against 147 us on
+            // 1024 x 4096 x 14336 in four).
+            if (cfg == GCFG_P256 && (tiles * ks < 160 || (ks > 1 && K / ks < 8192))) continue;
             const double rounds = double((tiles * ks + 255) / 256);
             double cost = rounds * (100.0 * area * (double(K) / ks / 4096.0) / eff[cfg] + 6.0);
             // measured: the parts cross the chip twice, at device scope; and a split must promise 8 % to be taken
-            if (ks > 1) cost = (cost + 10.0 + 20.0 * area * ks) * 1.08;
+            if (ks > 1) cost = (cost + (cfg == GCFG_P256 ? 8.0 + 0.12 * double(tiles) * ks : 10.0 + 20.0 * area * ks)) * 1.08;
             if (cost < best_cost) { best_cost = cost; best = GemmChoice{cfg, ks}; }
         }
     }
@@ -687,7 +770,7 @@ static hipError_t gemm_launch_cfg(int cfg, int ks, const GemmSplitWs* ws, const 
     const long tiles128 = long((M + 127) / 128) * (N / (EPI == EPI_SWIGLU ? 64 : 128)) * ks;
     if (cfg == GCFG_P256) {
         // a whole number of rounds: every workgroup takes `rounds` tiles (the last may take one less)
-        const int tiles_m = (M + 255) / 256, tiles_n = N / (EPI == EPI_SWIGLU ? 128 : 256), nb = tiles_m * tiles_n;
+        const int tiles_m = (M + 255) / 256, tiles_n = N / (EPI == EPI_SWIGLU ? 128 : 256), nb = tiles_m * tiles_n * ks;
         const int rounds = (nb + 255) / 256, wgs = (nb + rounds - 1) / rounds;
         auto kern = gemm_p256_kernel<EPI>;
         static bool attr_set = false;
@@ -696,7 +779,13 @@ static hipError_t gemm_launch_cfg(int cfg, int ks, const GemmSplitWs* ws, const 
             if (e != hipSuccess) return e;
             attr_set = true;
         }
-        hipLaunchKernelGGL(kern, dim3(wgs), dim3(256), P_LDS, st, A, W, W2, out, M, N, K, tiles_m, tiles_n, rounds);
+        hipLaunchKernelGGL(kern, dim3(wgs), dim3(256), P_LDS, st, A, W, W2, out, M, N, K, tiles_m, tiles_n, rounds,
+                           ks > 1 ? ws->part : nullptr, ks);
+        if (ks > 1) {
+            if constexpr (EPI != EPI_SWIGLU)
+                hipLaunchKernelGGL(gemm_p256_finish_kernel<EPI>, dim3(tiles_m * tiles_n * 8), dim3(256), 0, st, ws->part, (float*)out,
+                                   M, N, tiles_m, ks);
+        }
         return hipGetLastError();
     }
     switch (cfg) {

@@ -53,6 +53,9 @@ def test_rmsnorm(kind, rows, d):
     ("bf16", 0, 700, 384, 96, 4), ("bf16", 0, 129, 768, 160, 4), ("bf16", 0, 1024, 6144, 512, 0),   # 128x192 tiles
     ("bf16", 0, 300, 192, 96, 5), ("bf16", 0, 512, 4096, 1024, 0), ("bf16", 0, 129, 64, 192, 5),   # 128x64 tiles
     ("bf16", 0, 300, 256, 512, 6), ("bf16", 0, 129, 384, 64, 6), ("bf16", 0, 1024, 4096, 1024, 6),  # 128x128, two waves per half along K
+    # the persistent four-wave kernel: one slice; ragged M over three slices; many slices; more tiles than
+    # workgroups (260 plain tiles = 2 rounds of 130 workgroups, 520 SwiGLU tiles = 3 rounds, the last one short)
+    ("bf16", 0, 257, 256, 64, 7), ("bf16", 0, 300, 768, 192, 7), ("bf16", 0, 1024, 512, 4096, 7), ("bf16", 0, 1000, 16640, 128, 7),
 ])
 def test_gemm_variants(kind, path, M, N, K, cfg):
     import torch
@@ -85,6 +88,7 @@ def test_gemm_variants(kind, path, M, N, K, cfg):
     (129, 768, 2048, 4, 2, (128, 192)),
     (200, 512, 1024, 5, 2, (128, 64)),
     (300, 768, 2048, 6, 4, (128, 128)),      # split over workgroups and, inside each, over two waves
+    (1024, 1024, 4096, 7, 4, (256, 256)), (700, 512, 2048, 7, 2, (256, 256)), (1024, 2048, 4096, 7, 8, (256, 256)),  # persistent kernel
     (512, 4096, 11008, 0, 0, None),          # down projection with 512-token chunks: the cost model splits it
 ])
 def test_gemm_split_k(M, N, K, cfg, ks, tile):
