@@ -131,17 +131,24 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
         int row = (wave + i * NW) * RPL + lr;
         bg[i] = w_row(row) + (lpos ^ gemm_swz<BK>(row)) * 8;
     }
-    auto issue = [&](int stage, int k0) {
+    // Wave-load idx of a slice (0 .. PER_TILE-1: the A loads, then the W loads) belongs to part idx % KS.  A slice
+    // is not requested in one burst: the texture addresser takes 16 cycles per wave-load and a full address
+    // FIFO blocks the issuing wave, MFMAs included.  Part 0 goes out after the barrier that frees the buffer,
+    // part p in step p-1 of the following slice, each load between two operand reads.
+    auto issue_one = [&](unsigned char* sa, int k0, int idx) {
+        if (idx < A_PER)
+            __builtin_amdgcn_global_load_lds((const CAKE_GLOBAL_AS void*)(ag[idx] + k0),
+                                             (CAKE_LDS_AS void*)(sa + (wave + idx * NW) * 1024), 16, 0, 0);
+        else
+            __builtin_amdgcn_global_load_lds((const CAKE_GLOBAL_AS void*)(bg[idx - A_PER] + k0),
+                                             (CAKE_LDS_AS void*)(sa + A_BYTES + (wave + (idx - A_PER) * NW) * 1024), 16, 0, 0);
+    };
+    auto issue = [&](int stage, int k0) {   // a whole slice at once (prologue)
         unsigned char* sa = lds + stage * STAGE;
 #pragma unroll
-        for (int i = 0; i < A_PER; ++i)
-            __builtin_amdgcn_global_load_lds((const CAKE_GLOBAL_AS void*)(ag[i] + k0),
-                                             (CAKE_LDS_AS void*)(sa + (wave + i * NW) * 1024), 16, 0, 0);
-#pragma unroll
-        for (int i = 0; i < B_PER; ++i)
-            __builtin_amdgcn_global_load_lds((const CAKE_GLOBAL_AS void*)(bg[i] + k0),
-                                             (CAKE_LDS_AS void*)(sa + A_BYTES + (wave + i * NW) * 1024), 16, 0, 0);
+        for (int idx = 0; idx < PER_TILE; ++idx) issue_one(sa, k0, idx);
     };
+    constexpr int PART_MAX = (PER_TILE + KS - 1) / KS;
 
     f32x16 acc[WTM][WTN];
 #pragma unroll
@@ -164,6 +171,19 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
 #pragma unroll
         for (int j = 0; j < WTN; ++j) bb[j] = *(const bf16x8*)(st + b_row_off + j * 32 * ROWB + koffv);
     };
+    // the same reads with part `part` of the slice bound for `stage_ld` dealt between them (a load to LDS and an
+    // LDS read may not pass each other, so this source order is the issue order)
+    auto rd_ld = [&](bf16x8* a, bf16x8* bb, int stage, int koffv, int stage_ld, int k0, auto part_tag) {
+        constexpr int PART = decltype(part_tag)::value;
+        const unsigned char* st = lds + stage * STAGE;
+        unsigned char* sa = lds + stage_ld * STAGE;
+#pragma unroll
+        for (int r = 0; r < WTM + WTN; ++r) {
+            if (r < WTM) a[r] = *(const bf16x8*)(st + a_row_off + r * 32 * ROWB + koffv);
+            else bb[r - WTM] = *(const bf16x8*)(st + b_row_off + (r - WTM) * 32 * ROWB + koffv);
+            if (r < PART_MAX && PART + r * KS < PER_TILE) issue_one(sa, k0, PART + r * KS);
+        }
+    };
     auto mm = [&](const bf16x8* a, const bf16x8* bb) {
 #pragma unroll
         for (int i = 0; i < WTM; ++i)
@@ -179,35 +199,87 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
         }
     };
 
-    const int nk = K / ksplit / BK;
-    // prologue: STAGES-1 slices in flight; slice 0 landed; its step-0 operands in registers
+    auto interleave_ld = [&](auto part_tag) {
+        constexpr int PART = decltype(part_tag)::value;
 #pragma unroll
-    for (int st = 0; st < STAGES - 1; ++st)
+        for (int i = 0; i < WTM + WTN; ++i) {
+            if constexpr ((WTM * WTN) / (WTM + WTN) > 0)
+                __builtin_amdgcn_sched_group_barrier(0x008, (WTM * WTN) / (WTM + WTN), 0);  // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                          // DS read
+            if (i < PART_MAX && PART + i * KS < PER_TILE) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // load
+        }
+    };
+    static_assert(PART_MAX <= WTM + WTN, "one load per operand read at most");
+
+    const int nk = K / ksplit / BK;
+    // Slices 0 .. n_steady-1 each request the slice STAGES-1 ahead (part 0 in their last step, the other parts in
+    // the first steps of the slice after them); the slices after that request nothing.
+    const int n_steady = nk > STAGES - 1 ? nk - (STAGES - 1) : 0;
+    // prologue: STAGES-1 slices in flight (of the last of them only part 0 if slice 0 will deal out the rest);
+    // slice 0 landed; its step-0 operands in registers
+#pragma unroll
+    for (int st = 0; st < STAGES - 2; ++st)
         if (st < nk) issue(st, st * BK);
-    if (nk >= STAGES - 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((STAGES - 2) * PER_TILE));
+    if (STAGES - 2 < nk) {
+        if (n_steady > 0) {
+            unsigned char* sa = lds + (STAGES - 2) * STAGE;
+#pragma unroll
+            for (int r = 0; r < PART_MAX; ++r)
+                if (r * KS < PER_TILE) issue_one(sa, (STAGES - 2) * BK, r * KS);
+        } else {
+            issue(STAGES - 2, (STAGES - 2) * BK);
+        }
+    }
+    constexpr int PART0 = (PER_TILE + KS - 1) / KS;   // loads in part 0
+    if (n_steady > 0) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((STAGES - 3) * PER_TILE + PART0));
+    else if (nk >= STAGES - 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((STAGES - 2) * PER_TILE));
     else asm volatile("s_waitcnt vmcnt(0)");
     __builtin_amdgcn_s_barrier();
     bf16x8 opa[2][WTM], opb[2][WTN];   // operands of the current and the next step
     rd(opa[0], opb[0], 0, koff[0]);
-    for (int kt = 0; kt < nk; ++kt) {
+    // One slice.  NEW: this slice requests part 0 of slice kt+STAGES-1 after its barrier.  DEFER: its first
+    // steps request the remaining parts of slice kt+STAGES-2 (whose part 0 the slice before requested).
+    auto slice = [&](int kt, auto new_tag, auto defer_tag) {
+        constexpr bool NEW = decltype(new_tag)::value, DEFER = decltype(defer_tag)::value;
         const int cur = kt % STAGES;
+        const int st_prev = (kt + STAGES - 2) % STAGES, k_prev = (kt + STAGES - 2) * BK;
         // steps 0 .. KS-2: this step's MFMAs, next step's operands from the same slice
-#pragma unroll
-        for (int ks = 0; ks + 1 < KS; ++ks) {
-            rd(opa[(ks + 1) & 1], opb[(ks + 1) & 1], cur, koff[ks + 1]);
-            mm(opa[ks & 1], opb[ks & 1]);
-            interleave();
-        }
-        // slice kt+1 must have landed before the last step reads its first operands
-        if (kt + STAGES - 1 <= nk) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((STAGES - 3) * PER_TILE));
+        [&]<int... PS>(std::integer_sequence<int, PS...>) {
+            ([&] {
+                constexpr int ks = PS;
+                if constexpr (DEFER) {
+                    rd_ld(opa[(ks + 1) & 1], opb[(ks + 1) & 1], cur, koff[ks + 1], st_prev, k_prev, std::integral_constant<int, ks + 1>{});
+                    mm(opa[ks & 1], opb[ks & 1]);
+                    interleave_ld(std::integral_constant<int, ks + 1>{});
+                } else {
+                    rd(opa[(ks + 1) & 1], opb[(ks + 1) & 1], cur, koff[ks + 1]);
+                    mm(opa[ks & 1], opb[ks & 1]);
+                    interleave();
+                }
+            }(), ...);
+        }(std::make_integer_sequence<int, KS - 1>{});
+        // slice kt+1 must have landed before the last step reads its first operands: in the steady state everything
+        // but the STAGES-3 slices after it may still be out
+        if constexpr (NEW || DEFER) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((STAGES - 3) * PER_TILE));
         else asm volatile("s_waitcnt vmcnt(0)");
         __builtin_amdgcn_s_barrier();
-        // every wave has finished reading slice kt-1: refill its buffer
-        if (kt + STAGES - 1 < nk) issue((kt + STAGES - 1) % STAGES, (kt + STAGES - 1) * BK);
-        // past the last slice this reads stale LDS that is never used
-        rd(opa[0], opb[0], (kt + 1) % STAGES, koff[0]);
-        mm(opa[(KS - 1) & 1], opb[(KS - 1) & 1]);
-        interleave();
+        // every wave has finished reading slice kt-1: its buffer is refilled, starting now
+        if constexpr (NEW) {
+            rd_ld(opa[0], opb[0], (kt + 1) % STAGES, koff[0], (kt + STAGES - 1) % STAGES, (kt + STAGES - 1) * BK, std::integral_constant<int, 0>{});
+            mm(opa[(KS - 1) & 1], opb[(KS - 1) & 1]);
+            interleave_ld(std::integral_constant<int, 0>{});
+        } else {
+            // past the last slice this reads stale LDS that is never used
+            rd(opa[0], opb[0], (kt + 1) % STAGES, koff[0]);
+            mm(opa[(KS - 1) & 1], opb[(KS - 1) & 1]);
+            interleave();
+        }
+    };
+    {
+        int kt = 0;
+        for (; kt < n_steady; ++kt) slice(kt, std::true_type{}, std::true_type{});
+        if (n_steady > 0) { slice(kt, std::false_type{}, std::true_type{}); ++kt; }
+        for (; kt < nk; ++kt) slice(kt, std::false_type{}, std::false_type{});
     }
 
     // With K divided between two waves, wave kw finishes the 32-row bands i with (i & 1) == kw.
@@ -730,15 +802,15 @@ static GemmChoice gemm_pick(int epi, int M, int N, int K, const GemmSplitWs* ws)
         const double area = double(c.bm) * c.bn / 65536.0;
         for (int ks = 1; ks <= 8; ks *= 2) {
             if (!ksplit_ok(cfg, ks, epi, M, N, K, ws)) continue;
-            // The persistent kernel needs a grid that fills the chip; split, its parts (256 KB per workgroup) go through
-            // memory to a second kernel, about 45 us for 256 of them, which only a long K range per workgroup repays
-            // (measured: 487 against 515-579 us on 1024 x 8192 x 28672 in two ranges, 155 against 147 us on
-            // 1024 x 4096 x 14336 in four).
-            if (cfg == GCFG_P256 && (tiles * ks < 160 || (ks > 1 && K / ks < 8192))) continue;
+            // The persistent kernel needs a grid that fills the chip.  Split, its parts (256 KB per workgroup) go
+            // through memory to a second kernel, about 45 us for 256 of them: measured 487 us against 443 for the
+            // eight-wave 256 x 256 kernel on 1024 x 8192 x 28672 in two ranges, 155 against 140 for 128 x 128 tiles
+            // on 1024 x 4096 x 14336 in four.  So it is chosen unsplit only (the split path stays for forced use).
+            if (cfg == GCFG_P256 && (tiles < 160 || ks > 1)) continue;
             const double rounds = double((tiles * ks + 255) / 256);
             double cost = rounds * (100.0 * area * (double(K) / ks / 4096.0) / eff[cfg] + 6.0);
             // measured: the parts cross the chip twice, at device scope; and a split must promise 8 % to be taken
-            if (ks > 1) cost = (cost + (cfg == GCFG_P256 ? 8.0 + 0.12 * double(tiles) * ks : 10.0 + 20.0 * area * ks)) * 1.08;
+            if (ks > 1) cost = (cost + 10.0 + 20.0 * area * ks) * 1.08;
             if (cost < best_cost) { best_cost = cost; best = GemmChoice{cfg, ks}; }
         }
     }
