@@ -10,6 +10,11 @@ All inputs (weights, token ids, stored KV, KV pool) are resident before the time
 
 Prints ONE JSON line.  `value` is the mean time-to-first-token of the timed bidirectional
 steps in seconds (entry of cake_bidirectional_prefill -> every chunk's KV resident).
+
+After the headline workload the same measurement runs on the other configured workloads and is
+appended under "configs" (tiny fp32 model at 1 GB/s; Llama2-7B shape, 16K tokens, chunk 512, 4 GB/s;
+Llama3-8B shape, 64K tokens at 2, 8 and 25 GB/s; Llama2-70B shape, 72K tokens, 8 GB/s; about a
+minute and a half together); `--headline-only` skips them, the headline keys are the same either way.
 """
 from __future__ import annotations
 
@@ -23,8 +28,19 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, the published figure
 PEAK_HBM_GBS = 8000.0
+# One 32x32x16 bf16 MFMA is 32768 FLOP and occupies a SIMD's matrix pipe for 8 passes of 4 clocks,
+# i.e. 1024 FLOP per clock per SIMD, 4 SIMDs per compute unit.
+BF16_FLOP_PER_CU_PER_CLOCK = 4096
+TRAFFIC_SUMMARY = os.path.join("profiles", "hbm_traffic_llama3_8b_32k.md")
+
+
+def derived_peak(eng):
+    """The bf16 MFMA peak from what the device reports: compute units x clock x FLOP per CU per clock."""
+    cus, khz, mem = eng.device_info()
+    return {"compute_units": cus, "clock_mhz": round(khz / 1e3, 1), "flop_per_cu_per_clock": BF16_FLOP_PER_CU_PER_CLOCK,
+            "tflops": round(cus * khz * 1e3 * BF16_FLOP_PER_CU_PER_CLOCK / 1e12, 1), "hbm_gib": round(mem / 2.0 ** 30, 1)}
 
 
 def cpu_baseline(shape, chunk, n_tokens, total_flops):
@@ -48,12 +64,47 @@ def cpu_baseline(shape, chunk, n_tokens, total_flops):
     fl = sum(otf.chunk_flops(small, i, chunk) for i in range(n_s))
     return {
         "value": dt * total_flops / fl, "unit": "s (TTFT, compute-only, extrapolated by FLOPs)",
-        "cores": int(threads), "kind": "oracle",
+        "cores": int(threads), "blas_threads": int(threads), "host_cpus": os.cpu_count(), "kind": "oracle",
         "sample": "oracle.prefill_chunked: first %d chunks of %d tokens through %d of %d layers at full width, "
                   "%.1f s measured, %.3f TFLOP; scaled x%.0f to the %d-token, %d-layer job"
                   % (n_s, chunk, small.n_layers, shape.n_layers, dt, fl / 1e12, total_flops / fl, n_tokens, shape.n_layers),
         "measured_s": dt, "measured_tflops": fl / dt / 1e12,
+        "tiny_config": cpu_baseline_tiny(int(threads)),
     }
+
+
+def cpu_baseline_tiny(threads):
+    """The smallest configured workload run whole by the oracle: the full chunked prefill of the tiny
+    fp32 model (2 layers, d 256, 2048 tokens, chunk 256) and the exhaustive meet-point search
+    (Sec. 3.1) over its 8 chunks and over a 4096-chunk instance, each timed on the host."""
+    import numpy as np
+    import synth_inputs as si
+    from oracle import transformer as otf
+    from oracle import meet_point as omp
+    shape, T, C = si.TINY, 2048, 256
+    w = si.make_weights(shape, seed=0)
+    toks = si.make_tokens(T, shape.vocab, seed=1)
+    t0 = time.perf_counter()
+    otf.prefill_chunked(w, shape, toks, C, kv_dtype="f32")
+    dt = time.perf_counter() - t0
+    n = T // C
+    fl = [otf.chunk_flops(shape, i, C) for i in range(n)]
+    c = [int(f / 1e3) for f in fl]                           # ns at 1 TFLOP/s
+    l = [C * otf.kv_bytes_per_token(shape.n_layers, shape.n_kv, shape.head_dim, 4)] * n   # ns at 1 GB/s
+    t0 = time.perf_counter()
+    for _ in range(1000):
+        m = omp.brute_force_meet_point(c, l)
+    dt_plan = (time.perf_counter() - t0) / 1000
+    rng = np.random.default_rng(0)
+    big_c = np.cumsum(rng.integers(1, 1000, 4096)).tolist()
+    big_l = rng.integers(1000, 2000000, 4096).tolist()
+    t0 = time.perf_counter()
+    omp.brute_force_meet_point(big_c, big_l)
+    dt_big = time.perf_counter() - t0
+    return {"workload": "tiny-f32, 2048 tokens, chunk 256, float64 oracle", "prefill_s": round(dt, 4),
+            "prefill_gflops": round(sum(fl) / dt / 1e9, 2), "meet_point_search_8_chunks_s": round(dt_plan, 8),
+            "meet_point_8_chunks_at_1tflops_1gbs": m if isinstance(m, int) else list(m),
+            "meet_point_search_4096_chunks_s": round(dt_big, 4), "cores": threads, "blas_threads": threads}
 
 
 def recorded_traffic(kernel_class, default_workload):
@@ -61,7 +112,7 @@ def recorded_traffic(kernel_class, default_workload):
     WRITE_SIZE on the default workload (summary kept under profiles/); None if not recorded."""
     if not default_workload:
         return None
-    path = os.path.join(ROOT, "profiles", "hbm_traffic_llama3_8b_32k.md")
+    path = os.path.join(ROOT, TRAFFIC_SUMMARY)
     try:
         for line in open(path):
             f = line.split()
@@ -70,6 +121,62 @@ def recorded_traffic(kernel_class, default_workload):
     except OSError:
         pass
     return None
+
+
+def measure_config(cake, si, torch, name, T, C, pt, gbps_list, steps, warmup):
+    """TTFT of one configured workload under the three regimes (compute-only, load-only at each tier
+    bandwidth, bidirectional at each), with the per-class kernel rates of one bracketed compute-only pass."""
+    import numpy as np
+    shape = si.SHAPES[name]
+    n = (T + C - 1) // C
+    eng = cake.Engine(shape, None, max_tokens=T, max_chunk=C, page_tokens=pt, seed=0, with_head=False)
+    toks = si.make_tokens(T, shape.vocab, seed=1)
+    eng.bidirectional_prefill(toks, C, gbps_list[0], mode="compute_only", log=False)
+    eng.store_from_pool(T)
+    r_c = eng.bidirectional_prefill(toks, C, gbps_list[0], mode="compute_only")
+    eng.profile_enable(True)
+    eng.bidirectional_prefill(toks, C, gbps_list[0], mode="compute_only", log=False)
+    stats = eng.profile_read()
+    eng.profile_enable(False)
+    kernels = {k: {"avg_us": round(v["total_ns"] / v["launches"] / 1e3, 2),
+                   "tflops": round(v["flops"] / v["total_ns"] / 1e3, 1) if v["flops"] else None}
+               for k, v in stats.items() if v["launches"]}
+    tiers = {}
+    for gbps in gbps_list:
+        for _ in range(warmup):
+            eng.bidirectional_prefill(toks, C, gbps, mode="bidir", log=False)
+        runs = [eng.bidirectional_prefill(toks, C, gbps, mode="bidir") for _ in range(steps)]
+        r_l = eng.bidirectional_prefill(toks, C, gbps, mode="load_only")
+        ttft = float(np.mean([r.ttft_ns for r in runs])) / 1e9
+        load_bytes = sum(r.load_bytes for r in runs)
+        load_ns = sum(r.load_busy_ns for r in runs)
+        tiers["%g_gbs" % gbps] = {
+            "bidirectional": round(ttft, 5), "load_only": round(r_l.ttft_ns / 1e9, 5),
+            "meet_point": [r.meet_point for r in runs],
+            "speedup_over_load_only": round(r_l.ttft_ns / 1e9 / ttft, 3),
+            "speedup_over_compute_only": round(r_c.ttft_ns / 1e9 / ttft, 3),
+            "achieved_gbps_bidirectional": round(load_bytes / load_ns, 4) if load_ns else None,
+            "achieved_gbps_load_only": round(r_l.achieved_gbps, 4)}
+    out = {"workload": "%s, %d random tokens, chunk %d, page %d, stored KV in pinned host memory at %s GB/s"
+                       % (shape.name, T, C, pt, "/".join("%g" % g for g in gbps_list)),
+           "dtype": "bf16" if shape.dtype == "bf16" else "f32", "n_chunks": n, "steps": steps, "warmup": warmup,
+           "compute_only_s": round(r_c.ttft_ns / 1e9, 5), "prefill_tflops_compute_only": round(r_c.compute_tflops, 1),
+           "tiers": tiers, "kernels": kernels}
+    if shape.dtype == "bf16":
+        out["mfma_util_compute_only"] = round(r_c.compute_tflops / PEAK_BF16_TFLOPS, 4)
+    eng.close()
+    del eng
+    torch.cuda.empty_cache()
+    return out
+
+
+# the configured workloads besides the headline one: (key, shape, tokens, chunk, tier bandwidths in GB/s)
+OTHER_CONFIGS = [
+    ("tiny_f32_2k", "tiny-f32", 2048, 256, [1.0]),
+    ("llama2_7b_16k_chunk512", "llama2-7b-shape", 16384, 512, [4.0]),
+    ("llama3_8b_64k", "llama3-8b-shape", 65536, 1024, [2.0, 8.0, 25.0]),
+    ("llama2_70b_72k", "llama2-70b-shape", 73728, 1024, [8.0]),
+]
 
 
 def main():
@@ -84,6 +191,10 @@ def main():
     ap.add_argument("--gbps", type=float, default=4.0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with events in the timed region")
+    ap.add_argument("--all-configs", action="store_true",
+                    help="after the headline workload, also measure the other configured workloads (key \"configs\"); "
+                         "this is the default, the flag is accepted for clarity")
+    ap.add_argument("--headline-only", action="store_true", help="skip the other configured workloads")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy, so a counter run has a kernel of known traffic")
     args = ap.parse_args()
@@ -218,9 +329,16 @@ def main():
         dom = dominant
         s = dom_stats[dom]                       # from the timed region itself
         achieved = s["flops"] / s["total_ns"] / 1e3
+        traffic = recorded_traffic(dom, (args.shape, T, C, pt) == ("llama3-8b-shape", 32768, 1024, 256))
         roofline = {"kernel": dom, "bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS,
                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                    "traffic": recorded_traffic(dom, (args.shape, T, C, pt) == ("llama3-8b-shape", 32768, 1024, 256)),
+                    "peak_source": "published dense bf16 figure; peak_derived is this device's compute units x "
+                                   "clock x 4096 FLOP per CU per clock",
+                    "peak_derived": derived_peak(eng),
+                    "traffic": traffic,
+                    "traffic_source": None if traffic is None else
+                    "recorded, not measured in this run: %s (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes over "
+                    "this command, scaled by a 1 GiB copy)" % TRAFFIC_SUMMARY,
                     "avg_launch_us": round(s["total_ns"] / s["launches"] / 1e3, 2), "launches": s["launches"],
                     "flops_per_launch": s["flops"] // s["launches"]}
 
@@ -257,12 +375,23 @@ def main():
         "first_token": dict(first_token, ttft_to_first_token_s=round(ttft + ft_wall, 5)),
         "fine_fetch_unit": fine,
         "mfma_only": {"tflops": round(mfma_only, 1), "frac_of_peak": round(mfma_only / PEAK_BF16_TFLOPS, 4),
-                      "what": "bf16 32x32x16 MFMAs on register operands, no memory traffic: what the matrix pipes of "
-                              "this GPU deliver under its power limit (cake_op_mfma_rate)"},
+                      "what": "bf16 32x32x16 MFMAs on register operands, no memory traffic, every CU busy for "
+                              "about 10 ms: the rate the matrix pipes sustain at the clock the device holds "
+                              "under that load (cake_op_mfma_rate)"},
         "int8_store": int8_store,
         "int4_store": int4_store,
         "roofline": roofline,
     }
+    if not args.headline_only:
+        eng.close()
+        del eng
+        torch.cuda.empty_cache()
+        out["configs"] = {}
+        for key, name, T2, C2, tiers in OTHER_CONFIGS:
+            t_cfg = time.perf_counter()
+            out["configs"][key] = measure_config(cake, si, torch, name, T2, C2, min(pt, C2), tiers, 2, 1)
+            out["configs"][key]["wall_s"] = round(time.perf_counter() - t_cfg, 1)
+            print("bench.py: %s done in %.0f s" % (key, time.perf_counter() - t_cfg), file=sys.stderr, flush=True)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(shape, C, T, total_flops)
     print(json.dumps(out))

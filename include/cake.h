@@ -477,6 +477,11 @@ int32_t cake_op_gemm_plan(cake_ctx* ctx, int32_t residual, int32_t M, int32_t N,
  * of this GPU delivered for that (host).  Blocking; uses the context's activation workspace.
  * Errors: CAKE_E_INVAL (sizes), CAKE_E_HIP. */
 int32_t cake_op_mfma_rate(cake_ctx* ctx, int32_t workgroups, int32_t iters, double* tflops);
+/* What the context's device reports (hipDeviceGetAttribute): *compute_units, *clock_khz = its peak engine
+ * clock, *hbm_bytes = total device memory; the dense bf16 MFMA peak follows as compute_units x clock x 4096
+ * FLOP (one 32x32x16 MFMA = 32768 FLOP in 32 clocks on each of 4 SIMDs).  Host pointers, any may be NULL;
+ * pure.  Errors: CAKE_E_INVAL (ctx NULL), CAKE_E_HIP. */
+int32_t cake_device_info(cake_ctx* ctx, int32_t* compute_units, int32_t* clock_khz, uint64_t* hbm_bytes);
 /* out[M][N] = silu(a*wg^T) .* (a*wu^T), element type out */
 int32_t cake_op_gemm_swiglu(cake_ctx* ctx, const void* a, const void* wg, const void* wu,
                             void* out, int32_t M, int32_t N, int32_t K);

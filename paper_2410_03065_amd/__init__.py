@@ -29,7 +29,7 @@ EXPORTS = [
     "cake_load_chunk", "cake_plan_meet_point", "cake_bidirectional_prefill", "cake_set_bandwidth",
     "cake_schedule_bandwidth_step", "cake_chunk_state", "cake_sync_compute", "cake_sync_load",
     "cake_range_flops", "cake_page_image_bytes", "cake_simulate_race", "cake_op_rmsnorm",
-    "cake_op_gemm", "cake_op_gemm_residual", "cake_op_gemm_swiglu", "cake_op_gemm_plan", "cake_op_mfma_rate", "cake_op_rope_kv_write",
+    "cake_op_gemm", "cake_op_gemm_residual", "cake_op_gemm_swiglu", "cake_op_gemm_plan", "cake_op_mfma_rate", "cake_device_info", "cake_op_rope_kv_write",
     "cake_op_attention", "cake_profile_enable", "cake_profile_read", "cake_adaptive_serve", "cake_first_token",
     "cake_op_decode_attention", "cake_op_decode_attention_static", "cake_set_traces", "cake_store_image_bytes", "cake_write_store", "cake_prefix_keys", "cake_prefix_lookup",
 ]
@@ -165,6 +165,7 @@ def load_library():
         "cake_op_gemm_swiglu": (i32, [vp, vp, vp, vp, vp, i32, i32, i32]),
         "cake_op_gemm_plan": (i32, [vp, i32, i32, i32, i32, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
         "cake_op_mfma_rate": (i32, [vp, i32, i32, P(C.c_double)]),
+        "cake_device_info": (i32, [vp, P(i32), P(i32), P(C.c_uint64)]),
         "cake_op_rope_kv_write": (i32, [vp, vp, vp, i32, i32, i32, P(Kv)]),
         "cake_op_attention": (i32, [vp, vp, vp, i32, i32, i32, P(Kv)]),
     }
@@ -603,10 +604,16 @@ class Engine:
 
     def mfma_rate(self, workgroups=2048, iters=4096):
         """TFLOP/s of bf16 MFMAs on register operands only (cake_op_mfma_rate): what the matrix pipes of this GPU
-        deliver under its power limit, a yardstick for the GEMM and attention figures."""
+        sustain at the clock the device holds under that load, a yardstick for the GEMM and attention figures."""
         v = C.c_double(0.0)
         self._check(self.lib.cake_op_mfma_rate(self.ctx, workgroups, iters, C.byref(v)), "cake_op_mfma_rate")
         return v.value
+
+    def device_info(self):
+        """(compute units, peak engine clock in kHz, device memory in bytes) of the context's GPU."""
+        cu, khz, mem = C.c_int32(0), C.c_int32(0), C.c_uint64(0)
+        self._check(self.lib.cake_device_info(self.ctx, C.byref(cu), C.byref(khz), C.byref(mem)), "cake_device_info")
+        return cu.value, khz.value, mem.value
 
     def set_bandwidth(self, gbps):
         self._check(self.lib.cake_set_bandwidth(self.ctx, float(gbps)), "cake_set_bandwidth")

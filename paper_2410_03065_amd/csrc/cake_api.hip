@@ -1224,6 +1224,25 @@ int32_t cake_op_mfma_rate(cake_ctx* c, int32_t workgroups, int32_t iters, double
     return CAKE_OK;
 }
 
+int32_t cake_device_info(cake_ctx* c, int32_t* compute_units, int32_t* clock_khz, uint64_t* hbm_bytes) {
+    if (!c) return CAKE_E_INVAL;
+    int v = 0;
+    if (compute_units) {
+        HIP_TRY(c, hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, c->device));
+        *compute_units = v;
+    }
+    if (clock_khz) {
+        HIP_TRY(c, hipDeviceGetAttribute(&v, hipDeviceAttributeClockRate, c->device));
+        *clock_khz = v;
+    }
+    if (hbm_bytes) {
+        size_t free_b = 0, total_b = 0;
+        HIP_TRY(c, hipMemGetInfo(&free_b, &total_b));
+        *hbm_bytes = total_b;
+    }
+    return CAKE_OK;
+}
+
 int32_t cake_op_gemm_swiglu(cake_ctx* c, const void* a, const void* wg, const void* wu, void* out, int32_t M,
                             int32_t N, int32_t K) {
     if (!c || !a || !wg || !wu || !out || M < 0 || N <= 0 || K <= 0 || (K & 7)) return CAKE_E_INVAL;

@@ -617,6 +617,10 @@ gemm_p256_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
             }
         }
         if constexpr (EPI == EPI_SWIGLU) {
+            // The row pitch is made opaque here so that the 32 row offsets are formed per tile, on the scalar unit,
+            // and not kept in vector registers across the K loop (where there are none to spare).
+            int pitch = N * 2;
+            asm volatile("" : "+s"(pitch));
             const unsigned base = unsigned(row0 * N + c0 + wn * 64 + l16) * 2u;
 #pragma unroll
             for (int i = 0; i < 8; ++i)
@@ -629,7 +633,7 @@ gemm_p256_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
                         const bf16_t o = bf16_t(g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * up);
                         unsigned short bits;
                         __builtin_memcpy(&bits, &o, 2);
-                        __builtin_amdgcn_raw_buffer_store_b16(bits, obuf, base + unsigned((i * 16 + v) * N + (j >> 1) * 16) * 2u, 0, 0);
+                        __builtin_amdgcn_raw_buffer_store_b16(bits, obuf, base, (i * 16 + v) * pitch + (j >> 1) * 32, 0);
                         acc[i][j][v] = 0.f; acc[i][j + 1][v] = 0.f;
                     }
         } else if (finish) {
