@@ -514,51 +514,45 @@ gemm_p256_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
     kch[0] = (lq ^ sw) << 4;
     kch[1] = ((4 + lq) ^ sw) << 4;
     f32x4 acc[8][8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-#pragma unroll
-        for (int j = 0; j < 8; ++j)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.f;
-    bf16x8 a0[8], b0[8], a1[8], b1[8];
-    auto rd = [&](bf16x8* a, bf16x8* b, int sa, int sb, int ks) {
+    // Operand fragments are held as four 32-bit words (eight bf16 values along K).
+    typedef __attribute__((__vector_size__(4 * sizeof(int)))) int frag_t;
+    frag_t a0[8], b0[8], a1[8], b1[8];
+    auto rd = [&](frag_t* a, frag_t* b, int sa, int sb, int ks) {
         const unsigned char* pa = lds + sa * P_ITEM + a_lane + kch[ks];
         const unsigned char* pb = lds + sb * P_ITEM + b_lane + kch[ks];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) b[j] = *(const bf16x8*)(pb + j * 2048);
+        for (int j = 0; j < 8; ++j) b[j] = *(const frag_t*)(pb + j * 2048);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) a[i] = *(const bf16x8*)(pa + i * 2048);
+        for (int i = 0; i < 8; ++i) a[i] = *(const frag_t*)(pa + i * 2048);
     };
-    // the same reads with the eight wave-loads of one item dealt between them
-    auto rd_ld = [&](bf16x8* a, bf16x8* b, int sa, int sb, int ks, __amdgpu_buffer_rsrc_t rs, int slot, unsigned voff, int kk,
-                     unsigned step) {
+    // One phase: the 64 MFMAs of a k-step on (a, b), with the sixteen operand reads of the next k-step (into an,
+    // bn) and the eight wave-loads of one item dealt between them: two MFMAs, a read, two MFMAs, a read, two MFMAs,
+    // a load, eight times over, then the last sixteen MFMAs.  The MFMAs are written as asm statements with the
+    // accumulator tied to an AGPR tuple: the 64 accumulators then fill the AGPR file exactly and stay where they
+    // are (left to itself the allocator rotates them through misaligned tuples with a hundred register copies per
+    // slice, each waiting for the MFMA that wrote its source), and, being volatile, they pin the order of the
+    // reads and loads written between them: source order is issue order.
+    auto mfma = [&](int n, const frag_t* a, const frag_t* b) {
+        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[n >> 3][n & 7]) : "v"(a[n >> 3]), "v"(b[n & 7]));
+    };
+    auto phase = [&](const frag_t* a, const frag_t* b, frag_t* an, frag_t* bn, int sa, int sb, int ks, __amdgpu_buffer_rsrc_t rs,
+                     int slot, unsigned voff, int kk, unsigned step) {
         const unsigned char* pa = lds + sa * P_ITEM + a_lane + kch[ks];
         const unsigned char* pb = lds + sb * P_ITEM + b_lane + kch[ks];
         unsigned char* dst = lds + slot * P_ITEM + wave * 1024;
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
-            if (r < 4) { b[2 * r] = *(const bf16x8*)(pb + (2 * r) * 2048); b[2 * r + 1] = *(const bf16x8*)(pb + (2 * r + 1) * 2048); }
-            else { a[2 * r - 8] = *(const bf16x8*)(pa + (2 * r - 8) * 2048); a[2 * r - 7] = *(const bf16x8*)(pa + (2 * r - 7) * 2048); }
+            mfma(6 * r, a, b); mfma(6 * r + 1, a, b);
+            if (r < 4) bn[2 * r] = *(const frag_t*)(pb + (2 * r) * 2048);
+            else an[2 * r - 8] = *(const frag_t*)(pa + (2 * r - 8) * 2048);
+            mfma(6 * r + 2, a, b); mfma(6 * r + 3, a, b);
+            if (r < 4) bn[2 * r + 1] = *(const frag_t*)(pb + (2 * r + 1) * 2048);
+            else an[2 * r - 7] = *(const frag_t*)(pa + (2 * r - 7) * 2048);
+            mfma(6 * r + 4, a, b); mfma(6 * r + 5, a, b);
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (CAKE_LDS_AS void*)(dst + r * 4096), 16, voff, kk * 128 + r * step, 0, 0);
         }
-    };
-    auto mm = [&](const bf16x8* a, const bf16x8* b) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
-#pragma unroll
-            for (int j = 0; j < 8; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
-    };
-    auto mix = [&]() {   // 64 MFMAs, 16 operand reads, 8 loads
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-        }
-        __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
+        for (int n = 48; n < 64; ++n) mfma(n, a, b);
     };
 
     // prologue: items W0 A0 W1 A1 in flight (dummies past the end of the streams)
@@ -574,12 +568,18 @@ gemm_p256_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
     constexpr int OUT_ELT = EPI == EPI_SWIGLU ? 2 : 4;
     const __amdgpu_buffer_rsrc_t obuf = __builtin_amdgcn_make_buffer_rsrc(outv, 0, int(size_t(M) * N * OUT_ELT), 0x00020000);
     for (int u = 0; u < n_mine; ++u) {
+        // cleared here and nowhere else, so that no accumulator value lives from one item to the next
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("s_nop 7");
+        __builtin_amdgcn_sched_barrier(0);
         for (int kt = 0; kt < nk; ++kt) {
             // phase A: k-step 0; operands of k-step 1; the W item of the slice after next (the weights come from HBM
             // and get the longer run-up: a slice and a half; the activations are L2 hits)
-            rd_ld(a1, b1, sa, sb, 1, rw, slot_w, voff_w, kw, step_w);
-            mm(a0, b0);
-            mix();
+            phase(a0, b0, a1, b1, sa, sb, 1, rw, slot_w, voff_w, kw, step_w);
             next_w();
             // this wave has read all of this slice; the next slice must have landed: only the item just issued may be out
             asm volatile("s_waitcnt vmcnt(8)");
@@ -587,11 +587,14 @@ gemm_p256_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
             sa = sa >= P_SLOTS - 2 ? sa + 2 - P_SLOTS : sa + 2;
             sb = sb >= P_SLOTS - 2 ? sb + 2 - P_SLOTS : sb + 2;
             // phase B: k-step 1; first operands of the next slice; the A item of the slice after next into a freed slot
-            rd_ld(a0, b0, sa, sb, 0, ra, slot_a, voff_a, ka, step_a);
-            mm(a1, b1);
-            mix();
+            phase(a1, b1, a0, b0, sa, sb, 0, ra, slot_a, voff_a, ka, step_a);
             next_a();
         }
+        // The asm MFMAs are opaque to the compiler's hazard handling: let the last of them (four passes) retire
+        // before the accumulators are read.
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("s_nop 15\n\ts_nop 15");
+        __builtin_amdgcn_sched_barrier(0);
         // epilogue of item u (the next item's first slices are in flight); accumulator (i, j)[v] is row 16 i + 4 lq + v, column 16 j + l16
         const int q = tile_of(u), t = q % n_tiles;
         const int m0 = (t % tiles_m) * 256, c0 = (t / tiles_m) * OUT_COLS;
@@ -634,7 +637,6 @@ gemm_p256_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
                         unsigned short bits;
                         __builtin_memcpy(&bits, &o, 2);
                         __builtin_amdgcn_raw_buffer_store_b16(bits, obuf, base, (i * 16 + v) * pitch + (j >> 1) * 32, 0);
-                        acc[i][j][v] = 0.f; acc[i][j + 1][v] = 0.f;
                     }
         } else if (finish) {
             const unsigned base = unsigned(row0 * N + c0 + wn * 128 + l16) * 4u;
@@ -655,16 +657,8 @@ gemm_p256_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
                         float x = acc[i][j][v];
                         if constexpr (EPI == EPI_RESIDUAL_F32) x += old[j][v];
                         __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(x), obuf, base + unsigned((i * 16 + v) * N + j * 16) * 4u, 0, 0);
-                        acc[i][j][v] = 0.f;
                     }
             }
-        } else {
-#pragma unroll
-            for (int i = 0; i < 8; ++i)
-#pragma unroll
-                for (int j = 0; j < 8; ++j)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.f;
         }
         // loads and stores complete out of order with respect to each other: nothing is counted across them
         asm volatile("s_waitcnt vmcnt(0)");
