@@ -4,7 +4,9 @@
 // MFMA shape used throughout: v_mfma_f32_32x32x16_bf16.  For D[32x32] += A[32x16] * B[16x32]
 // lane l supplies A[l%32][8*(l/32) .. +7] and B[8*(l/32) .. +7][l%32], and holds
 // D[8*(v/4) + 4*(l/32) + v%4][l%32] in accumulator register v (0..15).
+#include <mutex>
 #include <type_traits>
+#include <vector>
 
 #include "kernels.hpp"
 
@@ -436,53 +438,85 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
 // =====================================================================================
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 constexpr int P_ITEM = 256 * 128, P_SLOTS = 5, P_LDS = P_ITEM * P_SLOTS;
+// Operand fragments are held as four 32-bit words (eight bf16 values along K).
+typedef __attribute__((__vector_size__(4 * sizeof(int)))) int p256_frag_t;
+
+// An MFMA as an asm statement with the accumulator tied to an AGPR tuple: the 64 accumulators of a wave then
+// fill the AGPR file exactly and stay where they are (left to itself the allocator rotates them through
+// misaligned tuples with a hundred register copies per slice, each waiting for the MFMA that wrote its source),
+// and, being volatile, the statements pin the order of the LDS reads and loads written between them: source
+// order is issue order.  The compiler's hazard handling does not see them: the kernel puts the wait states
+// between the last MFMA of an item and the first read of an accumulator itself.
+__device__ __forceinline__ void p256_mfma(f32x4& c, const p256_frag_t& a, const p256_frag_t& b) {
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+}
+
+// Column panels.  The N dimension is cut into panels of 8, 6 or 4 MFMA tiles per wave (256, 192 or 128 rows of
+// W; the widest first), so that the number of work items can be made a whole number of rounds over the CUs where
+// 256-wide panels alone leave some idle (448 items on 256 CUs: 224 workgroups of two; with 64 panels of 256 and
+// 64 of 192 every CU gets one item of each width, 7/8 of the time).  A work item is one panel x one band of 256
+// rows of A (x one K range when K is split, 256-wide panels only).
+struct P256Plan { int n8, n6, n4; };
 
 template <int EPI>
 __global__ void __launch_bounds__(256)
 gemm_p256_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, const bf16_t* __restrict__ W2,
-                 void* __restrict__ outv, int M, int N, int K, int tiles_m, int tiles_n, int tiles_per_wg,
+                 void* __restrict__ outv, int M, int N, int K, int tiles_m, P256Plan plan, int tiles_per_wg,
                  float* __restrict__ part, int ksplit) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
-    constexpr int OUT_COLS = EPI == EPI_SWIGLU ? 128 : 256;   // output columns per tile
+    constexpr int UNIT = EPI == EPI_SWIGLU ? 16 : 32;   // output columns per MFMA tile pair of a wave pair: panel of class c = c * UNIT columns
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
     const int l16 = lane & 15, lq = lane >> 4;
-    // A work item is one tile over one of `ksplit` K ranges, numbered range-major (item = range * tiles + tile),
-    // so that consecutive items share a K range of the same weight panels.
-    const int n_tiles = tiles_m * tiles_n;
+    // Items are numbered class-major (all 256-wide panels, then the 192-wide, then the 128-wide), within a class
+    // panel-major, and over the K ranges range-major (item = range * tiles + tile).
+    const int t8 = tiles_m * plan.n8, t6 = tiles_m * plan.n6, n_tiles = t8 + t6 + tiles_m * plan.n4;
     const int nb = n_tiles * ksplit, G = gridDim.x;
-    // item u of this workgroup.  Workgroup b runs on XCD b % 8: where the counts divide, an XCD owns
-    // nb / 8 consecutive items (whole weight panels, shared through its L2 by workgroups in step).
-    const bool by_xcd = (nb & 7) == 0 && (G & 7) == 0;
-    const int xcd = blockIdx.x & 7, jw = blockIdx.x >> 3, per_xcd = nb >> 3, wg_per_xcd = G >> 3;
-    auto tile_of = [&](int u) { return by_xcd ? xcd * per_xcd + jw + u * wg_per_xcd : int(blockIdx.x) + u * G; };
+    // item u of this workgroup: one per round of G items.  Workgroup b runs on XCD b % 8: where the grid divides,
+    // an XCD takes G / 8 consecutive items of a round (whole weight panels, shared through its L2).
+    const bool by_xcd = (G & 7) == 0;
+    const int in_round = by_xcd ? (blockIdx.x & 7) * (G >> 3) + (blockIdx.x >> 3) : int(blockIdx.x);
+    auto item_of = [&](int u) { return u * G + in_round; };
     int n_mine = 0;
     for (int u = 0; u < tiles_per_wg; ++u)
-        if (by_xcd ? jw + u * wg_per_xcd < per_xcd : int(blockIdx.x) + u * G < nb) ++n_mine;
+        if (item_of(u) < nb) ++n_mine;
     if (n_mine == 0) return;
     const int nk = K / ksplit / 64;   // slices per item
+    // geometry of tile t: MFMA tiles per wave along N, first row of A, first column (in units of UNIT)
+    auto tile_geom = [&](int t, int* nj, int* m0, int* col_units) {
+        int c, p;
+        if (t < t8) { c = 8; p = t; *col_units = 0; }
+        else if (t < t8 + t6) { c = 6; p = t - t8; *col_units = 8 * plan.n8; }
+        else { c = 4; p = t - t8 - t6; *col_units = 8 * plan.n8 + 6 * plan.n6; }
+        *nj = c;
+        *m0 = (p % tiles_m) * 256;
+        *col_units += c * (p / tiles_m);
+    };
 
     // ---- loads.  Wave-load wl = wave + 4 i of an item covers its rows 8 wl .. 8 wl + 7 (128 B each).
     const int lr = lane >> 3, lpos = lane & 7;
     const unsigned chunk = unsigned((lpos ^ (((wave & 1) << 2) + (lr >> 1))) << 4);
     const unsigned voff_a = unsigned((8 * wave + lr) * K * 2) + chunk, step_a = unsigned(32 * K * 2);
-    // W rows: plain, item row = matrix row; SwiGLU, waves 0 and 1 fetch gate rows, waves 2 and 3 up rows
+    // W rows: plain, item row = panel row; SwiGLU, waves 0 and 1 fetch gate rows, waves 2 and 3 up rows.  The
+    // item always has 256 rows: those past the panel lie outside the descriptor and arrive as zeros.
     const unsigned voff_w = EPI == EPI_SWIGLU ? unsigned((8 * (wave & 1) + lr) * K * 2) + chunk : voff_a;
     const unsigned step_w = EPI == EPI_SWIGLU ? unsigned(16 * K * 2) : step_a;
     __amdgpu_buffer_rsrc_t ra, rw;
     int ka = 0, ua = 0, kw = 0, uw = 0, slot_a = 1, slot_w = 0;
     // descriptors start at the item's first row and first K element
     auto set_a = [&]() {
-        const int q = tile_of(ua), t = q % n_tiles, kbeg = (q / n_tiles) * nk * 64;
-        const int m0 = (t % tiles_m) * 256;
+        const int q = item_of(ua), kbeg = (q / n_tiles) * nk * 64;
+        int nj, m0, cu;
+        tile_geom(q % n_tiles, &nj, &m0, &cu);
         ra = __builtin_amdgcn_make_buffer_rsrc((void*)(A + size_t(m0) * K + kbeg), 0, min(256, M - m0) * K * 2 - kbeg * 2, 0x00020000);
     };
     auto set_w = [&]() {
-        const int q = tile_of(uw), t = q % n_tiles, kbeg = (q / n_tiles) * nk * 64;
-        const int tn = t / tiles_m;
-        const bf16_t* base = EPI == EPI_SWIGLU ? ((wave >> 1) ? W2 : W) + size_t(tn) * 128 * K : W + size_t(tn) * 256 * K;
-        rw = __builtin_amdgcn_make_buffer_rsrc((void*)(base + kbeg), 0, OUT_COLS * K * 2 - kbeg * 2, 0x00020000);
+        const int q = item_of(uw), kbeg = (q / n_tiles) * nk * 64;
+        int nj, m0, cu;
+        tile_geom(q % n_tiles, &nj, &m0, &cu);
+        const bf16_t* base = (EPI == EPI_SWIGLU && (wave >> 1) ? W2 : W) + size_t(cu) * UNIT * K;
+        rw = __builtin_amdgcn_make_buffer_rsrc((void*)(base + kbeg), 0, nj * UNIT * K * 2 - kbeg * 2, 0x00020000);
     };
     auto next_a = [&]() {
         slot_a = slot_a >= P_SLOTS - 2 ? slot_a + 2 - P_SLOTS : slot_a + 2;
@@ -507,52 +541,44 @@ gemm_p256_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (CAKE_LDS_AS void*)(dst + r * 4096), 16, voff, kk * 128 + r * step, 0, 0);
     };
 
-    // ---- operand reads: MFMA tile i of this wave = rows 16 i .. 16 i + 15 of its 128; k-step ks = chunks 4 ks .. 4 ks + 3
+    // ---- operand reads: MFMA tile i of this wave = rows 16 i .. 16 i + 15 of its share of the item (A: 128 rows from
+    // 128 wm; W: 16 nj rows from 16 nj wn); k-step ks = chunks 4 ks .. 4 ks + 3
     const int sw = (l16 >> 1) & 7;
-    const int a_lane = (wm * 128 + l16) * 128, b_lane = (wn * 128 + l16) * 128;
+    const int a_lane = (wm * 128 + l16) * 128, b_lane = l16 * 128;
     int kch[2];
     kch[0] = (lq ^ sw) << 4;
     kch[1] = ((4 + lq) ^ sw) << 4;
     f32x4 acc[8][8];
-    // Operand fragments are held as four 32-bit words (eight bf16 values along K).
-    typedef __attribute__((__vector_size__(4 * sizeof(int)))) int frag_t;
-    frag_t a0[8], b0[8], a1[8], b1[8];
-    auto rd = [&](frag_t* a, frag_t* b, int sa, int sb, int ks) {
+    p256_frag_t a0[8], b0[8], a1[8], b1[8];
+    // One phase of an item of class nj (a constant where this is called): the 8 nj MFMAs of a k-step on (a, b), with
+    // the 8 + nj operand reads of the next k-step (into an, bn: W fragments first, they are needed by the first
+    // MFMAs) and the eight wave-loads of one item dealt between them in `slots` places, two reads then a load,
+    // at even distances, the last MFMAs after the last read.  b_wave: byte offset of this wave's W rows in an item,
+    // of the class the fragments READ here belong to (the next item's in the last phase of an item).
+    auto phase = [&](const int nj, const p256_frag_t* a, const p256_frag_t* b, p256_frag_t* an, p256_frag_t* bn, int sa, int sb,
+                     int ks, int b_wave, __amdgpu_buffer_rsrc_t rs, int slot, unsigned voff, int kk, unsigned step) {
         const unsigned char* pa = lds + sa * P_ITEM + a_lane + kch[ks];
-        const unsigned char* pb = lds + sb * P_ITEM + b_lane + kch[ks];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) b[j] = *(const frag_t*)(pb + j * 2048);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) a[i] = *(const frag_t*)(pa + i * 2048);
-    };
-    // One phase: the 64 MFMAs of a k-step on (a, b), with the sixteen operand reads of the next k-step (into an,
-    // bn) and the eight wave-loads of one item dealt between them: two MFMAs, a read, two MFMAs, a read, two MFMAs,
-    // a load, eight times over, then the last sixteen MFMAs.  The MFMAs are written as asm statements with the
-    // accumulator tied to an AGPR tuple: the 64 accumulators then fill the AGPR file exactly and stay where they
-    // are (left to itself the allocator rotates them through misaligned tuples with a hundred register copies per
-    // slice, each waiting for the MFMA that wrote its source), and, being volatile, they pin the order of the
-    // reads and loads written between them: source order is issue order.
-    auto mfma = [&](int n, const frag_t* a, const frag_t* b) {
-        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[n >> 3][n & 7]) : "v"(a[n >> 3]), "v"(b[n & 7]));
-    };
-    auto phase = [&](const frag_t* a, const frag_t* b, frag_t* an, frag_t* bn, int sa, int sb, int ks, __amdgpu_buffer_rsrc_t rs,
-                     int slot, unsigned voff, int kk, unsigned step) {
-        const unsigned char* pa = lds + sa * P_ITEM + a_lane + kch[ks];
-        const unsigned char* pb = lds + sb * P_ITEM + b_lane + kch[ks];
+        const unsigned char* pb = lds + sb * P_ITEM + b_wave + b_lane + kch[ks];
         unsigned char* dst = lds + slot * P_ITEM + wave * 1024;
+        const int n_mfma = 8 * nj, reads = 8 + nj, slots = reads + 8, spread = n_mfma - (nj == 8 ? 16 : nj == 6 ? 8 : 6);
 #pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            mfma(6 * r, a, b); mfma(6 * r + 1, a, b);
-            if (r < 4) bn[2 * r] = *(const frag_t*)(pb + (2 * r) * 2048);
-            else an[2 * r - 8] = *(const frag_t*)(pa + (2 * r - 8) * 2048);
-            mfma(6 * r + 2, a, b); mfma(6 * r + 3, a, b);
-            if (r < 4) bn[2 * r + 1] = *(const frag_t*)(pb + (2 * r + 1) * 2048);
-            else an[2 * r - 7] = *(const frag_t*)(pa + (2 * r - 7) * 2048);
-            mfma(6 * r + 4, a, b); mfma(6 * r + 5, a, b);
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (CAKE_LDS_AS void*)(dst + r * 4096), 16, voff, kk * 128 + r * step, 0, 0);
+        for (int n = 0; n <= 64; ++n) {
+#pragma unroll
+            for (int sl = 0; sl < 24; ++sl) {
+                if (sl < slots && ((sl + 1) * spread) / slots == n) {
+                    const int grp = sl / 3, pos = sl % 3;
+                    if (sl < 3 * (reads / 2) && pos < 2) {
+                        const int r = 2 * grp + pos;
+                        if (r < nj) bn[r] = *(const p256_frag_t*)(pb + r * 2048);
+                        else an[r - nj] = *(const p256_frag_t*)(pa + (r - nj) * 2048);
+                    } else {
+                        const int l = sl < 3 * (reads / 2) ? grp : reads / 2 + (sl - 3 * (reads / 2));
+                        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (CAKE_LDS_AS void*)(dst + l * 4096), 16, voff, kk * 128 + l * step, 0, 0);
+                    }
+                }
+            }
+            if (n < n_mfma) p256_mfma(acc[n / nj][n % nj], a[n / nj], b[n % nj]);
         }
-#pragma unroll
-        for (int n = 48; n < 64; ++n) mfma(n, a, b);
     };
 
     // prologue: items W0 A0 W1 A1 in flight (dummies past the end of the streams)
@@ -564,9 +590,97 @@ gemm_p256_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
     asm volatile("s_waitcnt vmcnt(16)");
     __builtin_amdgcn_s_barrier();
     int sa = 1, sb = 0;   // slots of the slice being consumed
-    rd(a0, b0, sa, sb, 0);
+    int nj_cur, m0_cur, cu_cur;
+    tile_geom(item_of(0) % n_tiles, &nj_cur, &m0_cur, &cu_cur);
+    {   // first operands of the first item
+        const unsigned char* pa = lds + sa * P_ITEM + a_lane + kch[0];
+        const unsigned char* pb = lds + sb * P_ITEM + wn * nj_cur * 2048 + b_lane + kch[0];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) b0[j] = *(const p256_frag_t*)(pb + j * 2048);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) a0[i] = *(const p256_frag_t*)(pa + i * 2048);
+    }
     constexpr int OUT_ELT = EPI == EPI_SWIGLU ? 2 : 4;
     const __amdgpu_buffer_rsrc_t obuf = __builtin_amdgcn_make_buffer_rsrc(outv, 0, int(size_t(M) * N * OUT_ELT), 0x00020000);
+    // The K loop of an item of class nj (a constant at each of the three call sites)
+    auto k_loop = [&](const int nj, int b_wave, int b_wave_next) {
+        for (int kt = 0; kt < nk; ++kt) {
+            // phase A: k-step 0; operands of k-step 1; the W item of the slice after next (the weights come from HBM
+            // and get the longer run-up: a slice and a half; the activations are L2 hits)
+            phase(nj, a0, b0, a1, b1, sa, sb, 1, b_wave, rw, slot_w, voff_w, kw, step_w);
+            next_w();
+            // this wave has read all of this slice; the next slice must have landed: only the item just issued may be out
+            asm volatile("s_waitcnt vmcnt(8)");
+            __builtin_amdgcn_s_barrier();
+            sa = sa >= P_SLOTS - 2 ? sa + 2 - P_SLOTS : sa + 2;
+            sb = sb >= P_SLOTS - 2 ? sb + 2 - P_SLOTS : sb + 2;
+            // phase B: k-step 1; first operands of the next slice; the A item of the slice after next into a freed slot
+            phase(nj, a1, b1, a0, b0, sa, sb, 0, kt + 1 == nk ? b_wave_next : b_wave, ra, slot_a, voff_a, ka, step_a);
+            next_a();
+        }
+    };
+    // Epilogue of an item of class nj; accumulator (i, j)[v] is row 16 i + 4 lq + v, column 16 j + l16 of the wave's share
+    auto epilogue = [&](const int nj, int q, int m0, int col_units) {
+        const int row0 = m0 + wm * 128 + 4 * lq;
+        if constexpr (EPI == EPI_SWIGLU) {
+            // silu(gate) * up from accumulator pairs (even j: gate, odd j: the same columns of up).  The row offsets go
+            // through the scalar offset of the store.
+            const int pitch = N * 2;
+            const unsigned base = unsigned(row0 * N + col_units * UNIT + wn * nj * 8 + l16) * 2u;
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+#pragma unroll
+                for (int j = 0; j < 8; j += 2)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        if (j < nj) {
+                            const float g = acc[i][j][v], up = acc[i][j + 1][v];
+                            // the hardware reciprocal (1 ulp) instead of an IEEE division: the result is rounded to bf16
+                            const bf16_t o = bf16_t(g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * up);
+                            unsigned short bits;
+                            __builtin_memcpy(&bits, &o, 2);
+                            __builtin_amdgcn_raw_buffer_store_b16(bits, obuf, base, (i * 16 + v) * pitch + (j >> 1) * 32, 0);
+                        }
+        } else if (ksplit > 1) {
+            // This K range's accumulators go to the item's slot of the workspace, in accumulator order (each store
+            // is 4 KB contiguous over the workgroup); a second kernel adds the ranges up and runs the epilogue:
+            // a single workgroup reading a tile's parts back would take longer than the whole K loop.
+            constexpr int TILE_B = 256 * 256 * 4;
+            const __amdgpu_buffer_rsrc_t ws = __builtin_amdgcn_make_buffer_rsrc(part, 0, n_tiles * ksplit * TILE_B, 0x00020000);
+            const unsigned mine = (unsigned(q % n_tiles) * ksplit + unsigned(q / n_tiles)) * TILE_B + unsigned(tid) * 16;
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    u32x4 v = {__float_as_uint(acc[i][j][0]), __float_as_uint(acc[i][j][1]), __float_as_uint(acc[i][j][2]),
+                               __float_as_uint(acc[i][j][3])};
+                    __builtin_amdgcn_raw_buffer_store_b128(v, ws, mine + (i * 8 + j) * 4096, 0, 0);
+                }
+        } else {
+            const unsigned base = unsigned(row0 * N + col_units * UNIT + wn * nj * 16 + l16) * 4u;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                float old[8][4];
+                if constexpr (EPI == EPI_RESIDUAL_F32) {   // all loads of a band of 16 rows in flight before the first add
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v)
+                            if (j < nj)
+                                old[j][v] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(obuf, base + unsigned((i * 16 + v) * N + j * 16) * 4u, 0, 0));
+                }
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        if (j < nj) {
+                            float x = acc[i][j][v];
+                            if constexpr (EPI == EPI_RESIDUAL_F32) x += old[j][v];
+                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(x), obuf, base + unsigned((i * 16 + v) * N + j * 16) * 4u, 0, 0);
+                        }
+            }
+        }
+    };
     for (int u = 0; u < n_mine; ++u) {
         // cleared here and nowhere else, so that no accumulator value lives from one item to the next
 #pragma unroll
@@ -576,90 +690,23 @@ gemm_p256_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
         __builtin_amdgcn_sched_barrier(0);
         asm volatile("s_nop 7");
         __builtin_amdgcn_sched_barrier(0);
-        for (int kt = 0; kt < nk; ++kt) {
-            // phase A: k-step 0; operands of k-step 1; the W item of the slice after next (the weights come from HBM
-            // and get the longer run-up: a slice and a half; the activations are L2 hits)
-            phase(a0, b0, a1, b1, sa, sb, 1, rw, slot_w, voff_w, kw, step_w);
-            next_w();
-            // this wave has read all of this slice; the next slice must have landed: only the item just issued may be out
-            asm volatile("s_waitcnt vmcnt(8)");
-            __builtin_amdgcn_s_barrier();
-            sa = sa >= P_SLOTS - 2 ? sa + 2 - P_SLOTS : sa + 2;
-            sb = sb >= P_SLOTS - 2 ? sb + 2 - P_SLOTS : sb + 2;
-            // phase B: k-step 1; first operands of the next slice; the A item of the slice after next into a freed slot
-            phase(a1, b1, a0, b0, sa, sb, 0, ra, slot_a, voff_a, ka, step_a);
-            next_a();
-        }
+        const int q = item_of(u);
+        int nj_next = nj_cur, m0_next = 0, cu_next = 0;
+        if (u + 1 < n_mine) tile_geom(item_of(u + 1) % n_tiles, &nj_next, &m0_next, &cu_next);
+        const int b_wave = wn * nj_cur * 2048, b_wave_next = wn * nj_next * 2048;
+        if (nj_cur == 8) k_loop(8, b_wave, b_wave_next);
+        else if (nj_cur == 6) k_loop(6, b_wave, b_wave_next);
+        else k_loop(4, b_wave, b_wave_next);
         // The asm MFMAs are opaque to the compiler's hazard handling: let the last of them (four passes) retire
         // before the accumulators are read.
         __builtin_amdgcn_sched_barrier(0);
         asm volatile("s_nop 15\n\ts_nop 15");
         __builtin_amdgcn_sched_barrier(0);
-        // epilogue of item u (the next item's first slices are in flight); accumulator (i, j)[v] is row 16 i + 4 lq + v, column 16 j + l16
-        const int q = tile_of(u), t = q % n_tiles;
-        const int m0 = (t % tiles_m) * 256, c0 = (t / tiles_m) * OUT_COLS;
-        const int row0 = m0 + wm * 128 + 4 * lq;
-        bool finish = true;
-        if constexpr (EPI != EPI_SWIGLU) {
-            if (ksplit > 1) {
-                // This K range's accumulators go to the item's slot of the workspace, in accumulator order (each store
-                // is 4 KB contiguous over the workgroup); a second kernel adds the ranges up and runs the epilogue:
-                // a single workgroup reading a tile's parts back would take longer than the whole K loop.
-                constexpr int TILE_B = 256 * 256 * 4;
-                const __amdgpu_buffer_rsrc_t ws = __builtin_amdgcn_make_buffer_rsrc(part, 0, n_tiles * ksplit * TILE_B, 0x00020000);
-                const unsigned mine = (unsigned(t) * ksplit + unsigned(q / n_tiles)) * TILE_B + unsigned(tid) * 16;
-#pragma unroll
-                for (int i = 0; i < 8; ++i)
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        u32x4 v = {__float_as_uint(acc[i][j][0]), __float_as_uint(acc[i][j][1]), __float_as_uint(acc[i][j][2]),
-                                   __float_as_uint(acc[i][j][3])};
-                        __builtin_amdgcn_raw_buffer_store_b128(v, ws, mine + (i * 8 + j) * 4096, 0, 0);
-                    }
-                finish = false;
-            }
-        }
-        if constexpr (EPI == EPI_SWIGLU) {
-            // The row pitch is made opaque here so that the 32 row offsets are formed per tile, on the scalar unit,
-            // and not kept in vector registers across the K loop (where there are none to spare).
-            int pitch = N * 2;
-            asm volatile("" : "+s"(pitch));
-            const unsigned base = unsigned(row0 * N + c0 + wn * 64 + l16) * 2u;
-#pragma unroll
-            for (int i = 0; i < 8; ++i)
-#pragma unroll
-                for (int j = 0; j < 8; j += 2)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const float g = acc[i][j][v], up = acc[i][j + 1][v];
-                        // silu(g) * up; the hardware reciprocal (1 ulp) instead of an IEEE division: the result is rounded to bf16
-                        const bf16_t o = bf16_t(g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * up);
-                        unsigned short bits;
-                        __builtin_memcpy(&bits, &o, 2);
-                        __builtin_amdgcn_raw_buffer_store_b16(bits, obuf, base, (i * 16 + v) * pitch + (j >> 1) * 32, 0);
-                    }
-        } else if (finish) {
-            const unsigned base = unsigned(row0 * N + c0 + wn * 128 + l16) * 4u;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                float old[8][4];
-                if constexpr (EPI == EPI_RESIDUAL_F32) {   // all 32 loads of a band of 16 rows in flight before the first add
-#pragma unroll
-                    for (int j = 0; j < 8; ++j)
-#pragma unroll
-                        for (int v = 0; v < 4; ++v)
-                            old[j][v] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(obuf, base + unsigned((i * 16 + v) * N + j * 16) * 4u, 0, 0));
-                }
-#pragma unroll
-                for (int j = 0; j < 8; ++j)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        float x = acc[i][j][v];
-                        if constexpr (EPI == EPI_RESIDUAL_F32) x += old[j][v];
-                        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(x), obuf, base + unsigned((i * 16 + v) * N + j * 16) * 4u, 0, 0);
-                    }
-            }
-        }
+        // (the next item's first slices are in flight during the epilogue)
+        if (nj_cur == 8) epilogue(8, q, m0_cur, cu_cur);
+        else if (nj_cur == 6) epilogue(6, q, m0_cur, cu_cur);
+        else epilogue(4, q, m0_cur, cu_cur);
+        nj_cur = nj_next; m0_cur = m0_next; cu_cur = cu_next;
         // loads and stores complete out of order with respect to each other: nothing is counted across them
         asm volatile("s_waitcnt vmcnt(0)");
     }
@@ -761,13 +808,20 @@ enum { GCFG_256x256 = 0, GCFG_256x128 = 1, GCFG_128x128 = 2, GCFG_128x192 = 3, G
        GCFG_COUNT = 7 };
 static const GemmCfg kGemmCfg[GCFG_COUNT] = {{256, 256}, {256, 128}, {128, 128}, {128, 192}, {128, 64}, {128, 128}, {256, 256}};
 
+struct P256Plan;
+static P256Plan p256_plan(int epi, int tiles_m, int N);
+static double p256_plan_cost(int tiles_m, int n8, int n6, int n4);
+
 static int out_cols_per_tile(int cfg, int epi) { return epi == EPI_SWIGLU ? kGemmCfg[cfg].bn / 2 : kGemmCfg[cfg].bn; }
 
 static bool gemm_cfg_ok(int cfg, int epi, int M, int N, int K) {
     if ((cfg == GCFG_128x192 || cfg == GCFG_128x64) && epi == EPI_SWIGLU) return false;   // odd n-tiles per wave: no gate/up pairs
     if (cfg == GCFG_128x128K && (epi == EPI_SWIGLU || (K % 64) != 0)) return false;
     // the persistent kernel addresses everything through 32-bit buffer offsets
-    if (cfg == GCFG_P256 && ((K % 64) != 0 || double(M) * N * 4 >= 2147483648.0 || double(K) * 512 >= 2147483648.0)) return false;
+    // (its column panels are 256, 192 or 128 rows of W wide: N in units of 64, of 32 for SwiGLU)
+    if (cfg == GCFG_P256)
+        return M > 0 && N > 0 && K >= 64 && (K % 64) == 0 && double(M) * N * 4 < 2147483648.0 && double(K) * 512 < 2147483648.0 &&
+               (N % (epi == EPI_SWIGLU ? 32 : 64)) == 0;
     return M > 0 && N > 0 && K >= 32 && (K % 32) == 0 && (N % out_cols_per_tile(cfg, epi)) == 0;
 }
 
@@ -786,25 +840,36 @@ static bool ksplit_ok(int cfg, int ks, int epi, int M, int N, int K, const GemmS
     if (!ws || !ws->part || !ws->counters || epi == EPI_SWIGLU) return false;
     if (K % ks || (K / ks) % 64 || K / ks < 512) return false;
     const GemmCfg& c = kGemmCfg[cfg];
+    if (N % c.bn) return false;
     const long tiles = long((M + c.bm - 1) / c.bm) * (N / c.bn);
     return tiles <= ws->n_counters && size_t(tiles) * ks * c.bm * c.bn * sizeof(float) <= ws->part_bytes;
 }
 static GemmChoice gemm_pick(int epi, int M, int N, int K, const GemmSplitWs* ws) {
-    static const double eff[GCFG_COUNT] = {1.0, 0.77, 0.62, 0.61, 0.40, 0.65, 1.11};   // measured TFLOP/s per busy CU, relative to 256x256
+    static const double eff[GCFG_COUNT] = {1.0, 0.60, 0.62, 0.80, 0.40, 0.65, 1.11};   // measured TFLOP/s per busy CU, relative to 256x256
     GemmChoice best{GCFG_128x128, 1};
     double best_cost = 1e30;
     for (int cfg = GCFG_COUNT - 1; cfg >= 0; --cfg) {
         if (!gemm_cfg_ok(cfg, epi, M, N, K)) continue;
         const GemmCfg& c = kGemmCfg[cfg];
+        if (cfg == GCFG_P256) {
+            // The persistent kernel needs a grid that fills the chip.  With K split, its parts (256 KB per workgroup)
+            // go through memory to a second kernel, about 45 us for 256 of them: measured 487 us against 443 for the
+            // eight-wave 256 x 256 kernel on 1024 x 8192 x 28672 in two ranges, 155 against 140 for 128 x 128 tiles
+            // on 1024 x 4096 x 14336 in four.  So it is chosen unsplit only (the split path stays for forced use).
+            const int tiles_m = (M + 255) / 256;
+            const P256Plan plan = p256_plan(epi, tiles_m, N);
+            const long items = long(tiles_m) * (plan.n8 + plan.n6 + plan.n4);
+            if (items < 160) continue;
+            // p256_plan_cost: the busiest workgroup's work in units of an eighth of a 256 x 256 tile
+            const double cost = p256_plan_cost(tiles_m, plan.n8, plan.n6, plan.n4) * 12.5 * (double(K) / 4096.0) / eff[cfg] +
+                                6.0 * double((items + 255) / 256);
+            if (cost < best_cost) { best_cost = cost; best = GemmChoice{cfg, 1}; }
+            continue;
+        }
         const long tiles = long((M + c.bm - 1) / c.bm) * (N / out_cols_per_tile(cfg, epi));
         const double area = double(c.bm) * c.bn / 65536.0;
         for (int ks = 1; ks <= 8; ks *= 2) {
             if (!ksplit_ok(cfg, ks, epi, M, N, K, ws)) continue;
-            // The persistent kernel needs a grid that fills the chip.  Split, its parts (256 KB per workgroup) go
-            // through memory to a second kernel, about 45 us for 256 of them: measured 487 us against 443 for the
-            // eight-wave 256 x 256 kernel on 1024 x 8192 x 28672 in two ranges, 155 against 140 for 128 x 128 tiles
-            // on 1024 x 4096 x 14336 in four.  So it is chosen unsplit only (the split path stays for forced use).
-            if (cfg == GCFG_P256 && (tiles < 160 || ks > 1)) continue;
             const double rounds = double((tiles * ks + 255) / 256);
             double cost = rounds * (100.0 * area * (double(K) / ks / 4096.0) / eff[cfg] + 6.0);
             // measured: the parts cross the chip twice, at device scope; and a split must promise 8 % to be taken
@@ -834,13 +899,55 @@ static hipError_t gemm_launch_t(const bf16_t* A, const bf16_t* W, const bf16_t* 
     return hipGetLastError();
 }
 
+// Panel widths of the persistent kernel for N columns and `tiles_m` row bands: counts of 8-, 6- and 4-tile panels
+// with 8 n8 + 6 n6 + 4 n4 = N / unit that minimise the time of the busiest workgroup: items go out widest first,
+// one per workgroup and round, so workgroup 0 takes the widest item of every round.  A narrow item is not
+// faster in proportion (measured, 256 items over K = 4096: 108 us at 256 wide, 86 to 100 at 192, 70 to 74 at 128,
+// and 1.2 us per slice at 128 wide over a long K against 1.46 at 256: the loads, reads and barriers of a slice
+// stay the same), and every item costs an epilogue.
+static double p256_plan_cost(int tiles_m, int n8, int n6, int n4) {
+    const int c8 = tiles_m * n8, c6 = tiles_m * n6, nb = c8 + c6 + tiles_m * n4;
+    const int rounds = (nb + 255) / 256, wgs = (nb + rounds - 1) / rounds;
+    double cost = 0.0;
+    for (int u = 0; u < rounds; ++u) {
+        const int first = u * wgs;
+        cost += (first < c8 ? 8.0 : first < c8 + c6 ? 7.0 : 6.2) + 0.4;
+    }
+    return cost;
+}
+static P256Plan p256_plan(int epi, int tiles_m, int N) {
+    const int unit = epi == EPI_SWIGLU ? 16 : 32;
+    if (N % (2 * unit)) return P256Plan{0, 0, 0};
+    const int U = N / unit;
+    struct Entry { int epi, tiles_m, N; P256Plan plan; };
+    static std::mutex mu;
+    static std::vector<Entry> cache;
+    std::lock_guard<std::mutex> lock(mu);
+    for (const Entry& e : cache)
+        if (e.epi == epi && e.tiles_m == tiles_m && e.N == N) return e.plan;
+    P256Plan best{0, 0, 0};
+    double best_cost = 1e30;
+    for (int n8 = 0; 8 * n8 <= U; ++n8)
+        for (int n6 = 0; 8 * n8 + 6 * n6 <= U; ++n6) {
+            const int rem = U - 8 * n8 - 6 * n6;
+            if (rem % 4) continue;
+            const double c = p256_plan_cost(tiles_m, n8, n6, rem / 4);
+            if (c < best_cost - 1e-9) { best_cost = c; best = P256Plan{n8, n6, rem / 4}; }
+        }
+    cache.push_back(Entry{epi, tiles_m, N, best});
+    return best;
+}
+
 template <int EPI>
 static hipError_t gemm_launch_cfg(int cfg, int ks, const GemmSplitWs* ws, const bf16_t* A, const bf16_t* W, const bf16_t* W2,
                                   void* out, int M, int N, int K, hipStream_t st) {
     const long tiles128 = long((M + 127) / 128) * (N / (EPI == EPI_SWIGLU ? 64 : 128)) * ks;
     if (cfg == GCFG_P256) {
-        // a whole number of rounds: every workgroup takes `rounds` tiles (the last may take one less)
-        const int tiles_m = (M + 255) / 256, tiles_n = N / (EPI == EPI_SWIGLU ? 128 : 256), nb = tiles_m * tiles_n * ks;
+        const int tiles_m = (M + 255) / 256;
+        const P256Plan plan = ks > 1 ? P256Plan{N / 256, 0, 0} : p256_plan(EPI, tiles_m, N);
+        const int panels = plan.n8 + plan.n6 + plan.n4, nb = tiles_m * panels * ks;
+        if (panels == 0) return hipErrorInvalidValue;
+        // a whole number of rounds: every workgroup takes `rounds` items (the last may take one less)
         const int rounds = (nb + 255) / 256, wgs = (nb + rounds - 1) / rounds;
         auto kern = gemm_p256_kernel<EPI>;
         static bool attr_set = false;
@@ -849,11 +956,11 @@ static hipError_t gemm_launch_cfg(int cfg, int ks, const GemmSplitWs* ws, const 
             if (e != hipSuccess) return e;
             attr_set = true;
         }
-        hipLaunchKernelGGL(kern, dim3(wgs), dim3(256), P_LDS, st, A, W, W2, out, M, N, K, tiles_m, tiles_n, rounds,
+        hipLaunchKernelGGL(kern, dim3(wgs), dim3(256), P_LDS, st, A, W, W2, out, M, N, K, tiles_m, plan, rounds,
                            ks > 1 ? ws->part : nullptr, ks);
         if (ks > 1) {
             if constexpr (EPI != EPI_SWIGLU)
-                hipLaunchKernelGGL(gemm_p256_finish_kernel<EPI>, dim3(tiles_m * tiles_n * 8), dim3(256), 0, st, ws->part, (float*)out,
+                hipLaunchKernelGGL(gemm_p256_finish_kernel<EPI>, dim3(tiles_m * plan.n8 * 8), dim3(256), 0, st, ws->part, (float*)out,
                                    M, N, tiles_m, ks);
         }
         return hipGetLastError();

@@ -36,6 +36,7 @@ def main(argv=None):
     ap.add_argument("--weight-sets", type=int, default=8)
     ap.add_argument("--ops", default=",".join(OPS))
     ap.add_argument("--gemm-config", type=int, default=0, help="0 = the library's choice, 1..7 = force a kernel")
+    ap.add_argument("--gemm-ksplit", type=int, default=0, help="0 = the library's choice, n = K in n ranges where the kernel allows")
     ap.add_argument("--attn-variant", type=int, default=0)
     ap.add_argument("--vendor", action="store_true", help="also run the GEMMs through torch.matmul")
     args = ap.parse_args(argv)
@@ -56,7 +57,7 @@ def main(argv=None):
         if o not in OPS:
             sys.exit("kernel_bench: unknown op %r (known: %s)" % (o, ", ".join(OPS)))
     eng = cake.Engine(shape, None, max_tokens=T, max_chunk=M, page_tokens=256, seed=0)
-    eng.set_tuning(gemm_config=args.gemm_config, attn_variant=args.attn_variant)
+    eng.set_tuning(gemm_config=args.gemm_config, gemm_ksplit=args.gemm_ksplit, attn_variant=args.attn_variant)
     lib, ctx = eng.lib, eng.ctx
     g = torch.Generator(device="cuda").manual_seed(1)
 

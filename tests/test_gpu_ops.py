@@ -56,6 +56,9 @@ def test_rmsnorm(kind, rows, d):
     # the persistent four-wave kernel: one slice; ragged M over three slices; many slices; more tiles than
     # workgroups (260 plain tiles = 2 rounds of 130 workgroups, 520 SwiGLU tiles = 3 rounds, the last one short)
     ("bf16", 0, 257, 256, 64, 7), ("bf16", 0, 300, 768, 192, 7), ("bf16", 0, 1024, 512, 4096, 7), ("bf16", 0, 1000, 16640, 128, 7),
+    # its column panels of mixed width: 256- and 192-wide in one round (plain) and in consecutive rounds of the same
+    # workgroups (SwiGLU: 64 + 64 panels x 4 row bands = 512 items); 192- and 128-wide likewise
+    ("bf16", 0, 1024, 14336, 128, 7), ("bf16", 0, 1024, 10240, 192, 7),
 ])
 def test_gemm_variants(kind, path, M, N, K, cfg):
     import torch
