@@ -23,7 +23,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-OPS = ("qkv", "attention", "o", "gateup", "down")
+OPS = ("qkv", "attention", "o", "gateup", "down", "mfma")
 
 
 def main(argv=None):
@@ -34,7 +34,8 @@ def main(argv=None):
     ap.add_argument("--iters", type=int, default=20)
     ap.add_argument("--warm", type=int, default=3)
     ap.add_argument("--weight-sets", type=int, default=8)
-    ap.add_argument("--ops", default=",".join(OPS))
+    ap.add_argument("--ops", default="qkv,attention,o,gateup,down",
+                    help="comma-separated: qkv, attention, o, gateup, down, and mfma (the MFMA-only yardstick, cake_op_mfma_rate)")
     ap.add_argument("--gemm-config", type=int, default=0, help="0 = the library's choice, 1..7 = force a kernel")
     ap.add_argument("--gemm-ksplit", type=int, default=0, help="0 = the library's choice, n = K in n ranges where the kernel allows")
     ap.add_argument("--attn-variant", type=int, default=0)
@@ -98,7 +99,8 @@ def main(argv=None):
     make = {"qkv": lambda: gemm_case(hq + 2 * hkv, d, False), "attention": attention_case,
             "o": lambda: gemm_case(d, hq, True), "gateup": gateup_case, "down": lambda: gemm_case(d, ff, True)}
     for o in ops:
-        cases[o] = make[o]()
+        if o != "mfma":
+            cases[o] = make[o]()
 
     def timed(fn, check):
         for i in range(args.warm):
@@ -120,6 +122,10 @@ def main(argv=None):
           % (full.name, M, args.tok_begin, ws, args.iters))
     print("# %-10s %10s %10s %12s %12s" % ("op", "us", "TFLOP/s", "vendor us", "vendor TFLOP/s"))
     for o in ops:
+        if o == "mfma":   # 2048 workgroups x 8 waves x 4096 rounds of eight 32x32x16 MFMAs on register operands
+            rates = sorted(eng.mfma_rate(2048, 4096) for _ in range(3))
+            print("  %-10s %10s %10.1f   (median of three 10 ms launches; min %.1f, max %.1f)" % (o, "-", rates[1], rates[0], rates[2]), flush=True)
+            continue
         flop, ours, vendor = cases[o]
         us = timed(ours, True)
         line = "  %-10s %10.1f %10.1f" % (o, us, flop / us / 1e6)
