@@ -129,7 +129,8 @@ def measure_config(cake, si, torch, name, T, C, pt, gbps_list, steps, warmup):
     import numpy as np
     shape = si.SHAPES[name]
     n = (T + C - 1) // C
-    eng = cake.Engine(shape, None, max_tokens=T, max_chunk=C, page_tokens=pt, seed=0, with_head=False)
+    step = max(C, 1024) if shape.dtype == "bf16" else C    # compute step of the wide-step leg below
+    eng = cake.Engine(shape, None, max_tokens=T, max_chunk=step, page_tokens=pt, seed=0, with_head=False)
     toks = si.make_tokens(T, shape.vocab, seed=1)
     eng.bidirectional_prefill(toks, C, gbps_list[0], mode="compute_only", log=False)
     eng.store_from_pool(T)
@@ -157,6 +158,23 @@ def measure_config(cake, si, torch, name, T, C, pt, gbps_list, steps, warmup):
             "speedup_over_compute_only": round(r_c.ttft_ns / 1e9 / ttft, 3),
             "achieved_gbps_bidirectional": round(load_bytes / load_ns, 4) if load_ns else None,
             "achieved_gbps_load_only": round(r_l.achieved_gbps, 4)}
+    # Chunks shorter than 1024 tokens halve the GEMMs' M.  The engine's compute step and its fetch unit are separate
+    # (Sec. 5.1 "Implementation": 128-token fetch chunks under 512/1024-token compute chunks), so the same request
+    # also runs with 1024-token compute steps over fetch units of one chunk: two chunks' rows per pass over the weights.
+    wide = None
+    if step > C:
+        reqs = [dict(tokens=toks, arrival_ns=0, prefix=True)]
+        wide = {}
+        for gbps in gbps_list:
+            eng.adaptive_serve(reqs, step, C, gbps)
+            fr = [eng.adaptive_serve(reqs, step, C, gbps) for _ in range(steps)]
+            wide["%g_gbs" % gbps] = {"compute_step_tokens": step, "fetch_unit_tokens": C,
+                                     "ttft_s": round(float(np.mean([f[0].ttft_ns for f in fr])) / 1e9, 5),
+                                     "tokens_computed": [f[1][0]["tokens_computed"] for f in fr],
+                                     "tokens_loaded": [f[1][0]["tokens_loaded"] for f in fr]}
+        r_w = eng.bidirectional_prefill(toks, step, gbps_list[0], mode="compute_only")
+        wide["compute_only_s"] = round(r_w.ttft_ns / 1e9, 5)
+        wide["prefill_tflops_compute_only"] = round(r_w.compute_tflops, 1)
     out = {"workload": "%s, %d random tokens, chunk %d, page %d, stored KV in pinned host memory at %s GB/s"
                        % (shape.name, T, C, pt, "/".join("%g" % g for g in gbps_list)),
            "dtype": "bf16" if shape.dtype == "bf16" else "f32", "n_chunks": n, "steps": steps, "warmup": warmup,
@@ -164,6 +182,8 @@ def measure_config(cake, si, torch, name, T, C, pt, gbps_list, steps, warmup):
            "tiers": tiers, "kernels": kernels}
     if shape.dtype == "bf16":
         out["mfma_util_compute_only"] = round(r_c.compute_tflops / PEAK_BF16_TFLOPS, 4)
+    if wide:
+        out["wide_compute_steps"] = wide
     eng.close()
     del eng
     torch.cuda.empty_cache()
