@@ -200,9 +200,17 @@ def test_attention(kind, path, variant, tok_begin, rows):
     Q = torch.from_numpy(q.transpose(1, 0, 2).astype(np.float32).copy()).cuda().to(td)
     got = eng.op_attention(Q, 0, tok_begin).float().cpu().numpy().reshape(rows, nq, hd)
     want = otf.attention(q, cache.k[0], cache.v[0], np.arange(tok_begin, T), np.arange(T))
-    # bf16: probabilities and the output are rounded to bf16 (2^-9 each, relative to the row's scale)
-    tol = 2e-5 if kind == "f32" else 1.2e-2
-    assert _rel(got, want) < tol, _rel(got, want)
+    # bf16: the output (2^-9), each probability where it enters P.V (2^-9) and, in the eight-wave kernels, Q once more
+    # after the softmax scale has been folded into it (2^-9, acting in the exponent: it dominates on these peaked
+    # rows).  The same three roundings repeated in float64 give up to 6.2e-3 of the largest value on inputs of this
+    # distribution (tests/test_gpu_attention_long.py has the derivation); the bound is 2^-7, and no row may be off
+    # as a whole (a tile dropped or read from the wrong page shifts a row; rounding does not).
+    tol = 2e-5 if kind == "f32" else 2.0 ** -7
+    err = _rel(got, want)
+    row_rms = np.sqrt(((got - want) ** 2).mean(axis=2)).max() / np.abs(want).max()
+    print("attention error: largest %.2e, worst row rms %.2e (of the largest value)" % (err, row_rms))
+    assert err < tol, err
+    assert row_rms < tol / 2, row_rms
 
 
 def test_attention_and_page_write_above_2_and_4_gib():
@@ -233,7 +241,7 @@ def test_attention_and_page_write_above_2_and_4_gib():
     # attention over what the pages actually hold (already checked against the oracle above)
     held = ostore.unpack_store(eng.pool_raw(T).view(np.uint16), T, nkv, hd, pt, "bf16")
     want = otf.attention(q64, held.k[0], held.v[0], pos, pos)
-    assert _rel(got, want) < 1.2e-2
+    assert _rel(got, want) < 2.0 ** -7
 
 
 @pytest.mark.parametrize("kind,path,shape_kw,T,pt", [
