@@ -458,7 +458,9 @@ __device__ __forceinline__ void p256_mfma(f32x4& c, const p256_frag_t& a, const 
 // rows of A (x one K range when K is split, 256-wide panels only).
 struct P256Plan { int n8, n6, n4; };
 
-template <int EPI>
+// SPLIT: the instantiation that runs one K range per item and leaves its accumulators in the workspace (256-wide
+// panels only); kept apart so that each instantiation has a single epilogue path.
+template <int EPI, bool SPLIT>
 __global__ void __launch_bounds__(256)
 gemm_p256_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, const bf16_t* __restrict__ W2,
                  void* __restrict__ outv, int M, int N, int K, int tiles_m, P256Plan plan, int tiles_per_wg,
@@ -556,7 +558,8 @@ gemm_p256_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
     // at even distances, the last MFMAs after the last read.  b_wave: byte offset of this wave's W rows in an item,
     // of the class the fragments READ here belong to (the next item's in the last phase of an item).
     auto phase = [&](const int nj, const p256_frag_t* a, const p256_frag_t* b, p256_frag_t* an, p256_frag_t* bn, int sa, int sb,
-                     int ks, int b_wave, __amdgpu_buffer_rsrc_t rs, int slot, unsigned voff, int kk, unsigned step) {
+                     int ks, int b_wave, __amdgpu_buffer_rsrc_t rs, int slot, unsigned voff, int kk, unsigned step)
+                     __attribute__((always_inline)) {
         const unsigned char* pa = lds + sa * P_ITEM + a_lane + kch[ks];
         const unsigned char* pb = lds + sb * P_ITEM + b_wave + b_lane + kch[ks];
         unsigned char* dst = lds + slot * P_ITEM + wave * 1024;
@@ -603,7 +606,7 @@ gemm_p256_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
     constexpr int OUT_ELT = EPI == EPI_SWIGLU ? 2 : 4;
     const __amdgpu_buffer_rsrc_t obuf = __builtin_amdgcn_make_buffer_rsrc(outv, 0, int(size_t(M) * N * OUT_ELT), 0x00020000);
     // The K loop of an item of class nj (a constant at each of the three call sites)
-    auto k_loop = [&](const int nj, int b_wave, int b_wave_next) {
+    auto k_loop = [&](const int nj, int b_wave, int b_wave_next) __attribute__((always_inline)) {
         for (int kt = 0; kt < nk; ++kt) {
             // phase A: k-step 0; operands of k-step 1; the W item of the slice after next (the weights come from HBM
             // and get the longer run-up: a slice and a half; the activations are L2 hits)
@@ -620,7 +623,7 @@ gemm_p256_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
         }
     };
     // Epilogue of an item of class nj; accumulator (i, j)[v] is row 16 i + 4 lq + v, column 16 j + l16 of the wave's share
-    auto epilogue = [&](const int nj, int q, int m0, int col_units) {
+    auto epilogue = [&](const int nj, int q, int m0, int col_units) __attribute__((always_inline)) {
         const int row0 = m0 + wm * 128 + 4 * lq;
         if constexpr (EPI == EPI_SWIGLU) {
             // silu(gate) * up from accumulator pairs (even j: gate, odd j: the same columns of up).  The row offsets go
@@ -641,7 +644,7 @@ gemm_p256_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
                             __builtin_memcpy(&bits, &o, 2);
                             __builtin_amdgcn_raw_buffer_store_b16(bits, obuf, base, (i * 16 + v) * pitch + (j >> 1) * 32, 0);
                         }
-        } else if (ksplit > 1) {
+        } else if constexpr (SPLIT) {
             // This K range's accumulators go to the item's slot of the workspace, in accumulator order (each store
             // is 4 KB contiguous over the workgroup); a second kernel adds the ranges up and runs the epilogue:
             // a single workgroup reading a tile's parts back would take longer than the whole K loop.
@@ -949,12 +952,15 @@ static hipError_t gemm_launch_cfg(int cfg, int ks, const GemmSplitWs* ws, const 
         if (panels == 0) return hipErrorInvalidValue;
         // a whole number of rounds: every workgroup takes `rounds` items (the last may take one less)
         const int rounds = (nb + 255) / 256, wgs = (nb + rounds - 1) / rounds;
-        auto kern = gemm_p256_kernel<EPI>;
-        static bool attr_set = false;
-        if (!attr_set) {
+        auto kern = gemm_p256_kernel<EPI, false>;
+        if constexpr (EPI != EPI_SWIGLU) {
+            if (ks > 1) kern = gemm_p256_kernel<EPI, true>;
+        }
+        static bool attr_set[2] = {false, false};
+        if (!attr_set[ks > 1]) {
             hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS);
             if (e != hipSuccess) return e;
-            attr_set = true;
+            attr_set[ks > 1] = true;
         }
         hipLaunchKernelGGL(kern, dim3(wgs), dim3(256), P_LDS, st, A, W, W2, out, M, N, K, tiles_m, plan, rounds,
                            ks > 1 ? ws->part : nullptr, ks);
