@@ -418,7 +418,7 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
 //  * K in 64-deep slices (whole 128-byte lines from L2, half the requests of 32-deep slices), each slice
 //    two 32 KB items (the A rows, the W rows) in a ring of five LDS slots filled by buffer loads to LDS;
 //    row r of an item stores its 16-byte chunk c at c ^ ((r >> 1) & 7), so the sixteen rows a
-//    quarter-wave reads hit all 64 banks once;
+//    quarter-wave reads hit all 64 banks once (the rows of an item are permuted in LDS, see tile_off);
 //  * a slice is two phases of 64 MFMAs: phase A computes k-step 0 while the operands of k-step 1 are read
 //    and the W item of slice g+2 is loaded; then one barrier (this slice's slots are free, the next slice
 //    has landed); phase B computes k-step 1 while the first operands of slice g+1 are read and the A item
@@ -536,17 +536,39 @@ gemm_p256_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
             else rw = __builtin_amdgcn_make_buffer_rsrc((void*)W, 0, 0, 0x00020000);
         }
     };
+    // wave-load l of an item: LDS base of its half of the wave's eight, the immediate offset picks one of four (the
+    // builtin wants it as a literal)
+    auto load_one = [&](__amdgpu_buffer_rsrc_t rs, unsigned char* dst, unsigned voff, int kk, unsigned step, int l)
+                        __attribute__((always_inline)) {
+        CAKE_LDS_AS void* d = (CAKE_LDS_AS void*)(dst + (l >> 2) * 4096);
+        const unsigned so = kk * 128 + l * step - (l & 3) * 1024;
+        switch (l & 3) {
+            case 0: __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, d, 16, voff, so, 0, 0); break;
+            case 1: __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, d, 16, voff, so, 1024, 0); break;
+            case 2: __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, d, 16, voff, so, 2048, 0); break;
+            default: __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, d, 16, voff, so, 3072, 0); break;
+        }
+    };
     auto load_item = [&](__amdgpu_buffer_rsrc_t rs, int slot, unsigned voff, int kk, unsigned step) {
-        unsigned char* dst = lds + slot * P_ITEM + wave * 1024;
+        unsigned char* dst = lds + slot * P_ITEM + wave * 8192;
 #pragma unroll
         for (int r = 0; r < 8; ++r)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (CAKE_LDS_AS void*)(dst + r * 4096), 16, voff, kk * 128 + r * step, 0, 0);
+            load_one(rs, dst, voff, kk, step, r);
     };
 
     // ---- operand reads: MFMA tile i of this wave = rows 16 i .. 16 i + 15 of its share of the item (A: 128 rows from
     // 128 wm; W: 16 nj rows from 16 nj wn); k-step ks = chunks 4 ks .. 4 ks + 3
     const int sw = (l16 >> 1) & 7;
-    const int a_lane = (wm * 128 + l16) * 128, b_lane = l16 * 128;
+    // Where item row R sits in LDS: a wave's eight wave-loads of an item lie next to each other, 1 KB apart, so that
+    // four of them share one value of M0 and differ in the instruction's immediate offset (which the hardware adds
+    // to the LDS address and to the memory address alike; the scalar offset takes it off the latter again).  Every
+    // write of M0 costs the one wave of a SIMD issue time: with one M0 per load the kernel ran 7 % longer.  Row
+    // R = 32 r + 8 w + lr (wave-load r of wave w, row lr of its eight) is at byte 8192 w + 1024 r + 128 lr; for the
+    // rows 16 i + l16 of MFMA tile i above a base that is a multiple of 32 rows that is
+    // 8192 (2 (i & 1) + (l16 >> 3)) + 1024 (base / 32 + (i >> 1)) + 128 (l16 & 7).
+    auto tile_off = [](int i) { return (i & 1) * 16384 + (i >> 1) * 1024; };
+    const int lane_off = (l16 >> 3) * 8192 + (l16 & 7) * 128;
+    const int a_lane = wm * 4096 + lane_off, b_lane = lane_off;
     int kch[2];
     kch[0] = (lq ^ sw) << 4;
     kch[1] = ((4 + lq) ^ sw) << 4;
@@ -562,7 +584,7 @@ gemm_p256_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
                      __attribute__((always_inline)) {
         const unsigned char* pa = lds + sa * P_ITEM + a_lane + kch[ks];
         const unsigned char* pb = lds + sb * P_ITEM + b_wave + b_lane + kch[ks];
-        unsigned char* dst = lds + slot * P_ITEM + wave * 1024;
+        unsigned char* dst = lds + slot * P_ITEM + wave * 8192;
         const int n_mfma = 8 * nj, reads = 8 + nj, slots = reads + 8, spread = n_mfma - (nj == 8 ? 16 : nj == 6 ? 8 : 6);
 #pragma unroll
         for (int n = 0; n <= 64; ++n) {
@@ -572,11 +594,11 @@ gemm_p256_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
                     const int grp = sl / 3, pos = sl % 3;
                     if (sl < 3 * (reads / 2) && pos < 2) {
                         const int r = 2 * grp + pos;
-                        if (r < nj) bn[r] = *(const p256_frag_t*)(pb + r * 2048);
-                        else an[r - nj] = *(const p256_frag_t*)(pa + (r - nj) * 2048);
+                        if (r < nj) bn[r] = *(const p256_frag_t*)(pb + tile_off(r));
+                        else an[r - nj] = *(const p256_frag_t*)(pa + tile_off(r - nj));
                     } else {
                         const int l = sl < 3 * (reads / 2) ? grp : reads / 2 + (sl - 3 * (reads / 2));
-                        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (CAKE_LDS_AS void*)(dst + l * 4096), 16, voff, kk * 128 + l * step, 0, 0);
+                        load_one(rs, dst, voff, kk, step, l);
                     }
                 }
             }
@@ -597,11 +619,11 @@ gemm_p256_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
     tile_geom(item_of(0) % n_tiles, &nj_cur, &m0_cur, &cu_cur);
     {   // first operands of the first item
         const unsigned char* pa = lds + sa * P_ITEM + a_lane + kch[0];
-        const unsigned char* pb = lds + sb * P_ITEM + wn * nj_cur * 2048 + b_lane + kch[0];
+        const unsigned char* pb = lds + sb * P_ITEM + wn * nj_cur * 512 + b_lane + kch[0];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) b0[j] = *(const p256_frag_t*)(pb + j * 2048);
+        for (int j = 0; j < 8; ++j) b0[j] = *(const p256_frag_t*)(pb + tile_off(j));
 #pragma unroll
-        for (int i = 0; i < 8; ++i) a0[i] = *(const p256_frag_t*)(pa + i * 2048);
+        for (int i = 0; i < 8; ++i) a0[i] = *(const p256_frag_t*)(pa + tile_off(i));
     }
     constexpr int OUT_ELT = EPI == EPI_SWIGLU ? 2 : 4;
     const __amdgpu_buffer_rsrc_t obuf = __builtin_amdgcn_make_buffer_rsrc(outv, 0, int(size_t(M) * N * OUT_ELT), 0x00020000);
@@ -696,7 +718,7 @@ gemm_p256_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, con
         const int q = item_of(u);
         int nj_next = nj_cur, m0_next = 0, cu_next = 0;
         if (u + 1 < n_mine) tile_geom(item_of(u + 1) % n_tiles, &nj_next, &m0_next, &cu_next);
-        const int b_wave = wn * nj_cur * 2048, b_wave_next = wn * nj_next * 2048;
+        const int b_wave = wn * nj_cur * 512, b_wave_next = wn * nj_next * 512;   // 16 nj rows = nj / 2 KB steps
         if (nj_cur == 8) k_loop(8, b_wave, b_wave_next);
         else if (nj_cur == 6) k_loop(6, b_wave, b_wave_next);
         else k_loop(4, b_wave, b_wave_next);
