@@ -132,13 +132,13 @@ def measure_config(cake, si, torch, name, T, C, pt, gbps_list, steps, warmup):
     step = max(C, 1024) if shape.dtype == "bf16" else C    # compute step of the wide-step leg below
     eng = cake.Engine(shape, None, max_tokens=T, max_chunk=step, page_tokens=pt, seed=0, with_head=False)
     toks = si.make_tokens(T, shape.vocab, seed=1)
-    eng.bidirectional_prefill(toks, C, gbps_list[0], mode="compute_only", log=False)
-    eng.store_from_pool(T)
-    r_c = eng.bidirectional_prefill(toks, C, gbps_list[0], mode="compute_only")
+    # the pass that produces the stored KV is also the one with every kernel class bracketed by events
     eng.profile_enable(True)
     eng.bidirectional_prefill(toks, C, gbps_list[0], mode="compute_only", log=False)
     stats = eng.profile_read()
     eng.profile_enable(False)
+    eng.store_from_pool(T)
+    r_c = eng.bidirectional_prefill(toks, C, gbps_list[0], mode="compute_only")
     kernels = {k: {"avg_us": round(v["total_ns"] / v["launches"] / 1e3, 2),
                    "tflops": round(v["flops"] / v["total_ns"] / 1e3, 1) if v["flops"] else None}
                for k, v in stats.items() if v["launches"]}
