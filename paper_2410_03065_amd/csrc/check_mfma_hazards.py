@@ -76,15 +76,12 @@ def parse_kernel(lines):
     return ins, labels, branches
 
 
-def check_pairs(before, after, gap, problems, where):
-    """`before` instructions end `gap` wait states before `after` begins (gap = 0: contiguous)."""
-    if not before or not after:
-        return
-    end = before[-1][0] + 1
-    start = after[0][0]
+def check_pairs(before, after, shift, problems, where):
+    """Every instruction of `before` against every instruction of `after`; an instruction of `after` at time ta is
+    issued ta + shift - tb wait states after one of `before` at time tb (shift = 0 along straight-line code)."""
     for tb, kb, rb, wb, xb in before:
         for ta, ka, ra, wa, xa in after:
-            dist = (end - tb) + gap + (ta - start)          # wait states from issue of b to issue of a
+            dist = ta + shift - tb
             if kb == "mfma" and ka == "other" and dist < MFMA_TO_OTHER and wb & (ra | wa):
                 problems.append("%s: %d wait states between\n    %s\n    %s" % (where, dist, xb, xa))
             if kb == "other" and ka == "mfma" and dist < OTHER_TO_MFMA and wb & ra:
@@ -101,15 +98,17 @@ def check_kernel(name, lines):
         while j >= 0 and cur[0] - ins[j][0] <= WINDOW:
             prev.append(ins[j])
             j -= 1
-        check_pairs(prev[::-1], [cur], 0, problems, name)
-    # every branch: the instructions before it against the instructions after its target
+        check_pairs(prev, [cur], 0, problems, name)
+    # every branch: the instructions up to it against the instructions from its target on, as if the target followed
+    # the branch directly
     for pos, target in branches:
-        if target not in labels:
+        if target not in labels or labels[target] >= len(ins):
             continue
-        tail = [x for x in ins[max(0, pos - WINDOW):pos + 1] if ins[pos][0] - x[0] <= WINDOW]
-        head_start = labels[target]
-        head = [x for x in ins[head_start:head_start + WINDOW + 1] if x[0] - ins[head_start][0] <= WINDOW] if head_start < len(ins) else []
-        check_pairs(tail, head, 0, problems, "%s (branch to %s)" % (name, target))
+        t_branch = ins[pos][0]
+        tail = [x for x in ins[max(0, pos - WINDOW):pos + 1] if t_branch - x[0] <= WINDOW]
+        h0 = labels[target]
+        head = [x for x in ins[h0:h0 + WINDOW + 1] if x[0] - ins[h0][0] <= WINDOW]
+        check_pairs(tail, head, t_branch + 1 - ins[h0][0], problems, "%s (branch to %s)" % (name, target))
     n_mfma = sum(1 for x in ins if x[1] == "mfma")
     return n_mfma, problems
 
